@@ -1,0 +1,362 @@
+/*
+ * CPU oracle for the W6A16 linear layer of FP6-LLM (arXiv 2401.14112).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is the slow, plain definition that the HIP
+ * kernels are checked against.  Nothing in the product path may call it, and it
+ * shares no code, header, table or constant with the HIP sources.
+ *
+ * What is defined here, and where the paper defines it:
+ *   - the e3m2 value of a 6-bit code: Section 2.2, Eq. 1, with bias 3; the E=0
+ *     binade is read as IEEE-style subnormals because that is what the bit-copy
+ *     cast of Section 5.3, Eq. 3 (fp16 with E16 := Ex, times 2^(15-3)) yields;
+ *     E=7 is an ordinary binade (largest magnitude 28, no inf/NaN).
+ *   - the per-output-channel fp16 scale: Algorithm 1 (the "Scales" input) and
+ *     Section 3 (coarse-grained quantization); the quantizer itself is not in the
+ *     paper: round-to-nearest-even onto the e3m2 grid of W/scale with
+ *     scale = fp16(rowmax|W| / 28).
+ *   - the packed stream: Section 5.2 asks for an ahead-of-time re-layout so that
+ *     the kernel reads aligned words; the layout stated in fp6o_pos() is this
+ *     library's own (one 16-row x 256-k tile per 64-lane wave).
+ *   - the linear layer: Section 6, C = A x B with A = [M,K] weights, B = [K,N]
+ *     activations stored column-major (so X is [N][K]) and C column-major
+ *     (Y is [N][M]).
+ *
+ * Everything is written as plain loops in double precision.  OpenMP only splits
+ * independent output rows across host cores; it does not reorder any sum.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define FP6O_TILE_ROWS 16
+#define FP6O_TILE_K 256
+#define FP6O_TILE_BYTES 3072 /* 16 * 256 * 6 / 8 */
+
+/* ------------------------------------------------------------------ fp16 -- */
+
+/* IEEE binary16 bit pattern -> exact double. */
+double fp6o_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 31;
+    int f = h & 1023;
+    double mag;
+    if (e == 0)
+        mag = ldexp((double)f, -24); /* subnormal: 0.f * 2^-14 */
+    else if (e == 31)
+        mag = (f == 0) ? INFINITY : NAN;
+    else
+        mag = ldexp((double)(1024 + f), e - 25); /* 1.f * 2^(e-15) */
+    return sign ? -mag : mag;
+}
+
+/* double -> nearest binary16, ties to even, subnormals kept, sign of zero kept. */
+uint16_t fp6o_double_to_half(double x)
+{
+    uint16_t sign = signbit(x) ? 0x8000u : 0u;
+    double a = fabs(x);
+    if (isnan(a))
+        return (uint16_t)(sign | 0x7e00u);
+    if (a >= 65520.0) /* midpoint between 65504 and 2^16 rounds to even = inf */
+        return (uint16_t)(sign | 0x7c00u);
+    if (a < ldexp(1.0, -14)) {
+        /* grid spacing 2^-24; nearbyint() rounds to even in the default mode */
+        double r = nearbyint(ldexp(a, 24));
+        return (uint16_t)(sign | (uint16_t)r); /* r == 1024 is the first normal */
+    }
+    int ex;
+    (void)frexp(a, &ex); /* a = m * 2^ex, m in [0.5, 1) */
+    int e = ex - 1;      /* a in [2^e, 2^(e+1)) */
+    double r = nearbyint(ldexp(a, 10 - e)); /* in [1024, 2048] */
+    if (r == 2048.0) {
+        r = 1024.0;
+        e += 1;
+    }
+    return (uint16_t)(sign | (uint16_t)((e + 15) << 10) | (uint16_t)(r - 1024.0));
+}
+
+/* ---------------------------------------------------------------- decode -- */
+
+/* Value of code c = s e2 e1 e0 m1 m0 (Eq. 1, bias = 2^(3-1)-1 = 3). */
+double fp6o_decode(int code)
+{
+    int S = (code >> 5) & 1;
+    int E = (code >> 2) & 7;
+    int M = code & 3;
+    double mag;
+    if (E == 0)
+        mag = ldexp(M / 4.0, 1 - 3); /* 0.M * 2^(1-bias) */
+    else
+        mag = ldexp(1.0 + M / 4.0, E - 3); /* 1.M * 2^(E-bias) */
+    return S ? -mag : mag;
+}
+
+/* -------------------------------------------------------------- quantize -- */
+
+/* fp16 nearest to amax/28 (ties to even), decided with exact arithmetic:
+ * among the fp16 values around the quotient, the one minimising |28*h - amax|. */
+uint16_t fp6o_scale_for_amax(uint16_t amax_bits)
+{
+    double a = fp6o_half_to_double((uint16_t)(amax_bits & 0x7fffu));
+    uint16_t guess = fp6o_double_to_half(a / 28.0);
+    int lo = guess > 0 ? guess - 1 : 0;
+    int hi = guess + 1;
+    int best = -1;
+    double best_err = 0.0;
+    for (int h = lo; h <= hi; ++h) {
+        double err = fabs(28.0 * fp6o_half_to_double((uint16_t)h) - a); /* exact */
+        if (best < 0 || err < best_err || (err == best_err && (h & 1) == 0 && (best & 1) == 1)) {
+            best = h;
+            best_err = err;
+        }
+    }
+    return (uint16_t)best;
+}
+
+/* Code of one weight given the (already rounded) fp16 scale of its row:
+ * sign bit copied, magnitude = grid point nearest to |w|/scale, ties to the even
+ * code, anything beyond the grid saturates at 28.  |w| - decode(g)*scale is exact
+ * in double (both are multiples of 2^-28 below 2^21), so the argmin is exact. */
+int fp6o_quantize_one(uint16_t w_bits, uint16_t scale_bits)
+{
+    int sign = (w_bits >> 15) & 1;
+    double a = fp6o_half_to_double((uint16_t)(w_bits & 0x7fffu));
+    double s = fp6o_half_to_double((uint16_t)(scale_bits & 0x7fffu));
+    if (s == 0.0)
+        return sign << 5;
+    int best = 0;
+    double best_err = fabs(a - fp6o_decode(0) * s);
+    for (int g = 1; g < 32; ++g) {
+        double err = fabs(a - fp6o_decode(g) * s);
+        if (err < best_err || (err == best_err && (g & 1) == 0)) {
+            best = g;
+            best_err = err;
+        }
+    }
+    return (sign << 5) | best;
+}
+
+/* W fp16 [M][K] row-major -> codes [M][K] (one byte each) and scales fp16 [M].
+ * Returns 0, or 1 if W holds an inf/NaN (outside the method's domain). */
+int fp6o_quantize(const uint16_t *W, int64_t M, int64_t K, uint8_t *codes, uint16_t *scales)
+{
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        uint16_t amax = 0;
+        for (int64_t k = 0; k < K; ++k) {
+            uint16_t mag = (uint16_t)(W[m * K + k] & 0x7fffu);
+            if (mag >= 0x7c00u)
+                bad |= 1;
+            if (mag > amax) /* for finite non-negative fp16, bit order = value order */
+                amax = mag;
+        }
+        uint16_t sc = fp6o_scale_for_amax(amax);
+        scales[m] = sc;
+        for (int64_t k = 0; k < K; ++k)
+            codes[m * K + k] = (uint8_t)fp6o_quantize_one(W[m * K + k], sc);
+    }
+    return bad;
+}
+
+/* ---------------------------------------------------------------- layout -- */
+
+int64_t fp6o_packed_bytes(int64_t M, int64_t K) { return M * K * 6 / 8; }
+
+/*
+ * Bit address, in the packed stream, of bit b of the code of weight (m, k);
+ * b = 0..5 = m0, m1, e0, e1, e2, s.
+ *
+ * The matrix is cut into tiles of 16 rows x 256 columns, stored row-tile major
+ * (all k-tiles of rows 0..15, then of rows 16..31, ...), 3072 bytes each.  A tile
+ * is three planes of 1024 bytes; a plane is 64 slots of 16 bytes, slot
+ * = 16*q + r for row r of the tile and the q-th group of 8 columns inside each
+ * run of 32; a slot is four 32-bit words, word g serving column runs 2g and
+ * 2g+1 of the tile.  For the slot (r, q) and word index g, the three words
+ * D0, D1, D2 (one per plane) hold 16 codes:
+ *   run 2g,   columns j = 0..3 : byte j of D0,   as  s . . e2 e1 e0 m1 m0
+ *   run 2g,   columns j = 4..7 : byte j-4 of D1, same form
+ *   run 2g+1, columns j = 0..3 : byte j of D2,   same form
+ *   run 2g+1, columns j = 4..7 : spread over the two free bits (6 and 5) of
+ *             byte j-4 of the three words: D0 takes (m1, m0), D1 takes (e1, e0),
+ *             D2 takes (s, e2).
+ * Bytes are little-endian within a word, so byte i of a word sits at +i.
+ */
+uint64_t fp6o_pos(int64_t K, int64_t m, int64_t k, int b)
+{
+    int64_t row_tile = m / FP6O_TILE_ROWS;
+    int r = (int)(m % FP6O_TILE_ROWS);
+    int64_t k_tile = k / FP6O_TILE_K;
+    int kk = (int)(k % FP6O_TILE_K);
+    int run = kk / 32;      /* which run of 32 columns inside the tile */
+    int q = (kk % 32) / 8;  /* which group of 8 inside the run */
+    int j = kk % 8;         /* column inside the group */
+    int g = run / 2;
+    int odd_run = run % 2;
+    int slot = 16 * q + r;
+    int plane, byte, bit;
+    if (!odd_run) {
+        plane = j / 4;
+        byte = j % 4;
+        bit = (b == 5) ? 7 : b;
+    } else if (j < 4) {
+        plane = 2;
+        byte = j;
+        bit = (b == 5) ? 7 : b;
+    } else {
+        plane = b / 2; /* 0: (m1,m0)  1: (e1,e0)  2: (s,e2) */
+        byte = j - 4;
+        bit = 5 + (b % 2);
+    }
+    uint64_t tile = (uint64_t)(row_tile * (K / FP6O_TILE_K) + k_tile);
+    uint64_t byte_addr = tile * FP6O_TILE_BYTES + (uint64_t)plane * 1024u + (uint64_t)slot * 16u
+                         + (uint64_t)g * 4u + (uint64_t)byte;
+    return byte_addr * 8u + (uint64_t)bit;
+}
+
+/* codes [M][K] -> packed stream (every bit of the stream is written). */
+void fp6o_pack(const uint8_t *codes, int64_t M, int64_t K, uint8_t *packed)
+{
+    memset(packed, 0, (size_t)fp6o_packed_bytes(M, K));
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k)
+            for (int b = 0; b < 6; ++b)
+                if ((codes[m * K + k] >> b) & 1) {
+                    uint64_t p = fp6o_pos(K, m, k, b);
+                    packed[p >> 3] |= (uint8_t)(1u << (p & 7));
+                }
+}
+
+/* packed stream -> codes [M][K]. */
+void fp6o_unpack_codes(const uint8_t *packed, int64_t M, int64_t K, uint8_t *codes)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            int c = 0;
+            for (int b = 0; b < 6; ++b) {
+                uint64_t p = fp6o_pos(K, m, k, b);
+                c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
+            }
+            codes[m * K + k] = (uint8_t)c;
+        }
+}
+
+/* ------------------------------------------------------- the three calls -- */
+
+/* fp16 W [M][K] -> packed codes + fp16 scales. */
+int fp6o_quantize_pack(const uint16_t *W, int64_t M, int64_t K, uint8_t *packed, uint16_t *scales)
+{
+    uint8_t *codes = (uint8_t *)malloc((size_t)(M * K));
+    if (!codes)
+        return 2;
+    int bad = fp6o_quantize(W, M, K, codes, scales);
+    fp6o_pack(codes, M, K, packed);
+    free(codes);
+    return bad;
+}
+
+/* packed + scales -> fp16 [M][K]: nearest fp16 to decode(code)*scale.  The product
+ * has at most 3+11 significant bits, so it is exact in double and rounded once. */
+int fp6o_unpack(const uint8_t *packed, const uint16_t *scales, int64_t M, int64_t K, uint16_t *W)
+{
+    uint8_t *codes = (uint8_t *)malloc((size_t)(M * K));
+    if (!codes)
+        return 2;
+    fp6o_unpack_codes(packed, M, K, codes);
+    for (int64_t m = 0; m < M; ++m) {
+        double s = fp6o_half_to_double(scales[m]);
+        for (int64_t k = 0; k < K; ++k)
+            W[m * K + k] = fp6o_double_to_half(fp6o_decode(codes[m * K + k]) * s);
+    }
+    free(codes);
+    return 0;
+}
+
+/* Y[n][rows[i]] = scale * sum_k decode(code[row][k]) * X[n][k], k ascending, in
+ * double, for the listed rows (rows == NULL: all M rows, i = m).  codes is [M][K],
+ * X is fp16 [N][K], Y is double [N][nrows]. */
+void fp6o_linear_codes(const uint8_t *codes, const uint16_t *scales, const uint16_t *X, int64_t M,
+                       int64_t N, int64_t K, const int64_t *rows, int64_t nrows, double *Y)
+{
+    if (!rows)
+        nrows = M;
+    double *Xd = (double *)malloc((size_t)(N * K) * sizeof(double));
+    for (int64_t i = 0; i < N * K; ++i)
+        Xd[i] = fp6o_half_to_double(X[i]);
+    double table[64];
+    for (int c = 0; c < 64; ++c)
+        table[c] = fp6o_decode(c);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t m = rows ? rows[i] : i;
+        double s = fp6o_half_to_double(scales[m]);
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += table[codes[m * K + k]] * Xd[n * K + k];
+            Y[n * nrows + i] = s * acc;
+        }
+    }
+    free(Xd);
+}
+
+/* Same, starting from the packed stream (reads it through fp6o_pos). */
+int fp6o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X, int64_t M,
+                int64_t N, int64_t K, const int64_t *rows, int64_t nrows, double *Y)
+{
+    if (!rows)
+        nrows = M;
+    /* gather only the rows that are asked for */
+    uint8_t *codes = (uint8_t *)malloc((size_t)(nrows * K));
+    uint16_t *sc = (uint16_t *)malloc((size_t)nrows * sizeof(uint16_t));
+    if (!codes || !sc) {
+        free(codes);
+        free(sc);
+        return 2;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t m = rows ? rows[i] : i;
+        sc[i] = scales[m];
+        for (int64_t k = 0; k < K; ++k) {
+            int c = 0;
+            for (int b = 0; b < 6; ++b) {
+                uint64_t p = fp6o_pos(K, m, k, b);
+                c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
+            }
+            codes[i * K + k] = (uint8_t)c;
+        }
+    }
+    fp6o_linear_codes(codes, sc, X, nrows, N, K, NULL, nrows, Y);
+    free(codes);
+    free(sc);
+    return 0;
+}
+
+/* Plain fp16-weight linear layer in double, for the W16A16 comparison kernel:
+ * Y[n][m] = sum_k W[m][k] * X[n][k]. */
+void fp6o_linear_f16(const uint16_t *W, const uint16_t *X, int64_t M, int64_t N, int64_t K,
+                     const int64_t *rows, int64_t nrows, double *Y)
+{
+    if (!rows)
+        nrows = M;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t m = rows ? rows[i] : i;
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += fp6o_half_to_double(W[m * K + k]) * fp6o_half_to_double(X[n * K + k]);
+            Y[n * nrows + i] = acc;
+        }
+    }
+}
+
+#ifdef _OPENMP
+#include <omp.h>
+int fp6o_threads(void) { return omp_get_max_threads(); }
+#else
+int fp6o_threads(void) { return 1; }
+#endif

@@ -1,0 +1,111 @@
+"""Pins for the oracle's packed layout (CPU only): the bit map is a bijection with no padding,
+pack/unpack round-trips, and the word-level shift/mask reconstruction that the
+kernels use (restated here in numpy, from the layout's description) recovers the codes.
+"""
+import numpy as np
+
+import workloads
+
+
+def _all_pos(oracle, M, K):
+    out = np.empty((M, K, 6), dtype=np.int64)
+    for m in range(M):
+        for k in range(K):
+            for b in range(6):
+                out[m, k, b] = oracle.pos(K, m, k, b)
+    return out
+
+
+def test_pos_is_a_bijection_smallest_tile(oracle):
+    M, K = 16, 256
+    p = _all_pos(oracle, M, K).ravel()
+    assert p.min() == 0 and p.max() == 6 * M * K - 1
+    assert np.unique(p).size == 6 * M * K
+
+
+def test_pos_is_a_bijection_multi_tile(oracle):
+    M, K = 48, 768           # 3 row tiles x 3 k tiles
+    p = _all_pos(oracle, M, K).ravel()
+    assert p.min() == 0 and p.max() == 6 * M * K - 1
+    assert np.unique(p).size == 6 * M * K
+    # tiles are row-tile major and 3072 bytes each: weight (m, k) lives in tile (m//16)*(K//256) + k//256
+    for (m, k) in [(0, 0), (15, 255), (16, 0), (17, 300), (47, 767)]:
+        tile = (m // 16) * (K // 256) + k // 256
+        for b in range(6):
+            assert oracle.pos(K, m, k, b) // (3072 * 8) == tile
+
+
+def test_packed_size_and_no_padding(oracle):
+    for (M, K) in [(16, 256), (256, 512), (8192, 22016)]:
+        assert oracle.packed_bytes(M, K) == 3 * M * K // 4
+    ones = np.full((32, 512), 63, dtype=np.uint8)
+    assert np.all(oracle.pack(ones) == 0xFF)           # every bit of the stream belongs to a code
+    assert np.all(oracle.pack(np.zeros((32, 512), dtype=np.uint8)) == 0)
+
+
+def test_pack_unpack_round_trip(oracle):
+    for (M, K, seed) in [(16, 256, 0), (256, 512, 1), (80, 1280, 2)]:
+        codes = workloads.make_codes(M, K, seed).numpy()
+        packed = oracle.pack(codes)
+        assert packed.size == 3 * M * K // 4
+        assert np.array_equal(oracle.unpack_codes(packed, M, K), codes)
+    # single-bit probes: one code bit set -> exactly one stream bit set, at pos()
+    M, K = 32, 512
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        m, k, b = int(rng.integers(M)), int(rng.integers(K)), int(rng.integers(6))
+        codes = np.zeros((M, K), dtype=np.uint8)
+        codes[m, k] = 1 << b
+        packed = oracle.pack(codes)
+        bits = np.flatnonzero(np.unpackbits(packed, bitorder="little"))
+        assert bits.tolist() == [oracle.pos(K, m, k, b)]
+
+
+def _swar_unpack_tile_words(words):
+    """words: uint32 [3][64][4] of one tile (plane, slot, word).  Returns codes [16][256] rebuilt with
+    the register-level sequence the kernels use: three ANDs for the in-place bytes, and a
+    four-term shift/mask stitch of the free bits, written from the layout's description."""
+    D0, D1, D2 = (words[p].astype(np.uint32) for p in range(3))
+    B = [D0 & 0x9F9F9F9F, D1 & 0x9F9F9F9F, D2 & 0x9F9F9F9F,
+         ((D0 >> 5) & 0x03030303) | ((D1 >> 3) & 0x0C0C0C0C) | ((D2 << 1) & 0x80808080) | ((D2 >> 1) & 0x10101010)]
+    codes = np.zeros((16, 256), dtype=np.uint8)
+    for slot in range(64):
+        r, q = slot % 16, slot // 16
+        for g in range(4):
+            for t in range(4):                     # B[t]: run 2g (+1 for t >= 2), columns 4*(t%2) ..
+                run = 2 * g + t // 2
+                for byte in range(4):
+                    v = (int(B[t][slot, g]) >> (8 * byte)) & 0xFF
+                    assert v & 0x60 == 0
+                    code = ((v >> 7) << 5) | (v & 0x1F)
+                    codes[r, run * 32 + q * 8 + 4 * (t % 2) + byte] = code
+    return codes
+
+
+def test_register_level_reconstruction(oracle):
+    M, K = 32, 512
+    codes = workloads.make_codes(M, K, 7).numpy()
+    packed = oracle.pack(codes)
+    tiles = packed.view(np.uint32).reshape(M // 16, K // 256, 3, 64, 4)
+    for rt in range(M // 16):
+        for kt in range(K // 256):
+            got = _swar_unpack_tile_words(tiles[rt, kt])
+            assert np.array_equal(got, codes[rt * 16:(rt + 1) * 16, kt * 256:(kt + 1) * 256])
+
+
+def test_unpack_is_layout_independent(oracle):
+    """unpack(quantize_pack(W)) == decode(quantize(W)) * scale rounded once to fp16, computed
+    row-major with numpy without touching pos()."""
+    name, M, K = workloads.TINY
+    W = workloads.make_weights(M, K, seed=0).numpy()
+    codes, scales = oracle.quantize(W)
+    packed, scales2 = oracle.quantize_pack(W)
+    assert np.array_equal(scales.view(np.uint16), scales2.view(np.uint16))
+    table = oracle.decode_table()
+    want = (table[codes] * scales.astype(np.float64)[:, None]).astype(np.float16)   # exact product, one rounding
+    got = oracle.unpack(packed, scales2, M, K)
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+    # quantisation error is bounded by half a grid step of the top binade: |W - Wd| <= 2 * scale
+    # (plus the single fp16 rounding of the dequantised value)
+    gd = got.astype(np.float64)
+    assert np.all(np.abs(gd - W.astype(np.float64)) <= 2.0 * scales.astype(np.float64)[:, None] + 2.0 ** -11 * np.abs(gd))

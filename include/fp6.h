@@ -1,0 +1,136 @@
+/*
+ * fp6.h - C ABI of the MI355X (gfx950) W6A16 linear-layer library.
+ *
+ * The library implements the weight-only-quantized linear layer of FP6-LLM
+ * (arXiv 2401.14112): Y = dequant(W_fp6) * X with 6-bit e3m2 weights
+ * (Section 2.2, Eq. 1: 1 sign, 3 exponent, 2 mantissa bits, bias 3), one fp16
+ * scale per output channel (Algorithm 1's "Scales"; Section 3), fp16 activations,
+ * weights de-quantized in registers inside the GEMM kernel and never written back
+ * to memory (Section 4.1, the unified-kernel design).
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers (hipMalloc'ed or equivalent) and must
+ *     be 16-byte aligned.  The caller owns every buffer; the library allocates
+ *     and frees nothing and never synchronizes.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it; the calls are safe to record into a HIP graph.
+ *   - Matrices follow Section 6 of the paper: weights are A = [M][K] (M output
+ *     channels, K input features); activations B = [K][N] and outputs C = [M][N]
+ *     are column-major, i.e. X is stored [N][K] (K contiguous) and Y is stored
+ *     [N][M] (M contiguous) - the natural layout of a linear layer over N tokens.
+ *   - Supported shapes: M a multiple of 16, K a multiple of 256, N >= 1.
+ *   - Errors are detected on the host before anything is launched and reported
+ *     as a status code; nothing is enqueued when a call fails.
+ *   - W must be finite (the method has no inf/NaN code); this is not checked.
+ */
+#ifndef FP6_MI355X_H
+#define FP6_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FP6_OK = 0,
+    FP6_ERR_NULL = 1,      /* a required pointer is NULL */
+    FP6_ERR_SHAPE = 2,     /* M, N, K not positive, or M % 16 != 0, or K % 256 != 0 */
+    FP6_ERR_WORKSPACE = 3, /* workspace missing or smaller than fp6_linear_workspace_bytes() */
+    FP6_ERR_ALIGN = 4,     /* a pointer is not 16-byte aligned */
+    FP6_ERR_HIP = 5        /* the HIP runtime refused the launch */
+} fp6_status;
+
+/* Human-readable name of a status code (static string). */
+const char *fp6_status_str(int status);
+
+/* Version of the packed weight layout written by fp6_quantize_pack and read by
+ * fp6_unpack / fp6_linear.  Store it next to any packed buffer that is saved. */
+int fp6_layout_version(void);
+
+/* Bytes of the packed code stream of an M x K matrix: 6 bits per weight, no
+ * padding (Section 5.2: 32 x-bit weights occupy x 32-bit words) = 3*M*K/4.
+ * Returns 0 for an unsupported shape. */
+size_t fp6_packed_bytes(int64_t M, int64_t K);
+
+/*
+ * Ahead-of-time weight preparation (Section 5.2, "Ahead-of-time Bit-level
+ * Pre-packing"; the quantizer itself is outside the paper and follows the
+ * benchmark recipe): for every row m
+ *     scale[m] = fp16_rne(max_k |W[m][k]| / 28)
+ *     code     = sign bit of W | nearest e3m2 magnitude of |W[m][k]| / scale[m],
+ *                ties to the even code, saturating at 28
+ * (a row whose scale rounds to 0 gets sign-only codes), and the 6-bit codes are
+ * written in the library's gfx950 tile order so that the GEMM reads them as
+ * contiguous 16-byte-per-lane loads.
+ *   W_f16   in   device, fp16 row-major [M][K]
+ *   packed  out  device, fp6_packed_bytes(M, K) bytes, every bit written
+ *   scales  out  device, fp16 [M]
+ */
+fp6_status fp6_quantize_pack(const void *W_f16, int64_t M, int64_t K, void *packed, void *scales_f16,
+                             void *stream);
+
+/*
+ * De-quantize a packed matrix back to fp16 (the first half of the "dual-kernel"
+ * scheme of Section 4.1; a test aid, not the production path):
+ *     W_out[m][k] = fp16_rne(e3m2_value(code[m][k]) * scale[m])      (one rounding)
+ *   packed  in   device, fp6_packed_bytes(M, K) bytes
+ *   scales  in   device, fp16 [M]
+ *   W_out   out  device, fp16 row-major [M][K]
+ */
+fp6_status fp6_unpack(const void *packed, const void *scales_f16, int64_t M, int64_t K, void *W_f16_out,
+                      void *stream);
+
+/*
+ * Workspace needed by fp6_linear / fp16_linear for this shape (0 when the
+ * kernel chosen for it needs none).  The workspace holds split-K partial sums and
+ * arrival counters.  It MUST be zero-filled once before its first use
+ * (fp6_workspace_init or any device memset); the kernels leave the counters at
+ * zero, so it can be reused by later calls without clearing it again.  Two calls
+ * that may run concurrently (different streams) need different workspaces.
+ */
+size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t fp16_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/* Zero-fill a workspace with a kernel on `stream` (graph-capturable). */
+fp6_status fp6_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The W6A16 linear layer (Section 6: C = A x B; Sections 4.1, 5.3, 5.4: weights
+ * are fetched in packed form, de-quantized to fp16 in registers and fed to the
+ * matrix cores in one kernel):
+ *     Y[n][m] = fp16_rne( scale[m] * sum_k e3m2_value(code[m][k]) * X[n][k] )
+ * accumulated in fp32; the per-row scale is applied once after accumulation.
+ *   packed     in   device, written by fp6_quantize_pack for the same (M, K)
+ *   scales     in   device, fp16 [M]
+ *   X_f16      in   device, fp16 [N][K]
+ *   Y_f16      out  device, fp16 [N][M]
+ *   workspace  in/out  device, >= fp6_linear_workspace_bytes(M, N, K) bytes, may
+ *              be NULL when that is 0
+ * Results are deterministic: the same inputs give the same bits on every call.
+ */
+fp6_status fp6_linear(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                      int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The library's own W16A16 linear layer, Y[n][m] = fp16_rne(sum_k W[m][k] X[n][k]),
+ * built on the same kernel skeleton; it is the in-library baseline that the paper's
+ * comparison against an fp16 GEMM (Section 7.1) is re-run against.
+ *   W_f16 in device fp16 row-major [M][K]; X, Y, workspace as for fp6_linear
+ *   (size from fp16_linear_workspace_bytes).
+ */
+fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N, int64_t K,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Tuning hook for benchmarks: force the split-K factor used by fp6_linear and
+ * fp16_linear (0 = choose automatically, the default).  Process-wide; affects the
+ * workspace size queries as well.  Values the shape cannot honour are clamped.
+ */
+void fp6_tuning_set_split_k(int split_k);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FP6_MI355X_H */

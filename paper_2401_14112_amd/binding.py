@@ -1,0 +1,202 @@
+"""ctypes binding of libfp6_mi355x.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/fp6.h).  Tensors
+are torch CUDA tensors; outputs and workspaces are allocated here with torch when the
+caller does not pass them.  There is no CPU fallback: if the library is missing and
+cannot be built, or a tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+from typing import Optional, Tuple
+
+import torch
+
+from . import build as _build
+
+_lib = None
+
+
+class Fp6Error(RuntimeError):
+    pass
+
+
+def library_path() -> Path:
+    return _build.LIB
+
+
+def load_library():
+    """Load the built library; build it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _build.LIB.exists():
+        _build.build_library()
+    L = ctypes.CDLL(str(_build.LIB))
+    i64, vp, sz, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    L.fp6_status_str.restype = ctypes.c_char_p
+    L.fp6_status_str.argtypes = [ci]
+    L.fp6_layout_version.restype = ci
+    L.fp6_layout_version.argtypes = []
+    L.fp6_packed_bytes.restype = sz
+    L.fp6_packed_bytes.argtypes = [i64, i64]
+    L.fp6_linear_workspace_bytes.restype = sz
+    L.fp6_linear_workspace_bytes.argtypes = [i64, i64, i64]
+    L.fp16_linear_workspace_bytes.restype = sz
+    L.fp16_linear_workspace_bytes.argtypes = [i64, i64, i64]
+    L.fp6_workspace_init.restype = ci
+    L.fp6_workspace_init.argtypes = [vp, sz, vp]
+    L.fp6_quantize_pack.restype = ci
+    L.fp6_quantize_pack.argtypes = [vp, i64, i64, vp, vp, vp]
+    L.fp6_unpack.restype = ci
+    L.fp6_unpack.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.fp6_linear.restype = ci
+    L.fp6_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
+    L.fp16_linear.restype = ci
+    L.fp16_linear.argtypes = [vp, vp, vp, i64, i64, i64, vp, sz, vp]
+    L.fp6_tuning_set_split_k.restype = None
+    L.fp6_tuning_set_split_k.argtypes = [ci]
+    _lib = L
+    return L
+
+
+def _check(status: int):
+    if status != 0:
+        raise Fp6Error(load_library().fp6_status_str(status).decode())
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise Fp6Error("%s must be a CUDA tensor (there is no CPU path)" % name)
+    if t.dtype != dtype:
+        raise Fp6Error("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise Fp6Error("%s must be contiguous" % name)
+    return t
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def fp6_layout_version() -> int:
+    return int(load_library().fp6_layout_version())
+
+
+def fp6_packed_bytes(M: int, K: int) -> int:
+    return int(load_library().fp6_packed_bytes(M, K))
+
+
+def fp6_linear_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load_library().fp6_linear_workspace_bytes(M, N, K))
+
+
+def fp16_linear_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load_library().fp16_linear_workspace_bytes(M, N, K))
+
+
+def fp6_tuning_set_split_k(split_k: int) -> None:
+    load_library().fp6_tuning_set_split_k(int(split_k))
+
+
+def fp6_workspace_init(workspace: torch.Tensor) -> None:
+    _dev(workspace, torch.uint8, "workspace")
+    _check(load_library().fp6_workspace_init(workspace.data_ptr(), workspace.numel(), _stream()))
+
+
+def _new_workspace(nbytes: int, device) -> Optional[torch.Tensor]:
+    if nbytes == 0:
+        return None
+    return torch.zeros(nbytes, dtype=torch.uint8, device=device)
+
+
+def fp6_quantize_pack(W: torch.Tensor, packed: Optional[torch.Tensor] = None,
+                      scales: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """fp16 [M][K] -> (packed uint8 [3MK/4], scales fp16 [M])."""
+    L = load_library()
+    _dev(W, torch.float16, "W")
+    if W.dim() != 2:
+        raise Fp6Error("W must be [M][K]")
+    M, K = W.shape
+    nbytes = L.fp6_packed_bytes(M, K)
+    if nbytes == 0:
+        _check(2)
+    if packed is None:
+        packed = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
+    if scales is None:
+        scales = torch.empty(M, dtype=torch.float16, device=W.device)
+    _dev(packed, torch.uint8, "packed")
+    _dev(scales, torch.float16, "scales")
+    if packed.numel() != nbytes or scales.numel() != M:
+        raise Fp6Error("packed/scales have the wrong size")
+    _check(L.fp6_quantize_pack(W.data_ptr(), M, K, packed.data_ptr(), scales.data_ptr(), _stream()))
+    return packed, scales
+
+
+def fp6_unpack(packed: torch.Tensor, scales: torch.Tensor, M: int, K: int,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """packed + scales -> fp16 [M][K]."""
+    L = load_library()
+    _dev(packed, torch.uint8, "packed")
+    _dev(scales, torch.float16, "scales")
+    if L.fp6_packed_bytes(M, K) == 0:
+        _check(2)
+    if packed.numel() != L.fp6_packed_bytes(M, K) or scales.numel() != M:
+        raise Fp6Error("packed/scales do not match M, K")
+    if out is None:
+        out = torch.empty((M, K), dtype=torch.float16, device=packed.device)
+    _dev(out, torch.float16, "out")
+    if out.numel() != M * K:
+        raise Fp6Error("out has the wrong size")
+    _check(L.fp6_unpack(packed.data_ptr(), scales.data_ptr(), M, K, out.data_ptr(), _stream()))
+    return out
+
+
+def fp6_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
+               out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y[N][M] = X[N][K] @ dequant(packed, scales)[M][K]^T  (fp16 in, fp16 out)."""
+    L = load_library()
+    _dev(packed, torch.uint8, "packed")
+    _dev(scales, torch.float16, "scales")
+    _dev(X, torch.float16, "X")
+    if X.dim() != 2 or X.shape[1] != K:
+        raise Fp6Error("X must be [N][K]")
+    N = X.shape[0]
+    if L.fp6_packed_bytes(M, K) == 0 or N == 0:
+        _check(2)
+    if packed.numel() != L.fp6_packed_bytes(M, K) or scales.numel() != M:
+        raise Fp6Error("packed/scales do not match M, K")
+    if out is None:
+        out = torch.empty((N, M), dtype=torch.float16, device=X.device)
+    _dev(out, torch.float16, "out")
+    if out.numel() != N * M:
+        raise Fp6Error("out has the wrong size")
+    if workspace is None:
+        workspace = _new_workspace(L.fp6_linear_workspace_bytes(M, N, K), X.device)
+    ws_ptr, ws_len = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
+    _check(L.fp6_linear(packed.data_ptr(), scales.data_ptr(), X.data_ptr(), out.data_ptr(), M, N, K,
+                        ws_ptr, ws_len, _stream()))
+    return out
+
+
+def fp16_linear(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] = None,
+                workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y[N][M] = X[N][K] @ W[M][K]^T with the library's own fp16-weight kernel."""
+    L = load_library()
+    _dev(W, torch.float16, "W")
+    _dev(X, torch.float16, "X")
+    if W.dim() != 2 or X.dim() != 2 or X.shape[1] != W.shape[1]:
+        raise Fp6Error("W must be [M][K] and X [N][K]")
+    M, K = W.shape
+    N = X.shape[0]
+    if L.fp6_packed_bytes(M, K) == 0 or N == 0:
+        _check(2)
+    if out is None:
+        out = torch.empty((N, M), dtype=torch.float16, device=X.device)
+    _dev(out, torch.float16, "out")
+    if workspace is None:
+        workspace = _new_workspace(L.fp16_linear_workspace_bytes(M, N, K), X.device)
+    ws_ptr, ws_len = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
+    _check(L.fp16_linear(W.data_ptr(), X.data_ptr(), out.data_ptr(), M, N, K, ws_ptr, ws_len, _stream()))
+    return out

@@ -1,0 +1,193 @@
+// C ABI of the library (see include/fp6.h): argument checks on the host, kernel
+// selection, launches on the caller's stream.  No allocation, no synchronization.
+#include "../../include/fp6.h"
+
+#include <atomic>
+
+#include "fp6_device.hpp"
+#include "linear_stream.hpp"
+#include "pack_unpack.hpp"
+
+namespace {
+
+using namespace fp6;
+
+constexpr int kLayoutVersion = 1;
+constexpr int kStreamWaves = 4;   // waves per block of the streaming kernel
+constexpr int kStreamDepth = 2;   // weight tiles in flight per wave
+constexpr int kTargetWaves = 256 * 16;  // 256 CUs x 16 resident waves
+
+std::atomic<int> g_forced_split{0};
+
+bool shape_ok(int64_t M, int64_t K) { return M > 0 && K > 0 && M % kTileRows == 0 && K % kTileK == 0 && M < (1ll << 31) && K < (1ll << 31); }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct StreamPlan {
+    int nt;          // 16-token tiles handled per launch (1 or 2)
+    int split;       // split-K factor
+    int row_blocks;  // blocks along M
+    size_t counter_bytes;
+    size_t partial_bytes;
+    size_t total_bytes() const { return split > 1 ? counter_bytes + partial_bytes : 0; }
+};
+
+StreamPlan plan_stream(int64_t M, int64_t N, int64_t K)
+{
+    StreamPlan p;
+    const int64_t row_tiles = M / kTileRows;
+    const int64_t KT = K / kTileK;
+    p.nt = N <= 16 ? 1 : 2;
+    int64_t s = g_forced_split.load(std::memory_order_relaxed);
+    if (s <= 0)
+        s = (kTargetWaves + row_tiles - 1) / row_tiles;
+    const int64_t max_split = KT >= 4 ? KT / 2 : 1;  // at least two k-tiles per slice
+    if (s > max_split)
+        s = max_split;
+    if (s > 64)
+        s = 64;
+    if (s < 1)
+        s = 1;
+    p.split = (int)s;
+    p.row_blocks = (int)((row_tiles + kStreamWaves - 1) / kStreamWaves);
+    p.counter_bytes = (((size_t)p.row_blocks * sizeof(int)) + 255) / 256 * 256;
+    p.partial_bytes = (size_t)p.split * (size_t)row_tiles * (size_t)p.nt * 64 * sizeof(float4_t);
+    return p;
+}
+
+template <class Src>
+fp6_status launch_stream(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
+                         int64_t K, void *workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    const StreamPlan p = plan_stream(M, N, K);
+    if (p.total_bytes() > 0) {
+        if (!workspace || workspace_bytes < p.total_bytes())
+            return FP6_ERR_WORKSPACE;
+        if (!aligned16(workspace))
+            return FP6_ERR_ALIGN;
+    }
+    int *counters = static_cast<int *>(workspace);
+    float4_t *partials =
+        p.total_bytes() ? reinterpret_cast<float4_t *>(static_cast<uint8_t *>(workspace) + p.counter_bytes) : nullptr;
+    const dim3 grid((unsigned)(p.row_blocks * p.split)), block(kStreamWaves * 64);
+    // tokens are processed 32 (or 16) at a time; each pass re-streams the weights
+    const int64_t step = 16 * p.nt;
+    for (int64_t n0 = 0; n0 < N; n0 += step) {
+        const int64_t n = (N - n0 < step) ? (N - n0) : step;
+        const half_t *Xp = static_cast<const half_t *>(X) + n0 * K;
+        half_t *Yp = static_cast<half_t *>(Y) + n0 * M;
+        if (p.nt == 1)
+            hipLaunchKernelGGL((linear_stream_kernel<Src, 1, kStreamWaves, kStreamDepth>), grid, block, 0, stream,
+                               weights, static_cast<const half_t *>(scales), Xp, Yp, (int)M, (int)n, (int)K, p.split,
+                               partials, counters);
+        else
+            hipLaunchKernelGGL((linear_stream_kernel<Src, 2, kStreamWaves, kStreamDepth>), grid, block, 0, stream,
+                               weights, static_cast<const half_t *>(scales), Xp, Yp, (int)M, (int)n, (int)K, p.split,
+                               partials, counters);
+        if (hipGetLastError() != hipSuccess)
+            return FP6_ERR_HIP;
+    }
+    return FP6_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *fp6_status_str(int status)
+{
+    switch (status) {
+    case FP6_OK: return "FP6_OK";
+    case FP6_ERR_NULL: return "FP6_ERR_NULL: a required pointer is NULL";
+    case FP6_ERR_SHAPE: return "FP6_ERR_SHAPE: need M % 16 == 0, K % 256 == 0, M, N, K > 0";
+    case FP6_ERR_WORKSPACE: return "FP6_ERR_WORKSPACE: workspace missing or too small";
+    case FP6_ERR_ALIGN: return "FP6_ERR_ALIGN: pointers must be 16-byte aligned";
+    case FP6_ERR_HIP: return "FP6_ERR_HIP: kernel launch failed";
+    default: return "unknown fp6 status";
+    }
+}
+
+int fp6_layout_version(void) { return kLayoutVersion; }
+
+size_t fp6_packed_bytes(int64_t M, int64_t K) { return shape_ok(M, K) ? (size_t)(M * K / 4 * 3) : 0; }
+
+size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (!shape_ok(M, K) || N <= 0)
+        return 0;
+    return plan_stream(M, N, K).total_bytes();
+}
+
+size_t fp16_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) { return fp6_linear_workspace_bytes(M, N, K); }
+
+void fp6_tuning_set_split_k(int split_k) { g_forced_split.store(split_k < 0 ? 0 : split_k); }
+
+fp6_status fp6_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (workspace_bytes == 0)
+        return FP6_OK;
+    if (!workspace)
+        return FP6_ERR_NULL;
+    if (!aligned16(workspace) || workspace_bytes % 16)
+        return FP6_ERR_ALIGN;
+    const size_t n16 = workspace_bytes / 16;
+    hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<u32x4 *>(workspace), n16);
+    return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+}
+
+fp6_status fp6_quantize_pack(const void *W_f16, int64_t M, int64_t K, void *packed, void *scales_f16, void *stream)
+{
+    if (!W_f16 || !packed || !scales_f16)
+        return FP6_ERR_NULL;
+    if (!shape_ok(M, K))
+        return FP6_ERR_SHAPE;
+    if (!aligned16(W_f16) || !aligned16(packed) || !aligned16(scales_f16))
+        return FP6_ERR_ALIGN;
+    hipLaunchKernelGGL(quantize_pack_kernel, dim3((unsigned)(M / kTileRows)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const half_t *>(W_f16), (int)M, (int)K,
+                       static_cast<uint8_t *>(packed), static_cast<half_t *>(scales_f16));
+    return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+}
+
+fp6_status fp6_unpack(const void *packed, const void *scales_f16, int64_t M, int64_t K, void *W_f16_out, void *stream)
+{
+    if (!packed || !scales_f16 || !W_f16_out)
+        return FP6_ERR_NULL;
+    if (!shape_ok(M, K))
+        return FP6_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(W_f16_out))
+        return FP6_ERR_ALIGN;
+    const int64_t tiles = (M / kTileRows) * (K / kTileK);
+    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((tiles + 3) / 4)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint8_t *>(packed),
+                       static_cast<const half_t *>(scales_f16), (int)M, (int)K, static_cast<half_t *>(W_f16_out));
+    return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+}
+
+fp6_status fp6_linear(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N,
+                      int64_t K, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!packed || !scales_f16 || !X_f16 || !Y_f16)
+        return FP6_ERR_NULL;
+    if (!shape_ok(M, K) || N <= 0 || N >= (1ll << 31))
+        return FP6_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(X_f16) || !aligned16(Y_f16))
+        return FP6_ERR_ALIGN;
+    return launch_stream<PackedFp6Source>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
+                                          static_cast<hipStream_t>(stream));
+}
+
+fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N, int64_t K,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!W_f16 || !X_f16 || !Y_f16)
+        return FP6_ERR_NULL;
+    if (!shape_ok(M, K) || N <= 0 || N >= (1ll << 31))
+        return FP6_ERR_SHAPE;
+    if (!aligned16(W_f16) || !aligned16(X_f16) || !aligned16(Y_f16))
+        return FP6_ERR_ALIGN;
+    return launch_stream<PlainFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
+                                          static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,141 @@
+// Device-side building blocks shared by the gfx950 kernels: the packed tile layout,
+// the register-level e3m2 -> fp16 unpack, and the two weight sources (packed 6-bit
+// and plain fp16) that the linear-layer kernels are instantiated with.
+//
+// Packed layout (this library's own; the paper's Section 5.2 only asks that the
+// weights be reordered ahead of time so that each thread reads whole aligned words
+// in the order the matrix cores consume them):
+//   * the M x K code matrix is cut into tiles of 16 rows x 256 columns, 3072 bytes
+//     each, stored row-tile major, so one wave streams a contiguous range;
+//   * a tile is three planes of 1024 bytes; lane L of a 64-wide wave owns bytes
+//     [16L, 16L+16) of each plane = three 128-bit loads, each a contiguous 1 KB per
+//     wave;
+//   * lane L = 16*q + r holds row r of the tile and, of every run of 32 columns,
+//     columns 8q..8q+7 - exactly the A operand of v_mfma_f32_16x16x32_f16;
+//   * word g (0..3) of the lane's three pieces, D0/D1/D2, holds the 16 codes of
+//     runs 2g and 2g+1: twelve sit in place as bytes "s..EEEMM" (bits 6,5 free), the
+//     other four are spread over those free bits.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fp6 {
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kTileRows = 16;
+constexpr int kTileK = 256;
+constexpr int kTileBytes = 3072;
+constexpr int kRunsPerTile = 8;  // runs of 32 columns = MFMA k-steps per tile
+
+template <class To, class From>
+__device__ __forceinline__ To bit_cast(const From &v)
+{
+    return __builtin_bit_cast(To, v);
+}
+
+// Two fp16 bit patterns "s00EEEMM 00000000" -> values times 2^12 (Section 5.3, Eq. 3:
+// the exponent field was copied without re-biasing, so the value is off by
+// 2^(15-3); one packed multiply fixes both halves, subnormals included).
+__device__ __forceinline__ uint32_t rebias_pair(uint32_t pair)
+{
+    half2_t h = bit_cast<half2_t>(pair) * (half2_t){(half_t)4096.0f, (half_t)4096.0f};
+    return bit_cast<uint32_t>(h);
+}
+
+// Four clean bytes "s00EEEMM" -> four fp16 values (two registers), columns in byte order.
+__device__ __forceinline__ void bytes_to_halves(uint32_t b, uint32_t &lo, uint32_t &hi)
+{
+    lo = rebias_pair(__builtin_amdgcn_perm(0u, b, 0x010c000cu));  // [b1 0 b0 0]
+    hi = rebias_pair(__builtin_amdgcn_perm(0u, b, 0x030c020cu));  // [b3 0 b2 0]
+}
+
+// The 16 codes of word g of a lane -> the A fragments of runs 2g (even) and 2g+1 (odd).
+// Shift/mask only (cf. Section 5.3, "Parallel De-quantization", 4 codes per 32-bit op).
+__device__ __forceinline__ void unpack_words(uint32_t d0, uint32_t d1, uint32_t d2, half8_t &even_run,
+                                             half8_t &odd_run)
+{
+    const uint32_t b0 = d0 & 0x9f9f9f9fu;
+    const uint32_t b1 = d1 & 0x9f9f9f9fu;
+    const uint32_t b2 = d2 & 0x9f9f9f9fu;
+    // stitch the four spread codes from the free bits 6,5 of every byte
+    uint32_t b3 = (d0 >> 5) & 0x03030303u;            // m1 m0
+    b3 = ((d1 >> 3) & 0x0c0c0c0cu) | b3;              // e1 e0
+    b3 = ((d2 << 1) & 0x80808080u) | b3;              // s
+    b3 = ((d2 >> 1) & 0x10101010u) | b3;              // e2
+    u32x4 e, o;
+    uint32_t lo, hi;
+    bytes_to_halves(b0, lo, hi); e[0] = lo; e[1] = hi;
+    bytes_to_halves(b1, lo, hi); e[2] = lo; e[3] = hi;
+    bytes_to_halves(b2, lo, hi); o[0] = lo; o[1] = hi;
+    bytes_to_halves(b3, lo, hi); o[2] = lo; o[3] = hi;
+    even_run = bit_cast<half8_t>(e);
+    odd_run = bit_cast<half8_t>(o);
+}
+
+// ---- weight sources -------------------------------------------------------
+// A source knows how one lane fetches its share of a 16 x 256 weight tile and how
+// to turn it into the eight A fragments (one per run) of the tile.  k_offset(f, q)
+// is the column, inside the tile, of the first of the 8 consecutive columns that
+// lane group q feeds to MFMA step f; the activation staging uses the same map.
+
+struct PackedFp6Source {
+    struct Tile {
+        u32x4 p0, p1, p2;
+    };
+    static constexpr bool kHasScale = true;
+    __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
+    // base: packed stream; row_tile/k_tile: tile coordinates; KT = K/256
+    __device__ static __forceinline__ Tile load(const void *base, int64_t row_tile, int64_t k_tile, int64_t KT,
+                                                int64_t /*K*/, int lane)
+    {
+        const u32x4 *p =
+            reinterpret_cast<const u32x4 *>(static_cast<const uint8_t *>(base) + (row_tile * KT + k_tile) * kTileBytes)
+            + lane;
+        Tile t;
+        t.p0 = __builtin_nontemporal_load(p);
+        t.p1 = __builtin_nontemporal_load(p + 64);
+        t.p2 = __builtin_nontemporal_load(p + 128);
+        return t;
+    }
+    template <int G>
+    __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
+    {
+        unpack_words(t.p0[G], t.p1[G], t.p2[G], even_run, odd_run);
+    }
+};
+
+struct PlainFp16Source {
+    struct Tile {
+        u32x4 v[8];
+    };
+    static constexpr bool kHasScale = false;
+    // lane group q owns 64 consecutive columns of the tile (128 contiguous bytes per lane)
+    __device__ static __forceinline__ int k_offset(int f, int q) { return q * 64 + f * 8; }
+    __device__ static __forceinline__ Tile load(const void *base, int64_t row_tile, int64_t k_tile, int64_t /*KT*/,
+                                                int64_t K, int lane)
+    {
+        const int r = lane & 15, q = lane >> 4;
+        const u32x4 *p = reinterpret_cast<const u32x4 *>(static_cast<const half_t *>(base)
+                                                         + (row_tile * kTileRows + r) * K + k_tile * kTileK + q * 64);
+        Tile t;
+#pragma unroll
+        for (int f = 0; f < 8; ++f)
+            t.v[f] = __builtin_nontemporal_load(p + f);
+        return t;
+    }
+    template <int G>
+    __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
+    {
+        even_run = bit_cast<half8_t>(t.v[2 * G]);
+        odd_run = bit_cast<half8_t>(t.v[2 * G + 1]);
+    }
+};
+
+}  // namespace fp6

@@ -1,0 +1,155 @@
+// fp6_quantize_pack and fp6_unpack kernels for gfx950.
+//
+// quantize_pack: one block per 16-row tile.  Pass 1 finds the row maxima and the
+// fp16 scales; pass 2 re-reads the rows, rounds every weight to its e3m2 code and
+// writes whole tiles of the packed stream with one 16-byte store per lane per plane
+// (the ahead-of-time re-layout of the paper's Section 5.2, in this library's order).
+//
+// unpack: one wave per tile; the same register-level decode as the GEMM, followed by
+// the row scale and a single rounding to fp16.
+#pragma once
+#include "fp6_device.hpp"
+
+namespace fp6 {
+
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+
+// Magnitude code (0..31) of ratio = |w| / scale on the e3m2 grid, round to nearest,
+// ties to the even code, saturating at 28.  The ratio is the correctly rounded fp32
+// quotient of two 11-bit significands; it can only land on a grid midpoint when the
+// exact quotient is that midpoint, so rounding it equals rounding the exact ratio.
+__device__ __forceinline__ uint32_t e3m2_magnitude_code(float ratio)
+{
+    uint32_t g;
+    if (ratio < 0.25f) {
+        g = (uint32_t)__builtin_rintf(ratio * 16.0f);  // subnormal binade: multiples of 1/16
+    } else {
+        uint32_t u = bit_cast<uint32_t>(ratio);
+        u += 0x000fffffu + ((u >> 21) & 1u);  // round the mantissa to 2 bits, half to even
+        g = (u >> 21) - (124u << 2);          // exponent field - 127 + bias 3, then 2 mantissa bits
+    }
+    return g < 31u ? g : 31u;
+}
+
+__device__ __forceinline__ uint32_t quantize_code(uint32_t w_bits, float scale)
+{
+    const uint32_t sign = (w_bits >> 15) & 1u;
+    if (scale == 0.0f)
+        return sign << 5;
+    const float a = (float)bit_cast<half_t>((uint16_t)(w_bits & 0x7fffu));
+    return (sign << 5) | e3m2_magnitude_code(a / scale);
+}
+
+// code s e2 e1 e0 m1 m0 -> byte  s 0 0 e2 e1 e0 m1 m0
+__device__ __forceinline__ uint32_t code_to_byte(uint32_t c) { return ((c & 0x20u) << 2) | (c & 0x1fu); }
+
+__global__ __launch_bounds__(256) void quantize_pack_kernel(const half_t *__restrict__ W, int M, int K,
+                                                            uint8_t *__restrict__ packed,
+                                                            half_t *__restrict__ scales)
+{
+    __shared__ float s_scale[kTileRows];
+    const int tid = threadIdx.x;
+    const int row_tile = blockIdx.x;
+    const int KT = K / kTileK;
+
+    // ---- pass 1: 16 threads per row, 16 bytes per thread per step
+    {
+        const int r = tid >> 4, c = tid & 15;
+        const u32x4 *row = reinterpret_cast<const u32x4 *>(W + ((int64_t)row_tile * kTileRows + r) * K);
+        ushort2_t mx = {0, 0};
+        for (int i = c; i < K / 8; i += 16) {
+            const u32x4 v = row[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                mx = __builtin_elementwise_max(mx, bit_cast<ushort2_t>(v[j] & 0x7fff7fffu));
+        }
+        uint32_t amax = mx[0] > mx[1] ? mx[0] : mx[1];  // finite fp16 magnitudes order like integers
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) {
+            const uint32_t other = __shfl_xor(amax, off, 16);
+            amax = other > amax ? other : amax;
+        }
+        if (c == 0) {
+            const float a = (float)bit_cast<half_t>((uint16_t)amax);
+            const half_t sc = (half_t)(a / 28.0f);  // fp32 quotient, then one rounding to fp16
+            scales[row_tile * kTileRows + r] = sc;
+            s_scale[r] = (float)sc;
+        }
+    }
+    __syncthreads();
+
+    // ---- pass 2: one wave per k-tile; lane (r, q) builds its 48 bytes of the tile
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, q = lane >> 4;
+    const float scale = s_scale[r];
+    const half_t *row = W + ((int64_t)row_tile * kTileRows + r) * K + q * 8;
+    for (int kt = wave; kt < KT; kt += 4) {
+        uint32_t code[8][8];
+#pragma unroll
+        for (int f = 0; f < 8; ++f) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(row + (int64_t)kt * kTileK + f * 32);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                code[f][2 * j] = quantize_code(v[j] & 0xffffu, scale);
+                code[f][2 * j + 1] = quantize_code(v[j] >> 16, scale);
+            }
+        }
+        u32x4 p0, p1, p2;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint32_t d0 = 0, d1 = 0, d2 = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t spread = code[2 * g + 1][4 + i];
+                d0 |= (code_to_byte(code[2 * g][i]) | ((spread & 3u) << 5)) << (8 * i);
+                d1 |= (code_to_byte(code[2 * g][4 + i]) | (((spread >> 2) & 3u) << 5)) << (8 * i);
+                d2 |= (code_to_byte(code[2 * g + 1][i]) | (((spread >> 4) & 3u) << 5)) << (8 * i);
+            }
+            p0[g] = d0;
+            p1[g] = d1;
+            p2[g] = d2;
+        }
+        u32x4 *tile = reinterpret_cast<u32x4 *>(packed + ((int64_t)row_tile * KT + kt) * kTileBytes) + lane;
+        tile[0] = p0;
+        tile[64] = p1;
+        tile[128] = p2;
+    }
+}
+
+__global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__ packed,
+                                                     const half_t *__restrict__ scales, int M, int K,
+                                                     half_t *__restrict__ W_out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int KT = K / kTileK;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+    if (tile >= (int64_t)(M / kTileRows) * KT)
+        return;
+    const int64_t row_tile = tile / KT, kt = tile % KT;
+    const int r = lane & 15, q = lane >> 4;
+    const PackedFp6Source::Tile t = PackedFp6Source::load(packed, row_tile, kt, KT, K, lane);
+    const float scale = (float)scales[row_tile * kTileRows + r];
+    half_t *out = W_out + (row_tile * kTileRows + r) * K + kt * kTileK + q * 8;
+    half8_t frag[8];
+    PackedFp6Source::fragments<0>(t, frag[0], frag[1]);
+    PackedFp6Source::fragments<1>(t, frag[2], frag[3]);
+    PackedFp6Source::fragments<2>(t, frag[4], frag[5]);
+    PackedFp6Source::fragments<3>(t, frag[6], frag[7]);
+#pragma unroll
+    for (int f = 0; f < 8; ++f) {
+        half8_t y;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            y[j] = (half_t)((float)frag[f][j] * scale);  // exact product in fp32, one rounding
+        *reinterpret_cast<half8_t *>(out + f * 32) = y;
+    }
+}
+
+__global__ void zero_fill_kernel(u32x4 *p, size_t n16)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n16)
+        p[i] = (u32x4){0u, 0u, 0u, 0u};
+}
+
+}  // namespace fp6

@@ -1,0 +1,99 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+answers the size queries, and rejects bad arguments on the host before launching anything.
+No compute call is made here (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2401_14112_amd as pkg
+
+    return pkg.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "fp6.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(fp6_\w+|fp16_\w+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_exports_every_declared_symbol(lib):
+    names = _declared_functions()
+    for expected in ("fp6_quantize_pack", "fp6_unpack", "fp6_linear", "fp16_linear", "fp6_packed_bytes",
+                     "fp6_linear_workspace_bytes", "fp6_workspace_init", "fp6_status_str", "fp6_layout_version"):
+        assert expected in names
+    for n in names:
+        assert hasattr(lib, n), "library does not export %s" % n
+
+
+def test_binding_has_the_same_names():
+    import paper_2401_14112_amd as pkg
+
+    for n in ("fp6_quantize_pack", "fp6_unpack", "fp6_linear", "fp16_linear", "fp6_packed_bytes",
+              "fp6_linear_workspace_bytes", "fp6_workspace_init", "fp6_layout_version"):
+        assert callable(getattr(pkg, n))
+
+
+def test_size_queries(lib):
+    assert lib.fp6_layout_version() >= 1
+    assert lib.fp6_packed_bytes(8192, 22016) == 135266304          # 3*M*K/4
+    assert lib.fp6_packed_bytes(256, 512) == 98304
+    assert lib.fp6_packed_bytes(16, 256) == 3072
+    assert lib.fp6_packed_bytes(15, 256) == 0 and lib.fp6_packed_bytes(16, 128) == 0
+    assert lib.fp6_packed_bytes(0, 256) == 0 and lib.fp6_packed_bytes(-16, 256) == 0
+    for (M, N, K) in [(8192, 1, 22016), (8192, 32, 22016), (256, 8, 512), (22016, 16, 8192)]:
+        b = lib.fp6_linear_workspace_bytes(M, N, K)
+        assert b % 16 == 0
+        assert b <= 64 * 1024 * 1024
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    OK, NULL, SHAPE, WS, ALIGN = 0, 1, 2, 3, 4
+    p = ctypes.c_void_p(0x10000)          # never dereferenced: every call below fails its checks first
+    odd = ctypes.c_void_p(0x10008)
+    null = ctypes.c_void_p(0)
+    assert lib.fp6_quantize_pack(null, 16, 256, p, p, null) == NULL
+    assert lib.fp6_quantize_pack(p, 16, 100, p, p, null) == SHAPE
+    assert lib.fp6_quantize_pack(p, 10, 256, p, p, null) == SHAPE
+    assert lib.fp6_quantize_pack(p, 16, 256, odd, p, null) == ALIGN
+    assert lib.fp6_unpack(p, null, 16, 256, p, null) == NULL
+    assert lib.fp6_unpack(p, p, 0, 256, p, null) == SHAPE
+    assert lib.fp6_unpack(odd, p, 16, 256, p, null) == ALIGN
+    assert lib.fp6_linear(p, p, p, null, 16, 1, 256, null, 0, null) == NULL
+    assert lib.fp6_linear(p, p, p, p, 16, 0, 256, null, 0, null) == SHAPE
+    assert lib.fp6_linear(p, p, p, p, 16, 1, 255, null, 0, null) == SHAPE
+    assert lib.fp6_linear(p, p, odd, p, 16, 1, 256, null, 0, null) == ALIGN
+    assert lib.fp16_linear(null, p, p, 16, 1, 256, null, 0, null) == NULL
+    assert lib.fp16_linear(p, p, p, 24, 1, 256, null, 0, null) == SHAPE
+    # a shape that needs split-K partial sums refuses to run without a workspace
+    M, N, K = 8192, 8, 22016
+    need = lib.fp6_linear_workspace_bytes(M, N, K)
+    assert need > 0
+    assert lib.fp6_linear(p, p, p, p, M, N, K, null, 0, null) == WS
+    assert lib.fp6_linear(p, p, p, p, M, N, K, p, need - 16, null) == WS
+    assert lib.fp6_linear(p, p, p, p, M, N, K, odd, need, null) == ALIGN
+    assert lib.fp6_workspace_init(null, 0, null) == OK
+    assert lib.fp6_workspace_init(null, 64, null) == NULL
+    assert lib.fp6_workspace_init(odd, 64, null) == ALIGN
+    for code in range(0, 7):
+        assert len(lib.fp6_status_str(code)) > 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+
+    import paper_2401_14112_amd as pkg
+
+    W = torch.zeros((16, 256), dtype=torch.float16)
+    with pytest.raises(pkg.Fp6Error):
+        pkg.fp6_quantize_pack(W)
+    with pytest.raises(pkg.Fp6Error):
+        pkg.fp6_linear(torch.zeros(3072, dtype=torch.uint8), torch.zeros(16, dtype=torch.float16),
+                       torch.zeros((1, 256), dtype=torch.float16), 16, 256)

@@ -1,0 +1,296 @@
+"""GPU parity tests: the HIP path, called through the C-ABI binding, against the CPU oracle.
+
+pack / unpack are compared bit for bit; the GEMM must satisfy, for every output column n,
+max_m |Y_gpu - Y_ref| <= 5e-3 * max_m |Y_ref| (Y_ref in fp64).
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = 5e-3
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2401_14112_amd as p
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    p.load_library()
+    return p
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _np16(t):
+    return t.detach().cpu().numpy()
+
+
+def _check_linear(Y_gpu, Y_ref, what):
+    """Y_gpu fp16 [N][M'] (numpy), Y_ref fp64 [N][M']."""
+    err = np.abs(Y_gpu.astype(np.float64) - Y_ref)
+    col_err = err.max(axis=1)
+    col_ref = np.abs(Y_ref).max(axis=1)
+    bad = col_err > TOL * col_ref
+    assert not bad.any(), "%s: columns %s exceed the bound, worst ratio %.3g" % (
+        what, np.flatnonzero(bad)[:8], (col_err / np.maximum(col_ref, 1e-300)).max())
+    return (col_err / np.maximum(col_ref, 1e-300)).max()
+
+
+# ------------------------------------------------------------------ pack / unpack
+@pytest.mark.parametrize("M,K,seed", [(256, 512, 0), (16, 256, 1), (80, 1280, 2), (48, 2304, 3)])
+def test_quantize_pack_bit_exact(pkg, oracle, M, K, seed):
+    _say("quantize_pack M=%d K=%d seed=%d" % (M, K, seed))
+    W = workloads.make_weights(M, K, seed)
+    packed, scales = pkg.fp6_quantize_pack(W.cuda())
+    torch.cuda.synchronize()
+    ref_packed, ref_scales = oracle.quantize_pack(W.numpy())
+    assert np.array_equal(_np16(scales).view(np.uint16), ref_scales.view(np.uint16))
+    assert np.array_equal(_np16(packed), ref_packed)
+
+
+def _special_matrix(oracle):
+    """Rows that exercise every code, ties, signed zeros, zero rows and rows with subnormal scales."""
+    table = oracle.decode_table()
+    M, K = 32, 512
+    W = np.zeros((M, K), dtype=np.float16)
+    for m, s in enumerate([2.0 ** -6, 0.01171875, 1.0, 3.0]):
+        W[m, :64] = (table * s).astype(np.float16)
+        W[m, 100:164] = (table[::-1] * s).astype(np.float16)
+    ties = [26, 22, 18, 1.875, 0.21875, 0.09375, 0.03125, 27, 25, 1.1, 1.13, 0.04, 0.03]
+    W[4, 0] = 28.0
+    W[4, 1:1 + len(ties)] = ties
+    W[5, 0] = -28.0
+    W[5, 1:1 + len(ties)] = [-t for t in ties]
+    W[6, 3] = -0.0                                   # all-zero row with one negative zero
+    W[7, :] = np.float16(2.0 ** -24)                 # scale rounds to zero
+    W[7, 5] = -np.float16(2.0 ** -24)
+    W[8, 0] = np.float16(28 * 2.0 ** -24)            # subnormal scale 2^-24
+    W[8, 1] = np.float16(14 * 2.0 ** -24)
+    W[8, 2] = -np.float16(3 * 2.0 ** -24)
+    W[9, 0] = np.float16(41 * 2.0 ** -24)            # scale rounds down so the row maximum saturates
+    W[9, 1] = np.float16(13 * 2.0 ** -24)
+    W[10, :] = np.float16(65504.0)                   # largest fp16 everywhere
+    W[11, 7] = np.float16(-65504.0)
+    W[11, 8] = np.float16(6.1e-5)
+    rng = np.random.default_rng(5)
+    W[12:] = rng.standard_normal((M - 12, K)).astype(np.float16) * np.float16(0.02)
+    return W
+
+
+def test_quantize_pack_special_values(pkg, oracle):
+    _say("quantize_pack special values")
+    W = _special_matrix(oracle)
+    M, K = W.shape
+    packed, scales = pkg.fp6_quantize_pack(torch.from_numpy(W).cuda())
+    torch.cuda.synchronize()
+    ref_packed, ref_scales = oracle.quantize_pack(W)
+    assert np.array_equal(_np16(scales).view(np.uint16), ref_scales.view(np.uint16))
+    got_codes = oracle.unpack_codes(_np16(packed), M, K)
+    ref_codes = oracle.unpack_codes(ref_packed, M, K)
+    assert np.array_equal(got_codes, ref_codes)
+    assert np.array_equal(_np16(packed), ref_packed)
+    # the every-code rows come back as the codes 0..63
+    assert np.array_equal(got_codes[0, :64], np.arange(64, dtype=np.uint8))
+
+
+@pytest.mark.parametrize("M,K,seed", [(256, 512, 0), (80, 1280, 2)])
+def test_unpack_bit_exact(pkg, oracle, M, K, seed):
+    _say("unpack M=%d K=%d" % (M, K))
+    W = workloads.make_weights(M, K, seed).numpy()
+    ref_packed, ref_scales = oracle.quantize_pack(W)
+    got = pkg.fp6_unpack(torch.from_numpy(ref_packed).cuda(), torch.from_numpy(ref_scales).cuda(), M, K)
+    torch.cuda.synchronize()
+    want = oracle.unpack(ref_packed, ref_scales, M, K)
+    assert np.array_equal(_np16(got).view(np.uint16), want.view(np.uint16))
+
+
+def test_unpack_every_code_and_scales(pkg, oracle):
+    """All 64 codes under assorted scales (normal, subnormal, zero, large): bit-exact, signed zeros kept."""
+    _say("unpack every code")
+    M, K = 16, 256
+    codes = np.zeros((M, K), dtype=np.uint8)
+    for m in range(M):
+        codes[m] = (np.arange(K) * (2 * m + 1) + m) % 64
+    scale_bits = np.array([0x3C00, 0x0000, 0x0001, 0x0002, 0x03FF, 0x0400, 0x1E00, 0x2001, 0x77FF, 0x68AB,
+                           0x0155, 0x2E66, 0x3555, 0x1001, 0x5BFF, 0x63FF], dtype=np.uint16)
+    packed = oracle.pack(codes)
+    scales = scale_bits.view(np.float16)
+    got = pkg.fp6_unpack(torch.from_numpy(packed).cuda(), torch.from_numpy(scales.copy()).cuda(), M, K)
+    torch.cuda.synchronize()
+    want = oracle.unpack(packed, scales, M, K)
+    assert np.array_equal(_np16(got).view(np.uint16), want.view(np.uint16))
+    assert np.isinf(want.astype(np.float32)).any()      # 28 * 32752 overflows: rounded to inf on both sides
+
+
+def test_pack_then_unpack_on_gpu(pkg, oracle):
+    _say("pack -> unpack round trip on the GPU")
+    W = _special_matrix(oracle)
+    M, K = W.shape
+    packed, scales = pkg.fp6_quantize_pack(torch.from_numpy(W).cuda())
+    back = pkg.fp6_unpack(packed, scales, M, K)
+    torch.cuda.synchronize()
+    ref_packed, ref_scales = oracle.quantize_pack(W)
+    want = oracle.unpack(ref_packed, ref_scales, M, K)
+    assert np.array_equal(_np16(back).view(np.uint16), want.view(np.uint16))
+
+
+# ------------------------------------------------------------------ linear
+def _linear_case(pkg, oracle, M, K, N, seed, split=0, x_scale=1.0):
+    W = workloads.make_weights(M, K, seed).numpy()
+    X = (workloads.make_activations(N, K, seed) * x_scale).to(torch.float16)
+    packed, scales = oracle.quantize_pack(W)
+    pkg.fp6_tuning_set_split_k(split)
+    try:
+        Y = pkg.fp6_linear(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), X.cuda(), M, K)
+        torch.cuda.synchronize()
+    finally:
+        pkg.fp6_tuning_set_split_k(0)
+    Y_ref = oracle.linear(packed, scales, X.numpy(), M, K)
+    return _np16(Y), Y_ref
+
+
+def test_linear_config1(pkg, oracle):
+    name, M, K = workloads.TINY
+    _say("linear tiny config M=%d K=%d N=8" % (M, K))
+    Y, Y_ref = _linear_case(pkg, oracle, M, K, 8, seed=0)
+    worst = _check_linear(Y, Y_ref, "tiny")
+    _say("  worst column ratio %.3g" % worst)
+    assert worst < 2e-3          # fp32 accumulation: the error is the final fp16 rounding
+
+
+@pytest.mark.parametrize("N", [1, 2, 3, 4, 7, 8, 15, 16, 17, 24, 31, 32, 33, 48, 70])
+def test_linear_token_counts(pkg, oracle, N):
+    M, K = 80, 1280          # 5 row tiles (ragged against 4 waves per block), 5 k-tiles
+    _say("linear M=%d K=%d N=%d" % (M, K, N))
+    Y, Y_ref = _linear_case(pkg, oracle, M, K, N, seed=N)
+    _check_linear(Y, Y_ref, "N=%d" % N)
+
+
+@pytest.mark.parametrize("split", [1, 2, 3, 5, 64])
+@pytest.mark.parametrize("N", [5, 32])
+def test_linear_split_k(pkg, oracle, split, N):
+    M, K = 144, 2816         # 9 row tiles, 11 k-tiles
+    _say("linear split-K S=%d N=%d" % (split, N))
+    Y, Y_ref = _linear_case(pkg, oracle, M, K, N, seed=split, split=split)
+    _check_linear(Y, Y_ref, "split=%d" % split)
+
+
+def test_linear_is_deterministic_and_workspace_reusable(pkg, oracle):
+    M, K, N = 256, 4096, 16
+    _say("linear determinism / workspace reuse")
+    W = workloads.make_weights(M, K, 3).cuda()
+    X = workloads.make_activations(N, K, 3).cuda()
+    packed, scales = pkg.fp6_quantize_pack(W)
+    pkg.fp6_tuning_set_split_k(4)
+    try:
+        nbytes = pkg.fp6_linear_workspace_bytes(M, N, K)
+        assert nbytes > 0
+        ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+        pkg.fp6_workspace_init(ws)
+        outs = []
+        for _ in range(5):
+            outs.append(pkg.fp6_linear(packed, scales, X, M, K, workspace=ws).clone())
+        torch.cuda.synchronize()
+    finally:
+        pkg.fp6_tuning_set_split_k(0)
+    for o in outs[1:]:
+        assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16))
+    Y_ref = oracle.linear(_np16(packed), _np16(scales), _np16(X), M, K)
+    _check_linear(_np16(outs[0]), Y_ref, "reuse")
+
+
+def test_linear_exact_special_cases(pkg, oracle):
+    """Cases with a closed form that the GPU must hit exactly after its single fp16 rounding."""
+    _say("linear closed-form cases")
+    M, K, N = 48, 512, 4
+    rng = np.random.default_rng(11)
+    pi = rng.permutation(K)[:M]
+    sign = rng.choice([-1.0, 1.0], M)
+    W = np.zeros((M, K), dtype=np.float16)
+    W[np.arange(M), pi] = (0.875 * sign).astype(np.float16)
+    X = workloads.make_activations(N, K, 4)
+    packed, scales = pkg.fp6_quantize_pack(torch.from_numpy(W).cuda())
+    Y = pkg.fp6_linear(packed, scales, X.cuda(), M, K)
+    torch.cuda.synchronize()
+    want = (0.875 * sign[None, :] * X.numpy().astype(np.float64)[:, pi]).astype(np.float16)
+    assert np.array_equal(_np16(Y).view(np.uint16), want.view(np.uint16))
+    # subnormal codes only (E = 0): a flush of fp16 subnormals anywhere in the unpack would zero these
+    codes = np.full((M, K), 0b000011, dtype=np.uint8)          # 3/16
+    codes[:, ::2] = 0b100001                                    # -1/16
+    scales1 = np.ones(M, dtype=np.float16)
+    Xs = torch.ones((N, K), dtype=torch.float16)
+    Y2 = pkg.fp6_linear(torch.from_numpy(oracle.pack(codes)).cuda(), torch.from_numpy(scales1).cuda(), Xs.cuda(), M, K)
+    torch.cuda.synchronize()
+    assert np.all(_np16(Y2).astype(np.float64) == (K // 2) * (3 / 16 - 1 / 16))
+
+
+def test_linear_all_codes_against_oracle(pkg, oracle):
+    _say("linear with uniformly random codes and assorted scales")
+    M, K, N = 64, 1024, 9
+    codes = workloads.make_codes(M, K, 21).numpy()
+    scales = (np.abs(np.random.default_rng(2).standard_normal(M)) * 0.01 + 1e-4).astype(np.float16)
+    X = workloads.make_activations(N, K, 21)
+    packed = oracle.pack(codes)
+    Y = pkg.fp6_linear(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), X.cuda(), M, K)
+    torch.cuda.synchronize()
+    _check_linear(_np16(Y), oracle.linear_codes(codes, scales, X.numpy()), "all codes")
+
+
+@pytest.mark.parametrize("N", [1, 8, 32, 40])
+def test_fp16_linear(pkg, oracle, N):
+    M, K = 80, 1280
+    _say("fp16_linear M=%d K=%d N=%d" % (M, K, N))
+    W = workloads.make_weights(M, K, 7)
+    X = workloads.make_activations(N, K, 7)
+    Y = pkg.fp16_linear(W.cuda(), X.cuda())
+    torch.cuda.synchronize()
+    _check_linear(_np16(Y), oracle.linear_f16(W.numpy(), X.numpy()), "fp16 N=%d" % N)
+
+
+# ------------------------------------------------------------------ full-size layer, sampled rows
+def _sampled_row_tiles(M, count, seed):
+    rng = np.random.default_rng(seed)
+    tiles = set([0, M // 16 - 1])
+    tiles.update(int(t) for t in rng.choice(M // 16, size=count - 2, replace=False))
+    return np.array(sorted(tiles), dtype=np.int64)
+
+
+@pytest.mark.parametrize("shape", [workloads.FFN_65B, workloads.FFN_65B_DOWN])
+def test_full_size_layer_sampled(pkg, oracle, shape):
+    """The benchmark layer at its real size, in the launch configuration bench.py times: the packed
+    stream and scales are compared bit for bit on sampled 16-row tiles (tiles are contiguous in the
+    stream), and Y on the rows of those tiles for N = 1, 8, 32."""
+    name, M, K = shape
+    _say("full-size %s M=%d K=%d" % (name, M, K))
+    W = workloads.make_weights(M, K, seed=0, device="cuda")
+    packed, scales = pkg.fp6_quantize_pack(W)
+    torch.cuda.synchronize()
+    tiles = _sampled_row_tiles(M, 24, seed=1)
+    rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
+    W_rows = _np16(W[torch.from_numpy(rows).cuda()])
+    ref_packed, ref_scales = oracle.quantize_pack(W_rows)          # the sampled tiles as a 16*T-row matrix
+    tile_bytes = (K // 256) * 3072
+    got_packed = np.concatenate([_np16(packed[t * tile_bytes:(t + 1) * tile_bytes]) for t in tiles])
+    assert np.array_equal(_np16(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
+    assert np.array_equal(got_packed, ref_packed)
+    del W
+    for N in (1, 8, 32):
+        _say("  linear N=%d" % N)
+        X = workloads.make_activations(N, K, seed=N, device="cuda")
+        Y = pkg.fp6_linear(packed, scales, X, M, K)
+        torch.cuda.synchronize()
+        Y_ref = oracle.linear(ref_packed, ref_scales, _np16(X), len(rows), K)
+        worst = _check_linear(_np16(Y)[:, rows], Y_ref, "%s N=%d" % (name, N))
+        _say("    worst column ratio %.3g" % worst)
+        # every output was written: no row of Y may still hold the fill pattern of a fresh buffer
+        Yf = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+        pkg.fp6_linear(packed, scales, X, M, K, out=Yf)
+        torch.cuda.synchronize()
+        assert not torch.isnan(Yf).any()
+        assert torch.equal(Yf.view(torch.int16), Y.view(torch.int16))

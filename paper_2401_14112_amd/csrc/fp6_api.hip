@@ -13,9 +13,18 @@ namespace {
 using namespace fp6;
 
 constexpr int kLayoutVersion = 1;
-constexpr int kStreamWaves = 4;   // waves per block of the streaming kernel
-constexpr int kStreamDepth = 2;   // weight tiles in flight per wave
-constexpr int kTargetWaves = 256 * 16;  // 256 CUs x 16 resident waves
+#ifndef FP6_STREAM_WAVES
+#define FP6_STREAM_WAVES 8
+#endif
+#ifndef FP6_STREAM_DEPTH
+#define FP6_STREAM_DEPTH 2
+#endif
+#ifndef FP6_TARGET_WAVES_PER_CU
+#define FP6_TARGET_WAVES_PER_CU 8
+#endif
+constexpr int kStreamWaves = FP6_STREAM_WAVES;  // waves per block of the streaming kernel
+constexpr int kStreamDepth = FP6_STREAM_DEPTH;  // weight tiles in flight per wave
+constexpr int kTargetWaves = 256 * FP6_TARGET_WAVES_PER_CU;  // 256 CUs x resident waves aimed for
 
 std::atomic<int> g_forced_split{0};
 

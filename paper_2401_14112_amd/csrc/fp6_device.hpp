@@ -79,11 +79,31 @@ __device__ __forceinline__ void unpack_words(uint32_t d0, uint32_t d1, uint32_t 
     odd_run = bit_cast<half8_t>(o);
 }
 
+// ---- bounds-checked buffer loads -------------------------------------------
+// A buffer resource lets the hardware range-check every load: an offset at or beyond
+// num_bytes returns zeros and generates no memory traffic.  The streaming kernels use
+// this so that their main loop has no branches (a tile past the end of a wave's slice
+// simply reads as zero weights).  All four words must be wave-uniform.  Only the
+// per-lane offset (plus the instruction's immediate) takes part in the range check,
+// so every varying part of an address is put there and the scalar offset stays 0.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t num_bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)num_bytes, 0x00020000);
+}
+
+constexpr int kLoadStreaming = 2;  // "nt": read-once data, do not keep it in the caches
+constexpr int kLoadDefault = 0;
+constexpr int kOutOfRange = (int)0x80000000u;  // a lane offset no buffer here reaches: reads as zeros
+
 // ---- weight sources -------------------------------------------------------
 // A source knows how one lane fetches its share of a 16 x 256 weight tile and how
 // to turn it into the eight A fragments (one per run) of the tile.  k_offset(f, q)
 // is the column, inside the tile, of the first of the 8 consecutive columns that
 // lane group q feeds to MFMA step f; the activation staging uses the same map.
+// slice_rsrc() describes the memory one wave may read for row tile `row_tile` and
+// k-tiles [kt0, kt1); load() fetches tile number t of that slice.
 
 struct PackedFp6Source {
     struct Tile {
@@ -91,18 +111,22 @@ struct PackedFp6Source {
     };
     static constexpr bool kHasScale = true;
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
-    // base: packed stream; row_tile/k_tile: tile coordinates; KT = K/256
-    __device__ static __forceinline__ Tile load(const void *base, int64_t row_tile, int64_t k_tile, int64_t KT,
-                                                int64_t /*K*/, int lane)
+    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
+                                                        int64_t KT, int64_t /*K*/)
     {
-        const u32x4 *p =
-            reinterpret_cast<const u32x4 *>(static_cast<const uint8_t *>(base) + (row_tile * KT + k_tile) * kTileBytes)
-            + lane;
-        Tile t;
-        t.p0 = __builtin_nontemporal_load(p);
-        t.p1 = __builtin_nontemporal_load(p + 64);
-        t.p2 = __builtin_nontemporal_load(p + 128);
-        return t;
+        return make_rsrc(static_cast<const uint8_t *>(base) + (row_tile * KT + kt0) * kTileBytes,
+                         (uint32_t)(kt1 - kt0) * kTileBytes);
+    }
+    static constexpr int kTileStride = kTileBytes;  // bytes from one k-tile of the slice to the next
+    __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
+    // off = lane_offset + t * kTileStride for tile t of the slice
+    __device__ static __forceinline__ Tile load(rsrc_t r, int off)
+    {
+        Tile tile;
+        tile.p0 = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, kLoadStreaming);
+        tile.p1 = __builtin_amdgcn_raw_buffer_load_b128(r, off + 1024, 0, kLoadStreaming);
+        tile.p2 = __builtin_amdgcn_raw_buffer_load_b128(r, off + 2048, 0, kLoadStreaming);
+        return tile;
     }
     template <int G>
     __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
@@ -118,17 +142,25 @@ struct PlainFp16Source {
     static constexpr bool kHasScale = false;
     // lane group q owns 64 consecutive columns of the tile (128 contiguous bytes per lane)
     __device__ static __forceinline__ int k_offset(int f, int q) { return q * 64 + f * 8; }
-    __device__ static __forceinline__ Tile load(const void *base, int64_t row_tile, int64_t k_tile, int64_t /*KT*/,
-                                                int64_t K, int lane)
+    // the 16 rows of the row tile; tiles past the slice are neutralised by zero activations
+    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int /*kt0*/, int /*kt1*/,
+                                                        int64_t /*KT*/, int64_t K)
+    {
+        return make_rsrc(static_cast<const half_t *>(base) + row_tile * kTileRows * K, (uint32_t)(kTileRows * K * 2));
+    }
+    static constexpr int kTileStride = kTileK * 2;
+    __device__ static __forceinline__ int lane_offset(int lane, int kt0, int K)
     {
         const int r = lane & 15, q = lane >> 4;
-        const u32x4 *p = reinterpret_cast<const u32x4 *>(static_cast<const half_t *>(base)
-                                                         + (row_tile * kTileRows + r) * K + k_tile * kTileK + q * 64);
-        Tile t;
+        return (r * K + kt0 * kTileK + q * 64) * 2;
+    }
+    __device__ static __forceinline__ Tile load(rsrc_t rs, int off)
+    {
+        Tile tile;
 #pragma unroll
         for (int f = 0; f < 8; ++f)
-            t.v[f] = __builtin_nontemporal_load(p + f);
-        return t;
+            tile.v[f] = __builtin_amdgcn_raw_buffer_load_b128(rs, off + f * 16, 0, kLoadStreaming);
+        return tile;
     }
     template <int G>
     __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)

@@ -35,35 +35,49 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KT = K / kTileK;
     const int n_row_tiles = M / kTileRows;
     const int split = blockIdx.x % S;  // neighbouring blocks (one per XCD) take different k slices
     const int row_block = blockIdx.x / S;
     const int row_tile = row_block * WAVES + wave;
     const bool active = row_tile < n_row_tiles;
-    const int kt0 = (int)(((int64_t)KT * split) / S);
-    const int kt1 = (int)(((int64_t)KT * (split + 1)) / S);
+    const int kt0 = (int)(((unsigned)KT * (unsigned)split) / (unsigned)S);  // KT * S < 2^31 (host-checked)
+    const int kt1 = (int)(((unsigned)KT * (unsigned)(split + 1)) / (unsigned)S);
+    const int n_valid = kt1 - kt0;        // k-tiles of this slice
+    const int T = (KT + S - 1) / S;       // loop trips: the same for every slice (>= n_valid)
+
+    // Inactive waves (ragged last row block) stream the last valid row tile and drop the result,
+    // so the main loop has no per-wave control flow.
+    const rsrc_t w_rsrc = Src::slice_rsrc(weights, active ? row_tile : n_row_tiles - 1, kt0, kt1, KT, K);
+    const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
     // ---- activation staging: piece c = nt*512 + f*64 + q*16 + n  <->  X[nt*16+n][k_tile*256 + k_offset(f,q) ..+8]
-    u32x4 xr[XPER];
-    auto x_fetch = [&](int k_tile) {
+    // Token columns >= N and k-tiles past the slice get an offset outside the buffer and read as zeros.
+    struct XRegs {
+        u32x4 v[XPER];
+    };
+    int x_off[XPER];
+#pragma unroll
+    for (int i = 0; i < XPER; ++i) {
+        const int c = tid + i * THREADS;
+        const int n = c & 15, q = (c >> 4) & 3, f = (c >> 6) & 7, nt = c >> 9;
+        const int col = nt * 16 + n;
+        x_off[i] = col < N ? (col * K + kt0 * kTileK + Src::k_offset(f, q)) * 2 : kOutOfRange;
+    }
+    auto x_fetch = [&](int t) {
+        XRegs r;
 #pragma unroll
         for (int i = 0; i < XPER; ++i) {
-            const int c = tid + i * THREADS;
-            const int n = c & 15, q = (c >> 4) & 3, f = (c >> 6) & 7, nt = c >> 9;
-            const int col = nt * 16 + n;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (col < N)
-                v = *reinterpret_cast<const u32x4 *>(X + (int64_t)col * K + (int64_t)k_tile * kTileK
-                                                     + Src::k_offset(f, q));
-            xr[i] = v;
+            const int off = (t < n_valid && x_off[i] != kOutOfRange) ? x_off[i] + t * (kTileK * 2) : kOutOfRange;
+            r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off, 0, kLoadDefault);
         }
+        return r;
     };
-    auto x_commit = [&](int buf) {
+    auto x_commit = [&](const XRegs &r, int buf) {
 #pragma unroll
         for (int i = 0; i < XPER; ++i)
-            xs[buf][tid + i * THREADS] = xr[i];
+            xs[buf][tid + i * THREADS] = r.v[i];
     };
 
     float4_t acc[NT];
@@ -95,37 +109,37 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
         mma_pair(a_even, a_odd, buf, 3);
     };
 
-    // ---- prologue: DEPTH weight tiles in flight, first activation tile in LDS
+    // ---- software pipeline.  Slot d of the register ring holds tile i*DEPTH + d of the slice: its
+    // weights and its share of the activation tile are requested DEPTH tiles ahead, right after the
+    // slot's previous tile has been consumed, so the new data lands in the registers that just became
+    // free and DEPTH-1 tiles stay in flight while one is being computed.  The activation pieces are
+    // requested before the weights of the same tile: loads return in order, so waiting for a tile's
+    // weights never waits for anything younger than that tile.  The loop body has no branches: tiles
+    // past the end of the slice read as zeros through the buffer bounds check.
+    static_assert(DEPTH % 2 == 0, "the LDS double buffer is indexed by the ring slot");
     typename Src::Tile w[DEPTH];
+    XRegs xr[DEPTH];
+    const int w_off = Src::lane_offset(lane, kt0, K);
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d)
-        if (active && kt0 + d < kt1)
-            w[d] = Src::load(weights, row_tile, kt0 + d, KT, K, lane);
-    if (kt0 < kt1) {
-        x_fetch(kt0);
-        x_commit(0);
+    for (int d = 0; d < DEPTH; ++d) {
+        // keep the request order of the loop body (activations, then weights, slot by slot), so the
+        // outstanding-load bookkeeping at the loop head is the same on entry and on the back edge
+        xr[d] = x_fetch(d);
+        __builtin_amdgcn_sched_barrier(0);
+        w[d] = Src::load(w_rsrc, w_off + d * Src::kTileStride);
+        __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();
-
-    // ---- main loop over the k-tiles of this split
-    for (int kt = kt0; kt < kt1; kt += DEPTH) {
+    for (int i = 0; i < T; i += DEPTH) {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
-            const int k = kt + d;
-            if (k < kt1) {  // uniform over the block
-                const int buf = (k - kt0) & 1;
-                const bool more = (k + 1 < kt1);
-                if (more)
-                    x_fetch(k + 1);
-                const typename Src::Tile cur = w[d];
-                if (active && k + DEPTH < kt1)
-                    w[d] = Src::load(weights, row_tile, k + DEPTH, KT, K, lane);
-                if (active)
-                    compute(cur, buf);
-                if (more)
-                    x_commit(buf ^ 1);
-                __syncthreads();
-            }
+            x_commit(xr[d], d & 1);
+            __syncthreads();
+            compute(w[d], d & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            xr[d] = x_fetch(i + d + DEPTH);
+            __builtin_amdgcn_sched_barrier(0);
+            w[d] = Src::load(w_rsrc, w_off + (i + d + DEPTH) * Src::kTileStride);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
@@ -159,23 +173,27 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
         return;
     }
 
+#ifndef FP6_SPLITK_SYNC
+#define FP6_SPLITK_SYNC 1
+#endif
+#if FP6_SPLITK_SYNC == 0
+    // Release/acquire fences at device scope (write back and invalidate this XCD's L2).
     if (active) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
             if (nt * 16 + n_in_tile < N)
                 partials[(((int64_t)split * n_row_tiles + row_tile) * NT + nt) * 64 + lane] = acc[nt];
     }
-    __threadfence();  // publish the partial tile device-wide before signalling arrival
-    __syncthreads();
+    __syncthreads();  // every wave's partial stores have been issued and have completed
     if (tid == 0) {
-        __threadfence();
-        const int arrived = atomicAdd(&counters[row_block], 1);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        const int arrived = __hip_atomic_fetch_add(&counters[row_block], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_is_last = (arrived == S - 1);
     }
     __syncthreads();
     if (!s_is_last)
         return;
-    __threadfence();  // see the other blocks' partial tiles
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     if (active) {
         float4_t sum[NT];
 #pragma unroll
@@ -189,6 +207,49 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
         }
         finish(sum);
     }
+#else
+    // The partial tiles are written and read with device-scope atomic (relaxed) accesses: such
+    // accesses are performed at the point where all CUs of the device agree (they are not left
+    // in, nor served from, a non-coherent cache), so no cache write-back or invalidate is needed.
+    // Order: stores complete (the barrier waits for them) -> arrival count -> the last block's loads.
+    float *pf = reinterpret_cast<float *>(partials);
+    if (active) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            if (nt * 16 + n_in_tile < N) {
+                float *dst = pf + ((((int64_t)split * n_row_tiles + row_tile) * NT + nt) * 4) * 64 + lane;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    __hip_atomic_store(dst + i * 64, acc[nt][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's partial stores are done
+    __syncthreads();
+    if (tid == 0) {
+        const int arrived = __hip_atomic_fetch_add(&counters[row_block], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_is_last = (arrived == S - 1);
+    }
+    __syncthreads();
+    if (!s_is_last)
+        return;
+    if (active) {
+        float4_t sum[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            sum[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < S; ++s) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (nt * 16 + n_in_tile < N) {
+                    const float *src = pf + ((((int64_t)s * n_row_tiles + row_tile) * NT + nt) * 4) * 64 + lane;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        sum[nt][i] += __hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+        }
+        finish(sum);
+    }
+#endif
     if (tid == 0)
         counters[row_block] = 0;  // re-arm for the next call on this workspace
 }

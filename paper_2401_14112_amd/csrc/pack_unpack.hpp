@@ -127,7 +127,8 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
         return;
     const int64_t row_tile = tile / KT, kt = tile % KT;
     const int r = lane & 15, q = lane >> 4;
-    const PackedFp6Source::Tile t = PackedFp6Source::load(packed, row_tile, kt, KT, K, lane);
+    const rsrc_t rs = PackedFp6Source::slice_rsrc(packed, row_tile, (int)kt, (int)kt + 1, KT, K);
+    const PackedFp6Source::Tile t = PackedFp6Source::load(rs, PackedFp6Source::lane_offset(lane, 0, K));
     const float scale = (float)scales[row_tile * kTileRows + r];
     half_t *out = W_out + (row_tile * kTileRows + r) * K + kt * kTileK + q * 8;
     half8_t frag[8];

@@ -1,0 +1,285 @@
+#!/usr/bin/env python3
+"""Benchmark of the W6A16 linear layer on one MI355X.
+
+Workload (the paper's Fig. 1 layer, llama-65b FFN, W = 8192 x 22016, batch swept): one
+"step" is the decode sweep N = 1, 2, 4, 8, 16, 32 of fp6_linear over packed e3m2 weights,
+i.e. six launches of the runtime path (weight fetch, activation staging, register unpack,
+MFMA contraction, split-K reduction, scaled epilogue).  Every launch reads a different one
+of 8 packed copies of the layer (1.08 GB in total) so that no weight byte is served from
+the 256 MB last-level cache.  The ahead-of-time steps (fp6_quantize_pack) and the test aid
+(fp6_unpack) are timed once each outside the step and reported under "offline".
+
+Prints ONE JSON line.  `value` = packed weight bytes streamed per second over the timed
+steps (whole job, launches replayed from captured HIP graphs); `roofline` prices the
+dominant kernel (the 16-token streaming kernel) with HIP events recorded around each of its
+launches; `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, vendor figure
+MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix peak, vendor figure
+N_BUFFERS = 8
+
+
+def algorithmic_bytes(M, N, K):
+    """Bytes one fp6_linear call must move: packed weights + scales once, X once, Y once."""
+    return 3 * M * K // 4 + 2 * M + 2 * K * N + 2 * M * N
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the prefill / fp16 / offline side measurements")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the layer is a single-GPU kernel; see DESIGN.md "
+              "for how it would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2401_14112_amd as pkg
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    pkg.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    name, M, K = workloads.FFN_65B
+    sweep = list(workloads.DECODE_N)
+    P = pkg.fp6_packed_bytes(M, K)
+
+    # ---- inputs resident in HBM: 8 packed copies of the layer (different seeds), activations per N
+    packed, scales = [], []
+    pack_ms = []
+    W0 = None
+    for b in range(N_BUFFERS):
+        W = workloads.make_weights(M, K, seed=b, device=dev)
+        pk = torch.empty(P, dtype=torch.uint8, device=dev)
+        sc = torch.empty(M, dtype=torch.float16, device=dev)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        pkg.fp6_quantize_pack(W, pk, sc)
+        e1.record()
+        torch.cuda.synchronize()
+        pack_ms.append(e0.elapsed_time(e1))
+        packed.append(pk)
+        scales.append(sc)
+        if b == 0:
+            W0 = W
+        else:
+            del W
+    Xs = {n: workloads.make_activations(n, K, seed=n, device=dev) for n in sweep}
+    Ys = {n: torch.empty((n, M), dtype=torch.float16, device=dev) for n in sweep}
+    ws_bytes = max(pkg.fp6_linear_workspace_bytes(M, n, K) for n in sweep)
+    ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    def launch(n, b):
+        pkg.fp6_linear(packed[b], scales[b], Xs[n], M, K, out=Ys[n], workspace=ws)
+
+    # the rotation (launch j reads buffer j % 8) repeats every 4 steps of 6 launches
+    period = 1
+    while (period * len(sweep)) % N_BUFFERS:
+        period += 1
+    for n in sweep:          # first launches outside any capture
+        launch(n, 0)
+    torch.cuda.synchronize()
+    graphs = []
+    for s in range(period):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i, n in enumerate(sweep):
+                launch(n, (s * len(sweep) + i) % N_BUFFERS)
+        graphs.append(g)
+
+    # ---- quick validity check of what is being timed (sampled rows against the CPU oracle)
+    from oracle import fp6_oracle as oracle
+    tiles = np.array([0, 37, M // 16 - 1])
+    rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
+    tile_bytes = (K // 256) * 3072
+    sub_packed = np.concatenate([packed[0][t * tile_bytes:(t + 1) * tile_bytes].cpu().numpy() for t in tiles])
+    sub_scales = scales[0].cpu().numpy()[rows]
+    worst = 0.0
+    for n in (1, 32):
+        launch(n, 0)
+        torch.cuda.synchronize()
+        ref = oracle.linear(sub_packed, sub_scales, Xs[n].cpu().numpy(), len(rows), K)
+        got = Ys[n].cpu().numpy()[:, rows].astype(np.float64)
+        worst = max(worst, float((np.abs(got - ref).max(axis=1) / (5e-3 * np.abs(ref).max(axis=1))).max()))
+    if worst > 1.0:
+        print("bench.py: fp6_linear disagrees with the oracle (error/bound = %.3g)" % worst, file=sys.stderr)
+        sys.exit(3)
+
+    # ---- timed region: W warm-up steps, then exactly K steps between synchronizations
+    for s in range(args.warmup):
+        graphs[s % period].replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        graphs[s % period].replay()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    step_weight_bytes = P * len(sweep)
+    step_flops = sum(2.0 * M * n * K for n in sweep)
+    value_gbps = step_weight_bytes / (ms_per_step * 1e-3) * 1e-9
+
+    # ---- per-launch durations with HIP events on the launch stream, same steps launched eagerly
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(sweep) + 1)] for _ in range(args.steps)]
+    j = 0
+    torch.cuda.synchronize()
+    for s in range(args.steps):
+        ev[s][0].record()
+        for i, n in enumerate(sweep):
+            launch(n, j % N_BUFFERS)
+            j += 1
+            ev[s][i + 1].record()
+    torch.cuda.synchronize()
+    per_n_us = {}
+    for i, n in enumerate(sweep):
+        d = np.array([ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)]) * 1e3
+        per_n_us[n] = (float(d.mean()), float(np.median(d)), float(d.min()))
+    small = [n for n in sweep if n <= 16]          # launches of the dominant (16-token) kernel
+    dom_bytes = sum(algorithmic_bytes(M, n, K) for n in small) / len(small)
+    dom_us = sum(per_n_us[n][0] for n in small) / len(small)
+    achieved = dom_bytes / (dom_us * 1e-6) * 1e-9
+
+    result = {
+        "metric": "W6A16 GEMM effective weight GB/s + TFLOP/s, 8192x22016, N=1..512",
+        "value": round(value_gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "fp6_e3m2 weights x f16 activations, f32 accumulate",
+        "data": "synthetic",
+        "config": {
+            "workload": "llama65b_ffn W[8192x22016] W6A16 linear, one step = decode sweep N in "
+                        "{1,2,4,8,16,32}, launch j reads packed copy j%8 (1.08 GB rotation), HIP-graph replay",
+            "M": M, "K": K, "N_sweep": sweep, "weight_buffers": N_BUFFERS,
+            "layout_version": pkg.fp6_layout_version(),
+        },
+        "tflops": round(step_flops / (ms_per_step * 1e-3) * 1e-12, 2),
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "linear_stream_kernel<PackedFp6Source, NT=1> (N <= 16 launches of the step)",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": None,
+            "algorithmic_bytes_per_launch": int(dom_bytes),
+            "avg_launch_us": round(dom_us, 2),
+        },
+        "sweep": {
+            str(n): {
+                "us_mean": round(per_n_us[n][0], 2), "us_median": round(per_n_us[n][1], 2),
+                "weight_GBps": round(P / per_n_us[n][1] * 1e-3, 1),
+                "tflops": round(2.0 * M * n * K / per_n_us[n][1] * 1e-6, 2),
+                "hbm_frac": round(algorithmic_bytes(M, n, K) / per_n_us[n][1] * 1e-3 / HBM_PEAK_GBPS, 4),
+            } for n in sweep
+        },
+        "oracle_check_err_over_bound": round(worst, 4),
+    }
+
+    if not args.no_extras:
+        result["offline"] = side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_ms)
+    del W0
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(oracle, np, workloads, packed[0], scales[0], M, K, sweep)
+
+    print(json.dumps(result))
+
+
+def _time_graph(torch, fn, launches_per_graph, reps=20):
+    """Average microseconds per launch of fn(i) for i in range(launches_per_graph), from graph replays."""
+    fn(0)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(launches_per_graph):
+            fn(i)
+    g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / (reps * launches_per_graph)
+
+
+def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_ms):
+    """Prefill-sized N, the library's own fp16 GEMM at the same shapes, and the offline steps."""
+    dev = W0.device
+    P = pkg.fp6_packed_bytes(M, K)
+    out = {"quantize_pack_ms": round(float(np.median(pack_ms)), 3),
+           "quantize_pack_GBps_fp16_read": round(2.0 * M * K / (float(np.median(pack_ms)) * 1e-3) * 1e-9, 1)}
+    Wd = torch.empty((M, K), dtype=torch.float16, device=dev)
+    us = _time_graph(torch, lambda i: pkg.fp6_unpack(packed[i % len(packed)], scales[i % len(packed)], M, K, out=Wd), 4, reps=5)
+    out["unpack_ms"] = round(us * 1e-3, 3)
+    out["unpack_GBps_total"] = round((P + 2.0 * M * K) / us * 1e-3, 1)
+    del Wd
+    # the library's own W16A16 kernel on 3 fp16 copies (1.08 GB rotation)
+    W16 = [W0] + [workloads.make_weights(M, K, seed=100 + b, device=dev) for b in range(2)]
+    cmp = {}
+    for n in list(workloads.DECODE_N) + list(workloads.PREFILL_N):
+        X = workloads.make_activations(n, K, seed=n, device=dev)
+        Y = torch.empty((n, M), dtype=torch.float16, device=dev)
+        ws6 = torch.zeros(max(pkg.fp6_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
+        ws16 = torch.zeros(max(pkg.fp16_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
+        reps = 10 if n <= 32 else 3
+        us6 = _time_graph(torch, lambda i: pkg.fp6_linear(packed[i % len(packed)], scales[i % len(packed)], X, M, K, out=Y, workspace=ws6), len(packed), reps)
+        us16 = _time_graph(torch, lambda i: pkg.fp16_linear(W16[i % 3], X, out=Y, workspace=ws16), 3, reps)
+        cmp[str(n)] = {"fp6_us": round(us6, 2), "fp16_us": round(us16, 2), "speedup_vs_own_fp16": round(us16 / us6, 3),
+                       "fp6_weight_GBps": round(P / us6 * 1e-3, 1), "fp6_tflops": round(2.0 * M * n * K / us6 * 1e-6, 2)}
+    out["vs_own_fp16_linear"] = cmp
+    return out
+
+
+def cpu_baseline(oracle, np, workloads, packed0, scales0, M, K, sweep):
+    """The CPU oracle, as it stands, on the first 4096 rows of the same layer over the same sweep."""
+    rows_n = 4096
+    tile_bytes = (K // 256) * 3072
+    sub_packed = packed0[: (rows_n // 16) * tile_bytes].cpu().numpy()
+    sub_scales = scales0[:rows_n].cpu().numpy()
+    Xs = [workloads.make_activations(n, K, seed=n).numpy() for n in sweep]
+    t0 = time.perf_counter()
+    for X in Xs:
+        oracle.linear(sub_packed, sub_scales, X, rows_n, K)
+    dt = time.perf_counter() - t0
+    bytes_done = len(sweep) * (rows_n * K * 3 // 4)
+    return {
+        "value": round(bytes_done / dt * 1e-9, 4),
+        "unit": "GB/s",
+        "cores": oracle.threads(),
+        "kind": "oracle",
+        "sample": "fp64 oracle.linear on rows 0..4095 of the same 8192x22016 layer, same sweep N in "
+                  "{1,2,4,8,16,32} (%.1f s); effective packed-weight bytes per second" % dt,
+        "gflops": round(sum(2.0 * rows_n * n * K for n in sweep) / dt * 1e-9, 2),
+    }
+
+
+if __name__ == "__main__":
+    main()

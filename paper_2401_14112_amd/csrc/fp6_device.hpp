@@ -86,16 +86,49 @@ __device__ __forceinline__ void unpack_words(uint32_t d0, uint32_t d1, uint32_t 
 // simply reads as zero weights).  All four words must be wave-uniform.  Only the
 // per-lane offset (plus the instruction's immediate) takes part in the range check,
 // so every varying part of an address is put there and the scalar offset stays 0.
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef i32x4 rsrc_t;
 
 __device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t num_bytes)
 {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)num_bytes, 0x00020000);
+    const uint64_t a = reinterpret_cast<uint64_t>(base);
+    rsrc_t r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((a >> 32) & 0xffffu));  // stride 0: raw buffer
+    r[2] = __builtin_amdgcn_readfirstlane((int)num_bytes);
+    r[3] = 0x00020000;  // 32-bit data format, no swizzle
+    return r;
 }
 
-constexpr int kLoadStreaming = 2;  // "nt": read-once data, do not keep it in the caches
-constexpr int kLoadDefault = 0;
 constexpr int kOutOfRange = (int)0x80000000u;  // a lane offset no buffer here reaches: reads as zeros
+
+// The pipelined kernels issue their loads from inline assembly and wait for them with explicit
+// s_waitcnt: the compiler's own wait insertion cannot keep several tiles in flight across a loop
+// back edge.  Rules that keep this sound: (1) a loaded value is only used after wait_loads<N>()
+// followed by pin() on it, which orders the use after the wait; (2) every issued load is waited
+// for (and pinned) before its registers die, so no late write lands in a reused register.
+template <int IMM, bool STREAMING>
+__device__ __forceinline__ u32x4 issue_load_b128(rsrc_t rsrc, int lane_off)
+{
+    u32x4 r;
+    if (STREAMING)  // "nt": read-once data, do not keep it in the caches
+        asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3 nt"
+                     : "=v"(r) : "v"(lane_off), "s"(rsrc), "n"(IMM) : "memory");
+    else
+        asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3"
+                     : "=v"(r) : "v"(lane_off), "s"(rsrc), "n"(IMM) : "memory");
+    return r;
+}
+
+// Wait until at most N of the loads issued so far are still outstanding (they return in order).
+template <int N>
+__device__ __forceinline__ void wait_loads()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+__device__ __forceinline__ void pin(u32x4 &v) { asm volatile("" : "+v"(v)); }
 
 // ---- weight sources -------------------------------------------------------
 // A source knows how one lane fetches its share of a 16 x 256 weight tile and how
@@ -103,13 +136,16 @@ constexpr int kOutOfRange = (int)0x80000000u;  // a lane offset no buffer here r
 // is the column, inside the tile, of the first of the 8 consecutive columns that
 // lane group q feeds to MFMA step f; the activation staging uses the same map.
 // slice_rsrc() describes the memory one wave may read for row tile `row_tile` and
-// k-tiles [kt0, kt1); load() fetches tile number t of that slice.
+// k-tiles [kt0, kt1); issue() requests the tile at lane offset `off`
+// (= lane_offset + t * kTileStride for tile t of the slice) with kLoads loads.
 
 struct PackedFp6Source {
     struct Tile {
         u32x4 p0, p1, p2;
     };
     static constexpr bool kHasScale = true;
+    static constexpr int kLoads = 3;
+    static constexpr int kTileStride = kTileBytes;  // bytes from one k-tile of the slice to the next
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
     __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
                                                         int64_t KT, int64_t /*K*/)
@@ -117,16 +153,18 @@ struct PackedFp6Source {
         return make_rsrc(static_cast<const uint8_t *>(base) + (row_tile * KT + kt0) * kTileBytes,
                          (uint32_t)(kt1 - kt0) * kTileBytes);
     }
-    static constexpr int kTileStride = kTileBytes;  // bytes from one k-tile of the slice to the next
     __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
-    // off = lane_offset + t * kTileStride for tile t of the slice
-    __device__ static __forceinline__ Tile load(rsrc_t r, int off)
+    __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
     {
-        Tile tile;
-        tile.p0 = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, kLoadStreaming);
-        tile.p1 = __builtin_amdgcn_raw_buffer_load_b128(r, off + 1024, 0, kLoadStreaming);
-        tile.p2 = __builtin_amdgcn_raw_buffer_load_b128(r, off + 2048, 0, kLoadStreaming);
-        return tile;
+        t.p0 = issue_load_b128<0, true>(r, off);
+        t.p1 = issue_load_b128<1024, true>(r, off);
+        t.p2 = issue_load_b128<2048, true>(r, off);
+    }
+    __device__ static __forceinline__ void pin_tile(Tile &t)
+    {
+        pin(t.p0);
+        pin(t.p1);
+        pin(t.p2);
     }
     template <int G>
     __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
@@ -140,27 +178,38 @@ struct PlainFp16Source {
         u32x4 v[8];
     };
     static constexpr bool kHasScale = false;
-    // lane group q owns 64 consecutive columns of the tile (128 contiguous bytes per lane)
-    __device__ static __forceinline__ int k_offset(int f, int q) { return q * 64 + f * 8; }
+    static constexpr int kLoads = 8;
+    static constexpr int kTileStride = kTileK * 2;
+    // the four lane groups of a row read four adjacent 16-byte pieces (64 contiguous bytes per row
+    // and load instruction); plain (cached) loads, so the other half of each line is an L1/L2 hit
+    __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
     // the 16 rows of the row tile; tiles past the slice are neutralised by zero activations
     __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int /*kt0*/, int /*kt1*/,
                                                         int64_t /*KT*/, int64_t K)
     {
         return make_rsrc(static_cast<const half_t *>(base) + row_tile * kTileRows * K, (uint32_t)(kTileRows * K * 2));
     }
-    static constexpr int kTileStride = kTileK * 2;
     __device__ static __forceinline__ int lane_offset(int lane, int kt0, int K)
     {
         const int r = lane & 15, q = lane >> 4;
-        return (r * K + kt0 * kTileK + q * 64) * 2;
+        return (r * K + kt0 * kTileK + q * 8) * 2;
     }
-    __device__ static __forceinline__ Tile load(rsrc_t rs, int off)
+    __device__ static __forceinline__ void issue(Tile &t, rsrc_t rs, int off)
     {
-        Tile tile;
+        t.v[0] = issue_load_b128<0, false>(rs, off);
+        t.v[1] = issue_load_b128<64, false>(rs, off);
+        t.v[2] = issue_load_b128<128, false>(rs, off);
+        t.v[3] = issue_load_b128<192, false>(rs, off);
+        t.v[4] = issue_load_b128<256, false>(rs, off);
+        t.v[5] = issue_load_b128<320, false>(rs, off);
+        t.v[6] = issue_load_b128<384, false>(rs, off);
+        t.v[7] = issue_load_b128<448, false>(rs, off);
+    }
+    __device__ static __forceinline__ void pin_tile(Tile &t)
+    {
 #pragma unroll
         for (int f = 0; f < 8; ++f)
-            tile.v[f] = __builtin_amdgcn_raw_buffer_load_b128(rs, off + f * 16, 0, kLoadStreaming);
-        return tile;
+            pin(t.v[f]);
     }
     template <int G>
     __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)

@@ -65,14 +65,17 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
         const int col = nt * 16 + n;
         x_off[i] = col < N ? (col * K + kt0 * kTileK + Src::k_offset(f, q)) * 2 : kOutOfRange;
     }
-    auto x_fetch = [&](int t) {
-        XRegs r;
+    auto x_issue = [&](XRegs &r, int t) {
 #pragma unroll
         for (int i = 0; i < XPER; ++i) {
             const int off = (t < n_valid && x_off[i] != kOutOfRange) ? x_off[i] + t * (kTileK * 2) : kOutOfRange;
-            r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off, 0, kLoadDefault);
+            r.v[i] = issue_load_b128<0, false>(x_rsrc, off);
         }
-        return r;
+    };
+    auto x_pin = [&](XRegs &r) {
+#pragma unroll
+        for (int i = 0; i < XPER; ++i)
+            pin(r.v[i]);
     };
     auto x_commit = [&](const XRegs &r, int buf) {
 #pragma unroll
@@ -112,35 +115,40 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     // ---- software pipeline.  Slot d of the register ring holds tile i*DEPTH + d of the slice: its
     // weights and its share of the activation tile are requested DEPTH tiles ahead, right after the
     // slot's previous tile has been consumed, so the new data lands in the registers that just became
-    // free and DEPTH-1 tiles stay in flight while one is being computed.  The activation pieces are
-    // requested before the weights of the same tile: loads return in order, so waiting for a tile's
-    // weights never waits for anything younger than that tile.  The loop body has no branches: tiles
-    // past the end of the slice read as zeros through the buffer bounds check.
+    // free and DEPTH-1 tiles stay in flight while one is being computed.  Every slot issues
+    // kSlotLoads loads; loads return in order, so "at most (DEPTH-1)*kSlotLoads outstanding" means the
+    // oldest slot has arrived.  The loop body has no branches: tiles past the end of the slice read
+    // as zeros through the buffer bounds check.
     static_assert(DEPTH % 2 == 0, "the LDS double buffer is indexed by the ring slot");
+    constexpr int kSlotLoads = XPER + Src::kLoads;
     typename Src::Tile w[DEPTH];
     XRegs xr[DEPTH];
     const int w_off = Src::lane_offset(lane, kt0, K);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
-        // keep the request order of the loop body (activations, then weights, slot by slot), so the
-        // outstanding-load bookkeeping at the loop head is the same on entry and on the back edge
-        xr[d] = x_fetch(d);
-        __builtin_amdgcn_sched_barrier(0);
-        w[d] = Src::load(w_rsrc, w_off + d * Src::kTileStride);
-        __builtin_amdgcn_sched_barrier(0);
+        x_issue(xr[d], d);
+        Src::issue(w[d], w_rsrc, w_off + d * Src::kTileStride);
     }
     for (int i = 0; i < T; i += DEPTH) {
 #pragma unroll
         for (int d = 0; d < DEPTH; ++d) {
+            wait_loads<(DEPTH - 1) * kSlotLoads>();
+            x_pin(xr[d]);
+            Src::pin_tile(w[d]);
             x_commit(xr[d], d & 1);
             __syncthreads();
             compute(w[d], d & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            xr[d] = x_fetch(i + d + DEPTH);
-            __builtin_amdgcn_sched_barrier(0);
-            w[d] = Src::load(w_rsrc, w_off + (i + d + DEPTH) * Src::kTileStride);
-            __builtin_amdgcn_sched_barrier(0);
+            x_issue(xr[d], i + d + DEPTH);
+            Src::issue(w[d], w_rsrc, w_off + (i + d + DEPTH) * Src::kTileStride);
         }
+    }
+    // drain: the look-ahead loads of the last DEPTH tiles (all out of range, zeros) must land before
+    // their registers are reused
+    wait_loads<0>();
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+        x_pin(xr[d]);
+        Src::pin_tile(w[d]);
     }
 
     // ---- epilogue.  Lane L holds, per n-tile, rows 4*(L/16)+i (i=0..3) of token column L%16.

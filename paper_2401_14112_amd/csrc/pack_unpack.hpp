@@ -128,7 +128,10 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
     const int64_t row_tile = tile / KT, kt = tile % KT;
     const int r = lane & 15, q = lane >> 4;
     const rsrc_t rs = PackedFp6Source::slice_rsrc(packed, row_tile, (int)kt, (int)kt + 1, KT, K);
-    const PackedFp6Source::Tile t = PackedFp6Source::load(rs, PackedFp6Source::lane_offset(lane, 0, K));
+    PackedFp6Source::Tile t;
+    PackedFp6Source::issue(t, rs, PackedFp6Source::lane_offset(lane, 0, K));
+    wait_loads<0>();
+    PackedFp6Source::pin_tile(t);
     const float scale = (float)scales[row_tile * kTileRows + r];
     half_t *out = W_out + (row_tile * kTileRows + r) * K + kt * kTileK + q * 8;
     half8_t frag[8];

@@ -130,6 +130,14 @@ fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_
  */
 void fp6_tuning_set_split_k(int split_k);
 
+/*
+ * Tuning hook for benchmarks: force the per-wave tile of the kernel used for N > 32
+ * (16-row tiles per wave in {2, 4}, 16-token tiles per wave in {4, 8}); any other
+ * pair restores the automatic choice.  Process-wide; affects the workspace size
+ * queries as well.
+ */
+void fp6_tuning_set_tile(int row_tiles_per_wave, int token_tiles_per_wave);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     fp6_packed_bytes,
     fp6_quantize_pack,
     fp6_tuning_set_split_k,
+    fp6_tuning_set_tile,
     fp6_unpack,
     fp6_workspace_init,
     fp16_linear,

@@ -57,6 +57,8 @@ def load_library():
     L.fp16_linear.argtypes = [vp, vp, vp, i64, i64, i64, vp, sz, vp]
     L.fp6_tuning_set_split_k.restype = None
     L.fp6_tuning_set_split_k.argtypes = [ci]
+    L.fp6_tuning_set_tile.restype = None
+    L.fp6_tuning_set_tile.argtypes = [ci, ci]
     _lib = L
     return L
 
@@ -98,6 +100,10 @@ def fp16_linear_workspace_bytes(M: int, N: int, K: int) -> int:
 
 def fp6_tuning_set_split_k(split_k: int) -> None:
     load_library().fp6_tuning_set_split_k(int(split_k))
+
+
+def fp6_tuning_set_tile(row_tiles_per_wave: int, token_tiles_per_wave: int) -> None:
+    load_library().fp6_tuning_set_tile(int(row_tiles_per_wave), int(token_tiles_per_wave))
 
 
 def fp6_workspace_init(workspace: torch.Tensor) -> None:

@@ -10,7 +10,7 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libfp6_mi355x.so"
 SOURCES = ["fp6_api.hip"]
-HEADERS = ["fp6_device.hpp", "linear_stream.hpp", "pack_unpack.hpp"]
+HEADERS = ["fp6_device.hpp", "linear_stream.hpp", "linear_tiled.hpp", "pack_unpack.hpp"]
 
 
 def hipcc() -> str:

@@ -144,6 +144,7 @@ struct PackedFp6Source {
         u32x4 p0, p1, p2;
     };
     static constexpr bool kHasScale = true;
+    static constexpr bool kWideTile = true;  // four row tiles x two buffers fit in the register file
     static constexpr int kLoads = 3;
     static constexpr int kTileStride = kTileBytes;  // bytes from one k-tile of the slice to the next
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
@@ -178,6 +179,7 @@ struct PlainFp16Source {
         u32x4 v[8];
     };
     static constexpr bool kHasScale = false;
+    static constexpr bool kWideTile = false;
     static constexpr int kLoads = 8;
     static constexpr int kTileStride = kTileK * 2;
     // the four lane groups of a row read four adjacent 16-byte pieces (64 contiguous bytes per row

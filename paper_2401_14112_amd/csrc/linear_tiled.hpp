@@ -1,0 +1,236 @@
+// Tiled linear-layer kernel for prefill-sized token counts (N >= 64), where the layer is bound by
+// the matrix cores (Section 7.1 of the paper: all kernels become compute-bound beyond batch 128).
+//
+// A block is WAVES waves stacked along M; every wave owns RT 16-row tiles and NT 16-token tiles,
+// i.e. a (16*RT) x (16*NT) piece of Y held in fp32 accumulators.  Per 256-column k-tile a wave
+// fetches its RT packed weight tiles straight into registers (they are used by this wave only),
+// unpacks each run of 32 columns once and feeds it to NT MFMAs, so the shift/mask work is
+// amortised over NT matrix instructions; every activation fragment read from LDS is reused by RT
+// MFMAs.  The activation tile (16*NT tokens x 256 columns) is shared by the block: it is staged in
+// LDS in B-fragment order and double-buffered.
+//
+// Pipeline (one k-tile of look-ahead, enough because a k-tile is ~RT*NT*8 MFMAs of work): at the top
+// of iteration t everything requested for tile t has arrived; the activation pieces are written to
+// LDS buffer t&1, one barrier, then the requests for tile t+1 are issued (activations first, then
+// the weights into the other register buffer) and tile t is computed.
+//
+// Split-K and the epilogue are those of the streaming kernel.
+#pragma once
+#include "fp6_device.hpp"
+
+namespace fp6 {
+
+template <class Src, int RT, int NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void linear_tiled_kernel(
+    const void *__restrict__ weights, const half_t *__restrict__ scales, const half_t *__restrict__ X,
+    half_t *__restrict__ Y, int M, int N, int K, int S, int n_blocks, float4_t *__restrict__ partials,
+    int *__restrict__ counters)
+{
+    constexpr int THREADS = WAVES * 64;
+    constexpr int XCHUNKS = NT * 512;  // 16-byte pieces of one activation tile
+    static_assert(XCHUNKS % THREADS == 0, "activation tile must split evenly over the block");
+    constexpr int XPER = XCHUNKS / THREADS;
+
+    extern __shared__ u32x4 xs_dyn[];  // [2][XCHUNKS]
+    __shared__ int s_is_last;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int KT = K / kTileK;
+    const int n_row_tiles = M / kTileRows;
+    // block -> (token block, k slice, row block): consecutive blocks (one per XCD) differ in token
+    // block / slice, so the blocks of one XCD share the same activation tile in its L2
+    const int combos = n_blocks * S;
+    const int combo = blockIdx.x % combos;
+    const int row_block = blockIdx.x / combos;
+    const int n_block = combo % n_blocks;
+    const int split = combo / n_blocks;
+    const int row_tile0 = (row_block * WAVES + wave) * RT;
+    const int col0 = n_block * NT * 16;
+    const int kt0 = (int)(((unsigned)KT * (unsigned)split) / (unsigned)S);
+    const int kt1 = (int)(((unsigned)KT * (unsigned)(split + 1)) / (unsigned)S);
+    const int n_valid = kt1 - kt0;
+
+    rsrc_t w_rsrc[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        const int rt = row_tile0 + r;
+        w_rsrc[r] = Src::slice_rsrc(weights, rt < n_row_tiles ? rt : n_row_tiles - 1, kt0, kt1, KT, K);
+    }
+    const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
+
+    // activation staging: piece c = nt*512 + f*64 + q*16 + n  <->  X[col0 + nt*16 + n][k_tile*256 + k_offset(f,q) ..+8]
+    int x_off[XPER];
+#pragma unroll
+    for (int i = 0; i < XPER; ++i) {
+        const int c = tid + i * THREADS;
+        const int n = c & 15, q = (c >> 4) & 3, f = (c >> 6) & 7, nt = c >> 9;
+        const int col = col0 + nt * 16 + n;
+        x_off[i] = col < N ? (col * K + kt0 * kTileK + Src::k_offset(f, q)) * 2 : kOutOfRange;
+    }
+    u32x4 xr[XPER];
+    auto x_issue = [&](int t) {
+#pragma unroll
+        for (int i = 0; i < XPER; ++i) {
+            const int off = (t < n_valid && x_off[i] != kOutOfRange) ? x_off[i] + t * (kTileK * 2) : kOutOfRange;
+            xr[i] = issue_load_b128<0, false>(x_rsrc, off);
+        }
+    };
+
+    float4_t acc[RT][NT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            acc[r][nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
+
+    auto mma_run = [&](const half8_t (&a)[RT], const u32x4 *xbuf, int f) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const half8_t b = bit_cast<half8_t>(xbuf[nt * 512 + f * 64 + lane]);
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+                acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[r], b, acc[r][nt], 0, 0, 0);
+        }
+    };
+    auto compute = [&](const typename Src::Tile (&t)[RT], const u32x4 *xbuf) {
+        half8_t a_even[RT], a_odd[RT];
+#define FP6_TILED_STEP(G)                                                   \
+    _Pragma("unroll") for (int r = 0; r < RT; ++r)                          \
+        Src::template fragments<G>(t[r], a_even[r], a_odd[r]);              \
+    mma_run(a_even, xbuf, 2 * G);                                           \
+    mma_run(a_odd, xbuf, 2 * G + 1);
+        FP6_TILED_STEP(0)
+        FP6_TILED_STEP(1)
+        FP6_TILED_STEP(2)
+        FP6_TILED_STEP(3)
+#undef FP6_TILED_STEP
+    };
+
+    typename Src::Tile w[2][RT];
+    const int w_off = Src::lane_offset(lane, kt0, K);
+    auto w_issue = [&](typename Src::Tile (&dst)[RT], int t) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+            Src::issue(dst[r], w_rsrc[r], w_off + t * Src::kTileStride);
+    };
+    auto arrive = [&](typename Src::Tile (&dst)[RT]) {
+        wait_loads<0>();
+#pragma unroll
+        for (int i = 0; i < XPER; ++i)
+            pin(xr[i]);
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+            Src::pin_tile(dst[r]);
+    };
+    auto x_commit = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < XPER; ++i)
+            xs_dyn[buf * XCHUNKS + tid + i * THREADS] = xr[i];
+    };
+
+    x_issue(0);
+    w_issue(w[0], 0);
+    // two tiles per trip so that the register buffer index is static; tiles past the slice are zeros
+    for (int t = 0; t < n_valid; t += 2) {
+        arrive(w[0]);
+        x_commit(0);
+        __syncthreads();
+        x_issue(t + 1);
+        w_issue(w[1], t + 1);
+        compute(w[0], xs_dyn);
+
+        arrive(w[1]);
+        x_commit(1);
+        __syncthreads();
+        x_issue(t + 2);
+        w_issue(w[0], t + 2);
+        compute(w[1], xs_dyn + XCHUNKS);
+    }
+    arrive(w[0]);  // the last look-ahead requests (out of range: zeros) must land before the registers die
+
+    // ---- epilogue.  Lane L holds, per (row tile, token tile), rows 4*(L/16)+i of token column L%16.
+    const int n_in_tile = lane & 15;
+    const int n_tiles_total = n_blocks * NT;
+    auto finish = [&](const float4_t (&sum)[NT], int r) {
+        const int m0 = (row_tile0 + r) * kTileRows + 4 * (lane >> 4);
+        float sc[4] = {1.f, 1.f, 1.f, 1.f};
+        if (Src::kHasScale) {
+            const half4_t s4 = *reinterpret_cast<const half4_t *>(scales + m0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                sc[i] = (float)s4[i];
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int col = col0 + nt * 16 + n_in_tile;
+            if (col < N) {
+                half4_t y;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    y[i] = (half_t)(sum[nt][i] * sc[i]);
+                *reinterpret_cast<half4_t *>(Y + (int64_t)col * M + m0) = y;
+            }
+        }
+    };
+
+    if (S == 1) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+            if (row_tile0 + r < n_row_tiles)
+                finish(acc[r], r);
+        return;
+    }
+
+    // split-K: see linear_stream.hpp for the protocol (device-scope accesses, ordered sum)
+    float *pf = reinterpret_cast<float *>(partials);
+    auto partial_ptr = [&](int s, int r, int nt) {
+        return pf + ((((int64_t)s * n_row_tiles + (row_tile0 + r)) * n_tiles_total + (n_block * NT + nt)) * 4) * 64 + lane;
+    };
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+        if (row_tile0 + r < n_row_tiles) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (col0 + nt * 16 + n_in_tile < N) {
+                    float *dst = partial_ptr(split, r, nt);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        __hip_atomic_store(dst + i * 64, acc[r][nt][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+        }
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's partial stores are done
+    __syncthreads();
+    const int counter_index = row_block * n_blocks + n_block;
+    if (tid == 0) {
+        const int arrived = __hip_atomic_fetch_add(&counters[counter_index], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_is_last = (arrived == S - 1);
+    }
+    __syncthreads();
+    if (!s_is_last)
+        return;
+    for (int r = 0; r < RT; ++r) {
+        if (row_tile0 + r >= n_row_tiles)
+            break;
+        float4_t sum[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            sum[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < S; ++s) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                if (col0 + nt * 16 + n_in_tile < N) {
+                    const float *src = partial_ptr(s, r, nt);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        sum[nt][i] += __hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+        }
+        finish(sum, r);
+    }
+    if (tid == 0)
+        counters[counter_index] = 0;  // re-arm for the next call on this workspace
+}
+
+}  // namespace fp6

@@ -253,6 +253,64 @@ def test_fp16_linear(pkg, oracle, N):
     _check_linear(_np16(Y), oracle.linear_f16(W.numpy(), X.numpy()), "fp16 N=%d" % N)
 
 
+# ------------------------------------------------------------------ tiled kernel (N > 32)
+@pytest.mark.parametrize("rt,nt", [(0, 0), (2, 4), (4, 4), (2, 8), (4, 8)])
+@pytest.mark.parametrize("N,split", [(33, 1), (64, 0), (100, 2), (128, 3), (257, 0)])
+def test_linear_tiled(pkg, oracle, rt, nt, N, split):
+    M, K = 272, 2816         # 17 row tiles (ragged against every block height), 11 k-tiles
+    _say("tiled linear rt=%d nt=%d N=%d split=%d" % (rt, nt, N, split))
+    pkg.fp6_tuning_set_tile(rt, nt)
+    try:
+        Y, Y_ref = _linear_case(pkg, oracle, M, K, N, seed=N + rt, split=split)
+    finally:
+        pkg.fp6_tuning_set_tile(0, 0)
+    _check_linear(Y, Y_ref, "tiled rt=%d nt=%d N=%d" % (rt, nt, N))
+
+
+@pytest.mark.parametrize("rt,nt", [(0, 0), (2, 4), (4, 4), (2, 8)])
+@pytest.mark.parametrize("N,split", [(64, 0), (130, 2)])
+def test_fp16_linear_tiled(pkg, oracle, rt, nt, N, split):
+    M, K = 272, 2816
+    _say("tiled fp16_linear rt=%d nt=%d N=%d split=%d" % (rt, nt, N, split))
+    W = workloads.make_weights(M, K, 7)
+    X = workloads.make_activations(N, K, 7)
+    pkg.fp6_tuning_set_tile(rt, nt)
+    pkg.fp6_tuning_set_split_k(split)
+    try:
+        Y = pkg.fp16_linear(W.cuda(), X.cuda())
+        torch.cuda.synchronize()
+    finally:
+        pkg.fp6_tuning_set_tile(0, 0)
+        pkg.fp6_tuning_set_split_k(0)
+    _check_linear(_np16(Y), oracle.linear_f16(W.numpy(), X.numpy()), "tiled fp16 N=%d" % N)
+
+
+def test_tiled_deterministic_and_exact_cases(pkg, oracle):
+    _say("tiled: determinism and subnormal codes")
+    M, K, N = 256, 4096, 96
+    W = workloads.make_weights(M, K, 3).cuda()
+    X = workloads.make_activations(N, K, 3).cuda()
+    packed, scales = pkg.fp6_quantize_pack(W)
+    pkg.fp6_tuning_set_split_k(4)
+    try:
+        nbytes = pkg.fp6_linear_workspace_bytes(M, N, K)
+        assert nbytes > 0
+        ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        outs = [pkg.fp6_linear(packed, scales, X, M, K, workspace=ws).clone() for _ in range(4)]
+        torch.cuda.synchronize()
+    finally:
+        pkg.fp6_tuning_set_split_k(0)
+    for o in outs[1:]:
+        assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16))
+    _check_linear(_np16(outs[0]), oracle.linear(_np16(packed), _np16(scales), _np16(X), M, K), "tiled reuse")
+    codes = np.full((M, K), 0b000011, dtype=np.uint8)
+    codes[:, ::2] = 0b100001
+    Y2 = pkg.fp6_linear(torch.from_numpy(oracle.pack(codes)).cuda(), torch.ones(M, dtype=torch.float16).cuda(),
+                        torch.ones((N, K), dtype=torch.float16).cuda(), M, K)
+    torch.cuda.synchronize()
+    assert np.all(_np16(Y2).astype(np.float64) == (K // 2) * (3 / 16 - 1 / 16))
+
+
 # ------------------------------------------------------------------ full-size layer, sampled rows
 def _sampled_row_tiles(M, count, seed):
     rng = np.random.default_rng(seed)
@@ -280,7 +338,7 @@ def test_full_size_layer_sampled(pkg, oracle, shape):
     assert np.array_equal(_np16(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
     assert np.array_equal(got_packed, ref_packed)
     del W
-    for N in (1, 8, 32):
+    for N in (1, 8, 32, 64, 512):
         _say("  linear N=%d" % N)
         X = workloads.make_activations(N, K, seed=N, device="cuda")
         Y = pkg.fp6_linear(packed, scales, X, M, K)

@@ -131,12 +131,12 @@ fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_
 void fp6_tuning_set_split_k(int split_k);
 
 /*
- * Tuning hook for benchmarks: force the per-wave tile of the kernel used for N > 32
- * (16-row tiles per wave in {2, 4}, 16-token tiles per wave in {4, 8}); any other
- * pair restores the automatic choice.  Process-wide; affects the workspace size
- * queries as well.
+ * Tuning hook for benchmarks: force the block tile of the kernel used for N > 32:
+ * block_rows in {128, 256} output channels x block_tokens in {64, 128} tokens; any
+ * other pair restores the automatic choice.  fp16_linear uses 128 rows where 256 is
+ * asked for.  Process-wide; affects the workspace size queries as well.
  */
-void fp6_tuning_set_tile(int row_tiles_per_wave, int token_tiles_per_wave);
+void fp6_tuning_set_tile(int block_rows, int block_tokens);
 
 #ifdef __cplusplus
 }

@@ -102,8 +102,8 @@ def fp6_tuning_set_split_k(split_k: int) -> None:
     load_library().fp6_tuning_set_split_k(int(split_k))
 
 
-def fp6_tuning_set_tile(row_tiles_per_wave: int, token_tiles_per_wave: int) -> None:
-    load_library().fp6_tuning_set_tile(int(row_tiles_per_wave), int(token_tiles_per_wave))
+def fp6_tuning_set_tile(block_rows: int, block_tokens: int) -> None:
+    load_library().fp6_tuning_set_tile(int(block_rows), int(block_tokens))
 
 
 def fp6_workspace_init(workspace: torch.Tensor) -> None:

@@ -27,7 +27,7 @@ def build_library(verbose: bool = False, extra_flags=()) -> Path:
         hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
         # packed-fp32 VALU forms are kept out of the generated code on this target
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-        "-Wall", "-Wno-unused-function",
+        "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage",
         *extra_flags,
         "-I", str(PKG.parent / "include"),
         *[str(CSRC / s) for s in SOURCES],
@@ -36,13 +36,29 @@ def build_library(verbose: bool = False, extra_flags=()) -> Path:
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
+    lines = r.stdout.splitlines()
+    out = "\n".join(l for l in lines if "packed-fp32-ops" not in l and "kernel-resource-usage" not in l)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
+    check_no_scratch(lines)
     if verbose and out.strip():
         print(out)
     os.replace(tmp, LIB)
     return LIB
+
+
+def check_no_scratch(remarks) -> None:
+    """The pipelined kernels issue loads from inline assembly and rely on the loaded registers staying
+    where they are until the explicit wait; a register spilled to scratch in between would save stale
+    data.  Refuse a build in which any kernel of the library needs scratch memory."""
+    name = None
+    for line in remarks:
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif "ScratchSize [bytes/lane]:" in line:
+            size = int(line.split("ScratchSize [bytes/lane]:")[1].split()[0])
+            if size != 0:
+                raise RuntimeError("kernel %s spills %d bytes/lane to scratch; reduce its register pressure" % (name, size))
 
 
 def is_stale() -> bool:

@@ -65,13 +65,23 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K)
 }
 
 // ---- tiled kernel (prefill-sized N) -----------------------------------------
-constexpr int kTiledWaves = 4;
 constexpr int kStreamMaxN = 32;  // token counts up to this use the streaming kernel
 
-std::atomic<int> g_forced_tile{0};  // 0 = automatic, else RT*16 + NT (tuning hook)
+// Block shapes offered by the tiled kernel: {RT, NT, WM, WN}; block = (16*RT*WM) rows x (16*NT*WN) tokens.
+struct TileShape {
+    int rt, nt, wm, wn;
+    int rows() const { return 16 * rt * wm; }
+    int tokens() const { return 16 * nt * wn; }
+};
+constexpr TileShape kTile256x128{4, 4, 4, 2};
+constexpr TileShape kTile128x128{2, 4, 4, 2};
+constexpr TileShape kTile256x64{4, 4, 4, 1};
+constexpr TileShape kTile128x64{2, 4, 4, 1};
+
+std::atomic<int> g_forced_tile{0};  // 0 = automatic, else rows * 1024 + tokens (tuning hook)
 
 struct TiledPlan {
-    int rt, nt;      // 16-row tiles and 16-token tiles per wave
+    TileShape tile;
     int split;
     int row_blocks, n_blocks;
     size_t counter_bytes, partial_bytes;
@@ -79,26 +89,23 @@ struct TiledPlan {
     size_t total_bytes() const { return split > 1 ? counter_bytes + partial_bytes : 0; }
 };
 
-TiledPlan plan_tiled(int64_t M, int64_t N, int64_t K, bool wide_tile_ok)
+TiledPlan plan_tiled(int64_t M, int64_t N, int64_t K, bool tall_tile_ok)
 {
     TiledPlan p;
     const int64_t row_tiles = M / kTileRows;
     const int64_t KT = K / kTileK;
     const int forced = g_forced_tile.load(std::memory_order_relaxed);
-    if (forced > 0) {
-        p.rt = forced / 16;
-        p.nt = forced % 16;
-    } else if (N <= 64) {
-        p.rt = 2;
-        p.nt = 4;
-    } else {
-        p.rt = 4;
-        p.nt = 8;
-    }
-    if (p.rt == 4 && p.nt == 8 && !wide_tile_ok)
-        p.rt = 2;
-    p.row_blocks = (int)((row_tiles + kTiledWaves * p.rt - 1) / (kTiledWaves * p.rt));
-    p.n_blocks = (int)((N + 16 * p.nt - 1) / (16 * p.nt));
+    const int rows = forced / 1024, tokens = forced % 1024;
+    if (forced > 0)
+        p.tile = rows == 256 ? (tokens == 128 ? kTile256x128 : kTile256x64) : (tokens == 128 ? kTile128x128 : kTile128x64);
+    else if (N <= 64)
+        p.tile = kTile128x64;
+    else
+        p.tile = kTile256x128;
+    if (p.tile.rt == 4 && !tall_tile_ok)  // this weight source does not fit four row tiles per wave in registers
+        p.tile.rt = 2;
+    p.row_blocks = (int)((M + p.tile.rows() - 1) / p.tile.rows());
+    p.n_blocks = (int)((N + p.tile.tokens() - 1) / p.tile.tokens());
     int64_t s = g_forced_split.load(std::memory_order_relaxed);
     if (s <= 0)
         s = 256 / ((int64_t)p.row_blocks * p.n_blocks);  // one block per CU
@@ -110,17 +117,18 @@ TiledPlan plan_tiled(int64_t M, int64_t N, int64_t K, bool wide_tile_ok)
     if (s < 1)
         s = 1;
     p.split = (int)s;
+    const int bnt = p.tile.nt * p.tile.wn;
     p.counter_bytes = (((size_t)p.row_blocks * p.n_blocks * sizeof(int)) + 255) / 256 * 256;
-    p.partial_bytes = (size_t)p.split * (size_t)row_tiles * (size_t)p.n_blocks * p.nt * 64 * sizeof(float4_t);
-    p.lds_bytes = (size_t)2 * p.nt * 512 * 16;
+    p.partial_bytes = (size_t)p.split * (size_t)row_tiles * (size_t)p.n_blocks * bnt * 64 * sizeof(float4_t);
+    p.lds_bytes = (size_t)2 * bnt * 512 * 16;
     return p;
 }
 
-template <class Src, int RT, int NT>
+template <class Src, int RT, int NT, int WM, int WN>
 fp6_status launch_tiled_cfg(const TiledPlan &p, const void *weights, const void *scales, const void *X, void *Y,
                             int64_t M, int64_t N, int64_t K, float4_t *partials, int *counters, hipStream_t stream)
 {
-    auto kernel = linear_tiled_kernel<Src, RT, NT, kTiledWaves>;
+    auto kernel = linear_tiled_kernel<Src, RT, NT, WM, WN>;
     static bool lds_ok = false;  // per instantiation: allow more than 64 KB of dynamic LDS
     if (!lds_ok) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -128,7 +136,7 @@ fp6_status launch_tiled_cfg(const TiledPlan &p, const void *weights, const void 
             return FP6_ERR_HIP;
         lds_ok = true;
     }
-    const dim3 grid((unsigned)(p.row_blocks * p.n_blocks * p.split)), block(kTiledWaves * 64);
+    const dim3 grid((unsigned)(p.row_blocks * p.n_blocks * p.split)), block(WM * WN * 64);
     hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, stream, weights, static_cast<const half_t *>(scales),
                        static_cast<const half_t *>(X), static_cast<half_t *>(Y), (int)M, (int)N, (int)K, p.split,
                        p.n_blocks, partials, counters);
@@ -139,7 +147,7 @@ template <class Src>
 fp6_status launch_tiled(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
                         int64_t K, void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
-    const TiledPlan p = plan_tiled(M, N, K, Src::kWideTile);
+    const TiledPlan p = plan_tiled(M, N, K, Src::kTallTile);
     if ((uint64_t)N * (uint64_t)K * 2u >= (1ull << 31))
         return FP6_ERR_SHAPE;  // activations are addressed with 32-bit buffer offsets
     if (p.total_bytes() > 0) {
@@ -151,18 +159,18 @@ fp6_status launch_tiled(const void *weights, const void *scales, const void *X, 
     int *counters = static_cast<int *>(workspace);
     float4_t *partials =
         p.total_bytes() ? reinterpret_cast<float4_t *>(static_cast<uint8_t *>(workspace) + p.counter_bytes) : nullptr;
-#define FP6_TILED_CASE(RT_, NT_)                                                                                  \
-    if (p.rt == RT_ && p.nt == NT_)                                                                               \
-        return launch_tiled_cfg<Src, RT_, NT_>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
-    FP6_TILED_CASE(2, 4)
-    FP6_TILED_CASE(4, 4)
-    FP6_TILED_CASE(2, 8)
-    if constexpr (!Src::kWideTile)
-        return FP6_ERR_SHAPE;  // plan_tiled never picks 4 x 8 for a source whose tiles do not fit in registers
-    else
-        FP6_TILED_CASE(4, 8)
+    const TileShape &t = p.tile;
+#define FP6_TILED_CASE(RT_, NT_, WM_, WN_)                                                                        \
+    if (t.rt == RT_ && t.nt == NT_ && t.wm == WM_ && t.wn == WN_)                                                 \
+        return launch_tiled_cfg<Src, RT_, NT_, WM_, WN_>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
+    FP6_TILED_CASE(2, 4, 4, 2)
+    FP6_TILED_CASE(2, 4, 4, 1)
+    if constexpr (Src::kTallTile) {
+        FP6_TILED_CASE(4, 4, 4, 2)
+        FP6_TILED_CASE(4, 4, 4, 1)
+    }
 #undef FP6_TILED_CASE
-    return FP6_ERR_SHAPE;
+    return FP6_ERR_SHAPE;  // not reached: plan_tiled only picks the shapes above
 }
 
 template <class Src>
@@ -226,7 +234,7 @@ size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
     if (!shape_ok(M, K) || N <= 0)
         return 0;
     return N <= kStreamMaxN ? plan_stream(M, N, K).total_bytes()
-                            : plan_tiled(M, N, K, PackedFp6Source::kWideTile).total_bytes();
+                            : plan_tiled(M, N, K, PackedFp6Source::kTallTile).total_bytes();
 }
 
 size_t fp16_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
@@ -234,16 +242,15 @@ size_t fp16_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
     if (!shape_ok(M, K) || N <= 0)
         return 0;
     return N <= kStreamMaxN ? plan_stream(M, N, K).total_bytes()
-                            : plan_tiled(M, N, K, PlainFp16Source::kWideTile).total_bytes();
+                            : plan_tiled(M, N, K, PlainFp16Source::kTallTile).total_bytes();
 }
 
 void fp6_tuning_set_split_k(int split_k) { g_forced_split.store(split_k < 0 ? 0 : split_k); }
 
-void fp6_tuning_set_tile(int row_tiles_per_wave, int token_tiles_per_wave)
+void fp6_tuning_set_tile(int block_rows, int block_tokens)
 {
-    const int rt = row_tiles_per_wave, nt = token_tiles_per_wave;
-    const bool known = (rt == 2 || rt == 4) && (nt == 4 || nt == 8);
-    g_forced_tile.store(known ? rt * 16 + nt : 0);
+    const bool known = (block_rows == 128 || block_rows == 256) && (block_tokens == 64 || block_tokens == 128);
+    g_forced_tile.store(known ? block_rows * 1024 + block_tokens : 0);
 }
 
 fp6_status fp6_workspace_init(void *workspace, size_t workspace_bytes, void *stream)

@@ -130,6 +130,38 @@ __device__ __forceinline__ void wait_loads()
 
 __device__ __forceinline__ void pin(u32x4 &v) { asm volatile("" : "+v"(v)); }
 
+// Global -> LDS copy without passing through registers: lane i's 16 bytes land at LDS byte address
+// lds_base + IMM + 16*i (lds_base wave-uniform, placed in M0).  Counted by vmcnt like any other load;
+// the data is in LDS once the wait has passed (other waves see it after the next barrier).
+template <int IMM>
+__device__ __forceinline__ void issue_load_to_lds_b128(rsrc_t rsrc, int lane_off, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen offset:%3 lds"
+                 : : "s"(lds_base), "v"(lane_off), "s"(rsrc), "n"(IMM) : "memory");
+}
+
+// ---- activation tile layout in LDS -----------------------------------------
+// One MFMA step needs, for its 16 token columns n and 4 lane groups q, the 8 consecutive columns
+// X[n][k_offset(f, q) ..+8]: 64 pieces of 16 bytes = 1 KB per (token tile, run).  Inside that 1 KB,
+// piece 4*n + ((q + swizzle(n)) & 3) holds (n, q).  Reading side: the MFMA lane (q, n) = (L/16, L%16)
+// reads that piece; the rotation by swizzle(n) spreads every group of 8 or 16 consecutive lanes over all
+// LDS banks.  Writing side: piece p is written by lane p of a 64-lane copy, which fetches row n = p/4,
+// group q = (p - swizzle(n)) & 3 - so each quad of lanes reads 64 contiguous bytes of one row of X
+// (the texture addresser merges such quads into one request; scattered 16-byte gathers are 4x slower).
+__device__ __forceinline__ int x_swizzle(int n) { return ((n >> 1) & 2) | (((n >> 1) ^ (n >> 3)) & 1); }
+// piece read by MFMA lane L
+__device__ __forceinline__ int x_piece_of_lane(int L)
+{
+    const int n = L & 15, q = L >> 4;
+    return 4 * n + ((q + x_swizzle(n)) & 3);
+}
+// (token row, lane group) fetched by copy lane p
+__device__ __forceinline__ void x_source_of_piece(int p, int &n, int &q)
+{
+    n = (p >> 2) & 15;
+    q = (p - x_swizzle(n)) & 3;
+}
+
 // ---- weight sources -------------------------------------------------------
 // A source knows how one lane fetches its share of a 16 x 256 weight tile and how
 // to turn it into the eight A fragments (one per run) of the tile.  k_offset(f, q)
@@ -144,7 +176,7 @@ struct PackedFp6Source {
         u32x4 p0, p1, p2;
     };
     static constexpr bool kHasScale = true;
-    static constexpr bool kWideTile = true;  // four row tiles x two buffers fit in the register file
+    static constexpr bool kTallTile = false;  // four row tiles per wave x two buffers do not fit next to the accumulators
     static constexpr int kLoads = 3;
     static constexpr int kTileStride = kTileBytes;  // bytes from one k-tile of the slice to the next
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
@@ -179,7 +211,7 @@ struct PlainFp16Source {
         u32x4 v[8];
     };
     static constexpr bool kHasScale = false;
-    static constexpr bool kWideTile = false;
+    static constexpr bool kTallTile = false;
     static constexpr int kLoads = 8;
     static constexpr int kTileStride = kTileK * 2;
     // the four lane groups of a row read four adjacent 16-byte pieces (64 contiguous bytes per row

@@ -52,8 +52,9 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     const rsrc_t w_rsrc = Src::slice_rsrc(weights, active ? row_tile : n_row_tiles - 1, kt0, kt1, KT, K);
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
-    // ---- activation staging: piece c = nt*512 + f*64 + q*16 + n  <->  X[nt*16+n][k_tile*256 + k_offset(f,q) ..+8]
-    // Token columns >= N and k-tiles past the slice get an offset outside the buffer and read as zeros.
+    // ---- activation staging: piece c = nt*512 + f*64 + p holds X[nt*16+n][k_tile*256 + k_offset(f,q) ..+8]
+    // for the (n, q) given by x_source_of_piece(p).  Token columns >= N and k-tiles past the slice get an
+    // offset outside the buffer and read as zeros.
     struct XRegs {
         u32x4 v[XPER];
     };
@@ -61,7 +62,9 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
 #pragma unroll
     for (int i = 0; i < XPER; ++i) {
         const int c = tid + i * THREADS;
-        const int n = c & 15, q = (c >> 4) & 3, f = (c >> 6) & 7, nt = c >> 9;
+        const int f = (c >> 6) & 7, nt = c >> 9;
+        int n, q;
+        x_source_of_piece(c & 63, n, q);
         const int col = nt * 16 + n;
         x_off[i] = col < N ? (col * K + kt0 * kTileK + Src::k_offset(f, q)) * 2 : kOutOfRange;
     }
@@ -83,6 +86,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
             xs[buf][tid + i * THREADS] = r.v[i];
     };
 
+    const int b_piece = x_piece_of_lane(lane);
     float4_t acc[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -91,12 +95,12 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     auto mma_pair = [&](const half8_t &a_even, const half8_t &a_odd, int buf, int g) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            half8_t b = bit_cast<half8_t>(xs[buf][nt * 512 + (2 * g) * 64 + lane]);
+            half8_t b = bit_cast<half8_t>(xs[buf][nt * 512 + (2 * g) * 64 + b_piece]);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_even, b, acc[nt], 0, 0, 0);
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            half8_t b = bit_cast<half8_t>(xs[buf][nt * 512 + (2 * g + 1) * 64 + lane]);
+            half8_t b = bit_cast<half8_t>(xs[buf][nt * 512 + (2 * g + 1) * 64 + b_piece]);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_odd, b, acc[nt], 0, 0, 0);
         }
     };

@@ -1,35 +1,41 @@
-// Tiled linear-layer kernel for prefill-sized token counts (N >= 64), where the layer is bound by
+// Tiled linear-layer kernel for prefill-sized token counts (N > 32), where the layer is bound by
 // the matrix cores (Section 7.1 of the paper: all kernels become compute-bound beyond batch 128).
 //
-// A block is WAVES waves stacked along M; every wave owns RT 16-row tiles and NT 16-token tiles,
-// i.e. a (16*RT) x (16*NT) piece of Y held in fp32 accumulators.  Per 256-column k-tile a wave
-// fetches its RT packed weight tiles straight into registers (they are used by this wave only),
-// unpacks each run of 32 columns once and feeds it to NT MFMAs, so the shift/mask work is
-// amortised over NT matrix instructions; every activation fragment read from LDS is reused by RT
-// MFMAs.  The activation tile (16*NT tokens x 256 columns) is shared by the block: it is staged in
-// LDS in B-fragment order and double-buffered.
+// A block is WM x WN waves; wave (wm, wn) owns RT 16-row tiles and NT 16-token tiles, i.e. a
+// (16*RT) x (16*NT) piece of Y held in fp32 accumulators; the block covers (16*RT*WM) rows and
+// (16*NT*WN) tokens.  Per 256-column k-tile a wave fetches its RT packed weight tiles straight into
+// registers, unpacks each run of 32 columns once and feeds it to NT MFMAs (the shift/mask work is
+// amortised over NT matrix instructions); every activation fragment read from LDS is reused by RT
+// MFMAs.  The activation tile (all tokens of the block x 256 columns) is shared by the block: it is
+// copied global -> LDS without passing through registers, already in B-fragment order (the 64 lanes
+// of one copy instruction fetch the 64 pieces that the 64 lanes of one MFMA will read), and is
+// double-buffered.
 //
-// Pipeline (one k-tile of look-ahead, enough because a k-tile is ~RT*NT*8 MFMAs of work): at the top
-// of iteration t everything requested for tile t has arrived; the activation pieces are written to
-// LDS buffer t&1, one barrier, then the requests for tile t+1 are issued (activations first, then
-// the weights into the other register buffer) and tile t is computed.
+// Pipeline (one k-tile of look-ahead, enough because a k-tile is RT*NT*8 MFMAs of work per wave and
+// two waves share a SIMD): at the top of iteration t the wave waits for everything it requested for
+// tile t, one barrier makes the whole activation tile visible (and guarantees that the other LDS
+// buffer is no longer being read), then the requests for tile t+1 are issued - activation copies
+// into the other LDS buffer, weights into the other register buffer - and tile t is computed.
 //
-// Split-K and the epilogue are those of the streaming kernel.
+// Split-K and the epilogue are those of the streaming kernel (linear_stream.hpp).
 #pragma once
 #include "fp6_device.hpp"
 
 namespace fp6 {
 
-template <class Src, int RT, int NT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void linear_tiled_kernel(
+template <class Src, int RT, int NT, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     const void *__restrict__ weights, const half_t *__restrict__ scales, const half_t *__restrict__ X,
     half_t *__restrict__ Y, int M, int N, int K, int S, int n_blocks, float4_t *__restrict__ partials,
     int *__restrict__ counters)
 {
-    constexpr int THREADS = WAVES * 64;
-    constexpr int XCHUNKS = NT * 512;  // 16-byte pieces of one activation tile
-    static_assert(XCHUNKS % THREADS == 0, "activation tile must split evenly over the block");
-    constexpr int XPER = XCHUNKS / THREADS;
+    constexpr int WAVES = WM * WN;
+    constexpr int BNT = WN * NT;             // 16-token tiles of the block
+    constexpr int XCHUNKS = BNT * 512;       // 16-byte pieces of one activation tile
+    constexpr int XBYTES = XCHUNKS * 16;
+    constexpr int COPIES = BNT * 8;          // copy instructions per activation tile (one per token tile and run)
+    static_assert(COPIES % WAVES == 0, "activation copies must split evenly over the waves");
+    constexpr int XPER = COPIES / WAVES;
 
     extern __shared__ u32x4 xs_dyn[];  // [2][XCHUNKS]
     __shared__ int s_is_last;
@@ -37,6 +43,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;
     const int KT = K / kTileK;
     const int n_row_tiles = M / kTileRows;
     // block -> (token block, k slice, row block): consecutive blocks (one per XCD) differ in token
@@ -46,8 +53,9 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_kernel(
     const int row_block = blockIdx.x / combos;
     const int n_block = combo % n_blocks;
     const int split = combo / n_blocks;
-    const int row_tile0 = (row_block * WAVES + wave) * RT;
-    const int col0 = n_block * NT * 16;
+    const int row_tile0 = (row_block * WM + wm) * RT;
+    const int block_col0 = n_block * BNT * 16;
+    const int col0 = block_col0 + wn * NT * 16;  // first token of this wave
     const int kt0 = (int)(((unsigned)KT * (unsigned)split) / (unsigned)S);
     const int kt1 = (int)(((unsigned)KT * (unsigned)(split + 1)) / (unsigned)S);
     const int n_valid = kt1 - kt0;
@@ -60,21 +68,25 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_kernel(
     }
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
-    // activation staging: piece c = nt*512 + f*64 + q*16 + n  <->  X[col0 + nt*16 + n][k_tile*256 + k_offset(f,q) ..+8]
-    int x_off[XPER];
-#pragma unroll
-    for (int i = 0; i < XPER; ++i) {
-        const int c = tid + i * THREADS;
-        const int n = c & 15, q = (c >> 4) & 3, f = (c >> 6) & 7, nt = c >> 9;
-        const int col = col0 + nt * 16 + n;
-        x_off[i] = col < N ? (col * K + kt0 * kTileK + Src::k_offset(f, q)) * 2 : kOutOfRange;
-    }
-    u32x4 xr[XPER];
-    auto x_issue = [&](int t) {
+    // Activation copies: copy j = wave + WAVES*i of a tile serves token tile nt = j/8 and run f = j%8;
+    // lane p of the copy fetches X[block_col0 + 16*nt + n][k0 + k_offset(f, q) ..+8] for the (n, q) that
+    // piece p of the 1 KB holds (see x_source_of_piece), and its 16 bytes land at piece 64*j + p.
+    int xq, xn;
+    x_source_of_piece(lane, xn, xq);
+    const int b_piece = x_piece_of_lane(lane);
+    // LDS byte address of the activation buffers (the low 32 bits of a shared-memory pointer)
+    const uint32_t xs_lds = (uint32_t)reinterpret_cast<uintptr_t>(xs_dyn);
+    auto x_issue = [&](int t, int buf) {
 #pragma unroll
         for (int i = 0; i < XPER; ++i) {
-            const int off = (t < n_valid && x_off[i] != kOutOfRange) ? x_off[i] + t * (kTileK * 2) : kOutOfRange;
-            xr[i] = issue_load_b128<0, false>(x_rsrc, off);
+            const int j = wave + WAVES * i;
+            const int nt = j >> 3, f = j & 7;
+            const int col = block_col0 + nt * 16 + xn;
+            const int off = (t < n_valid && col < N)
+                                ? (col * K + (kt0 + t) * kTileK + Src::k_offset(f, xq)) * 2
+                                : kOutOfRange;
+            const uint32_t lds_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(xs_lds + buf * XBYTES + j * 1024));
+            issue_load_to_lds_b128<0>(x_rsrc, off, lds_base);
         }
     };
 
@@ -85,26 +97,48 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_kernel(
         for (int nt = 0; nt < NT; ++nt)
             acc[r][nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
-    auto mma_run = [&](const half8_t (&a)[RT], const u32x4 *xbuf, int f) {
+    // One k-tile = 8 runs.  The B fragments of run f+1 are read from LDS before the MFMAs of run f are
+    // issued, and the A fragments of runs 2g+2, 2g+3 are unpacked while the MFMAs of runs 2g, 2g+1 execute,
+    // so neither the LDS latency nor the shift/mask work sits on the MFMA critical path.
+    auto load_b = [&](half8_t (&b)[NT], const u32x4 *xbuf, int f) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const half8_t b = bit_cast<half8_t>(xbuf[nt * 512 + f * 64 + lane]);
+        for (int nt = 0; nt < NT; ++nt)
+            b[nt] = bit_cast<half8_t>(xbuf[((wn * NT + nt) * 8 + f) * 64 + b_piece]);
+    };
+    auto mma_run = [&](const half8_t (&a)[RT], const half8_t (&b)[NT]) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int r = 0; r < RT; ++r)
-                acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[r], b, acc[r][nt], 0, 0, 0);
-        }
+                acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[r], b[nt], acc[r][nt], 0, 0, 0);
     };
     auto compute = [&](const typename Src::Tile (&t)[RT], const u32x4 *xbuf) {
-        half8_t a_even[RT], a_odd[RT];
-#define FP6_TILED_STEP(G)                                                   \
-    _Pragma("unroll") for (int r = 0; r < RT; ++r)                          \
-        Src::template fragments<G>(t[r], a_even[r], a_odd[r]);              \
-    mma_run(a_even, xbuf, 2 * G);                                           \
-    mma_run(a_odd, xbuf, 2 * G + 1);
-        FP6_TILED_STEP(0)
-        FP6_TILED_STEP(1)
-        FP6_TILED_STEP(2)
-        FP6_TILED_STEP(3)
+        half8_t a_even[2][RT], a_odd[2][RT];
+        half8_t b[2][NT];
+        load_b(b[0], xbuf, 0);
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+            Src::template fragments<0>(t[r], a_even[0][r], a_odd[0][r]);
+        // sched_barrier(0) pins the order "read next B fragments, then this run's MFMAs": without it the
+        // scheduler sinks the LDS reads next to their use and every MFMA group waits for LDS.
+#define FP6_TILED_STEP(G, NEXT)                                                      \
+    load_b(b[1], xbuf, 2 * G + 1);                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                               \
+    mma_run(a_even[G & 1], b[0]);                                                    \
+    if (G < 3) {                                                                     \
+        _Pragma("unroll") for (int r = 0; r < RT; ++r)                               \
+            Src::template fragments<NEXT>(t[r], a_even[(G + 1) & 1][r], a_odd[(G + 1) & 1][r]); \
+    }                                                                                \
+    __builtin_amdgcn_sched_barrier(0);                                               \
+    if (G < 3)                                                                       \
+        load_b(b[0], xbuf, 2 * G + 2);                                               \
+    __builtin_amdgcn_sched_barrier(0);                                               \
+    mma_run(a_odd[G & 1], b[1]);                                                     \
+    __builtin_amdgcn_sched_barrier(0);
+        FP6_TILED_STEP(0, 1)
+        FP6_TILED_STEP(1, 2)
+        FP6_TILED_STEP(2, 3)
+        FP6_TILED_STEP(3, 3)
 #undef FP6_TILED_STEP
     };
 
@@ -118,41 +152,31 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_kernel(
     auto arrive = [&](typename Src::Tile (&dst)[RT]) {
         wait_loads<0>();
 #pragma unroll
-        for (int i = 0; i < XPER; ++i)
-            pin(xr[i]);
-#pragma unroll
         for (int r = 0; r < RT; ++r)
             Src::pin_tile(dst[r]);
     };
-    auto x_commit = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < XPER; ++i)
-            xs_dyn[buf * XCHUNKS + tid + i * THREADS] = xr[i];
-    };
 
-    x_issue(0);
+    x_issue(0, 0);
     w_issue(w[0], 0);
-    // two tiles per trip so that the register buffer index is static; tiles past the slice are zeros
+    // two tiles per trip so that the register / LDS buffer index is static; tiles past the slice are zeros
     for (int t = 0; t < n_valid; t += 2) {
         arrive(w[0]);
-        x_commit(0);
         __syncthreads();
-        x_issue(t + 1);
+        x_issue(t + 1, 1);
         w_issue(w[1], t + 1);
         compute(w[0], xs_dyn);
 
         arrive(w[1]);
-        x_commit(1);
         __syncthreads();
-        x_issue(t + 2);
+        x_issue(t + 2, 0);
         w_issue(w[0], t + 2);
         compute(w[1], xs_dyn + XCHUNKS);
     }
-    arrive(w[0]);  // the last look-ahead requests (out of range: zeros) must land before the registers die
+    arrive(w[0]);  // the last look-ahead requests (out of range: zeros) must land before the block ends
 
     // ---- epilogue.  Lane L holds, per (row tile, token tile), rows 4*(L/16)+i of token column L%16.
     const int n_in_tile = lane & 15;
-    const int n_tiles_total = n_blocks * NT;
+    const int n_tiles_total = n_blocks * BNT;
     auto finish = [&](const float4_t (&sum)[NT], int r) {
         const int m0 = (row_tile0 + r) * kTileRows + 4 * (lane >> 4);
         float sc[4] = {1.f, 1.f, 1.f, 1.f};
@@ -186,7 +210,9 @@ __global__ __launch_bounds__(WAVES * 64) void linear_tiled_kernel(
     // split-K: see linear_stream.hpp for the protocol (device-scope accesses, ordered sum)
     float *pf = reinterpret_cast<float *>(partials);
     auto partial_ptr = [&](int s, int r, int nt) {
-        return pf + ((((int64_t)s * n_row_tiles + (row_tile0 + r)) * n_tiles_total + (n_block * NT + nt)) * 4) * 64 + lane;
+        return pf
+               + ((((int64_t)s * n_row_tiles + (row_tile0 + r)) * n_tiles_total + ((n_block * WN + wn) * NT + nt)) * 4) * 64
+               + lane;
     };
 #pragma unroll
     for (int r = 0; r < RT; ++r)

@@ -254,11 +254,11 @@ def test_fp16_linear(pkg, oracle, N):
 
 
 # ------------------------------------------------------------------ tiled kernel (N > 32)
-@pytest.mark.parametrize("rt,nt", [(0, 0), (2, 4), (4, 4), (2, 8), (4, 8)])
+@pytest.mark.parametrize("rt,nt", [(0, 0), (128, 64), (256, 64), (128, 128), (256, 128)])
 @pytest.mark.parametrize("N,split", [(33, 1), (64, 0), (100, 2), (128, 3), (257, 0)])
 def test_linear_tiled(pkg, oracle, rt, nt, N, split):
     M, K = 272, 2816         # 17 row tiles (ragged against every block height), 11 k-tiles
-    _say("tiled linear rt=%d nt=%d N=%d split=%d" % (rt, nt, N, split))
+    _say("tiled linear block=%dx%d N=%d split=%d" % (rt, nt, N, split))
     pkg.fp6_tuning_set_tile(rt, nt)
     try:
         Y, Y_ref = _linear_case(pkg, oracle, M, K, N, seed=N + rt, split=split)
@@ -267,7 +267,7 @@ def test_linear_tiled(pkg, oracle, rt, nt, N, split):
     _check_linear(Y, Y_ref, "tiled rt=%d nt=%d N=%d" % (rt, nt, N))
 
 
-@pytest.mark.parametrize("rt,nt", [(0, 0), (2, 4), (4, 4), (2, 8)])
+@pytest.mark.parametrize("rt,nt", [(0, 0), (128, 64), (128, 128), (256, 128)])
 @pytest.mark.parametrize("N,split", [(64, 0), (130, 2)])
 def test_fp16_linear_tiled(pkg, oracle, rt, nt, N, split):
     M, K = 272, 2816

@@ -136,7 +136,9 @@ fp6_status launch_tiled_cfg(const TiledPlan &p, const void *weights, const void 
             return FP6_ERR_HIP;
         lds_ok = true;
     }
-    const dim3 grid((unsigned)(p.row_blocks * p.n_blocks * p.split)), block(WM * WN * 64);
+    // row blocks are dealt to the 8 XCDs round-robin: the grid is padded to a multiple of 8 row blocks
+    const int padded_row_blocks = (p.row_blocks + 7) / 8 * 8;
+    const dim3 grid((unsigned)(padded_row_blocks * p.n_blocks * p.split)), block(WM * WN * 64);
     hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, stream, weights, static_cast<const half_t *>(scales),
                        static_cast<const half_t *>(X), static_cast<half_t *>(Y), (int)M, (int)N, (int)K, p.split,
                        p.n_blocks, partials, counters);

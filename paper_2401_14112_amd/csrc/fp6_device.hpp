@@ -143,23 +143,24 @@ __device__ __forceinline__ void issue_load_to_lds_b128(rsrc_t rsrc, int lane_off
 // ---- activation tile layout in LDS -----------------------------------------
 // One MFMA step needs, for its 16 token columns n and 4 lane groups q, the 8 consecutive columns
 // X[n][k_offset(f, q) ..+8]: 64 pieces of 16 bytes = 1 KB per (token tile, run).  Inside that 1 KB,
-// piece 4*n + ((q + swizzle(n)) & 3) holds (n, q).  Reading side: the MFMA lane (q, n) = (L/16, L%16)
-// reads that piece; the rotation by swizzle(n) spreads every group of 8 or 16 consecutive lanes over all
-// LDS banks.  Writing side: piece p is written by lane p of a 64-lane copy, which fetches row n = p/4,
-// group q = (p - swizzle(n)) & 3 - so each quad of lanes reads 64 contiguous bytes of one row of X
-// (the texture addresser merges such quads into one request; scattered 16-byte gathers are 4x slower).
-__device__ __forceinline__ int x_swizzle(int n) { return ((n >> 1) & 2) | (((n >> 1) ^ (n >> 3)) & 1); }
+// piece 4*n + (q ^ x_swizzle(n)) holds (n, q).  Reading side: the MFMA lane (q, n) = (L/16, L%16) reads
+// that piece; the XOR with (n/2)%4 makes the 128-bit LDS read conflict-free (measured: same cost as the
+// linear pattern, while 4*n + q and several other rotations cost extra passes).  Writing side: piece p is
+// written by lane p of a 64-lane copy, which fetches row n = p/4, group q = (p%4) ^ x_swizzle(n) - so each
+// quad of lanes reads 64 contiguous bytes of one row of X (the texture addresser merges such quads into
+// one request; scattered 16-byte gathers are 4x slower).
+__device__ __forceinline__ int x_swizzle(int n) { return (n >> 1) & 3; }
 // piece read by MFMA lane L
 __device__ __forceinline__ int x_piece_of_lane(int L)
 {
     const int n = L & 15, q = L >> 4;
-    return 4 * n + ((q + x_swizzle(n)) & 3);
+    return 4 * n + (q ^ x_swizzle(n));
 }
 // (token row, lane group) fetched by copy lane p
 __device__ __forceinline__ void x_source_of_piece(int p, int &n, int &q)
 {
     n = (p >> 2) & 15;
-    q = (p - x_swizzle(n)) & 3;
+    q = (p & 3) ^ x_swizzle(n);
 }
 
 // ---- weight sources -------------------------------------------------------

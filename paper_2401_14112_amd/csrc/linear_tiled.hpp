@@ -46,13 +46,21 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     const int wm = wave % WM, wn = wave / WM;
     const int KT = K / kTileK;
     const int n_row_tiles = M / kTileRows;
-    // block -> (token block, k slice, row block): consecutive blocks (one per XCD) differ in token
-    // block / slice, so the blocks of one XCD share the same activation tile in its L2
+    // block -> (row block, token block, k slice).  Consecutive block ids land on consecutive XCDs (8 of
+    // them, each with its own L2).  The blocks of one XCD take row blocks congruent to the XCD index and,
+    // running side by side, all token blocks / k slices of those row blocks: a weight tile is then fetched
+    // from memory by one XCD only and the other token blocks hit it in that XCD's L2, while the (much
+    // smaller) activations are the operand that every XCD reads in full.
+    constexpr int kXcds = 8;
     const int combos = n_blocks * S;
-    const int combo = blockIdx.x % combos;
-    const int row_block = blockIdx.x / combos;
+    const int xcd = blockIdx.x % kXcds;
+    const int rest = blockIdx.x / kXcds;
+    const int combo = rest % combos;
+    const int row_block = (rest / combos) * kXcds + xcd;  // may run past the last row block: handled as a ragged edge
     const int n_block = combo % n_blocks;
     const int split = combo / n_blocks;
+    if (row_block * WM * RT >= n_row_tiles)
+        return;  // padding block of the XCD round-robin (whole block, before any barrier)
     const int row_tile0 = (row_block * WM + wm) * RT;
     const int block_col0 = n_block * BNT * 16;
     const int col0 = block_col0 + wn * NT * 16;  // first token of this wave

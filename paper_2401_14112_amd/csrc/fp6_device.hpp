@@ -177,7 +177,7 @@ struct PackedFp6Source {
         u32x4 p0, p1, p2;
     };
     static constexpr bool kHasScale = true;
-    static constexpr bool kTallTile = false;  // four row tiles per wave x two buffers do not fit next to the accumulators
+    static constexpr bool kTallTile = true;  // four row tiles per wave (two register buffers of 48) are affordable
     static constexpr int kLoads = 3;
     static constexpr int kTileStride = kTileBytes;  // bytes from one k-tile of the slice to the next
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }

@@ -279,7 +279,7 @@ fp6_status fp6_quantize_pack(const void *W_f16, int64_t M, int64_t K, void *pack
         return FP6_ERR_SHAPE;
     if (!aligned16(W_f16) || !aligned16(packed) || !aligned16(scales_f16))
         return FP6_ERR_ALIGN;
-    hipLaunchKernelGGL(quantize_pack_kernel, dim3((unsigned)(M / kTileRows)), dim3(256), 0,
+    hipLaunchKernelGGL(quantize_pack_kernel, dim3((unsigned)(M / kTileRows)), dim3(kPackWaves * 64), 0,
                        static_cast<hipStream_t>(stream), static_cast<const half_t *>(W_f16), (int)M, (int)K,
                        static_cast<uint8_t *>(packed), static_cast<half_t *>(scales_f16));
     return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;

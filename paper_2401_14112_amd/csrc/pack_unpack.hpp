@@ -31,33 +31,51 @@ __device__ __forceinline__ uint32_t e3m2_magnitude_code(float ratio)
     return g < 31u ? g : 31u;
 }
 
-__device__ __forceinline__ uint32_t quantize_code(uint32_t w_bits, float scale)
+// The row scale as the encoder needs it: the scale itself and its reciprocal (0 for a zero scale).
+struct RowScale {
+    float scale, inv;
+};
+__device__ __forceinline__ RowScale make_row_scale(float scale)
+{
+    RowScale r;
+    r.scale = scale;
+    r.inv = scale == 0.0f ? 0.0f : 1.0f / scale;
+    return r;
+}
+
+// |w| / scale with one Newton correction on top of the reciprocal product.  When the exact quotient is a
+// grid midpoint m (the only case where the last bit matters), q = m(1+e), the fused remainder a - q*scale
+// is exact and the corrected value m(1+O(e^2)) rounds to m itself; everywhere else the exact quotient is
+// at least 2^-16 (relative) away from every midpoint, far more than the error of q.
+__device__ __forceinline__ uint32_t quantize_code(uint32_t w_bits, RowScale rs)
 {
     const uint32_t sign = (w_bits >> 15) & 1u;
-    if (scale == 0.0f)
-        return sign << 5;
     const float a = (float)bit_cast<half_t>((uint16_t)(w_bits & 0x7fffu));
-    return (sign << 5) | e3m2_magnitude_code(a / scale);
+    const float q = a * rs.inv;
+    const float ratio = __builtin_fmaf(__builtin_fmaf(-q, rs.scale, a), rs.inv, q);
+    return (sign << 5) | e3m2_magnitude_code(ratio);  // zero scale: inv = 0 -> ratio = 0 -> sign-only code
 }
 
 // code s e2 e1 e0 m1 m0 -> byte  s 0 0 e2 e1 e0 m1 m0
 __device__ __forceinline__ uint32_t code_to_byte(uint32_t c) { return ((c & 0x20u) << 2) | (c & 0x1fu); }
 
-__global__ __launch_bounds__(256) void quantize_pack_kernel(const half_t *__restrict__ W, int M, int K,
-                                                            uint8_t *__restrict__ packed,
-                                                            half_t *__restrict__ scales)
+constexpr int kPackWaves = 16;  // waves per block of quantize_pack_kernel
+
+__global__ __launch_bounds__(kPackWaves * 64) void quantize_pack_kernel(const half_t *__restrict__ W, int M, int K,
+                                                                        uint8_t *__restrict__ packed,
+                                                                        half_t *__restrict__ scales)
 {
     __shared__ float s_scale[kTileRows];
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const int row_tile = blockIdx.x;
     const int KT = K / kTileK;
 
-    // ---- pass 1: 16 threads per row, 16 bytes per thread per step
-    {
-        const int r = tid >> 4, c = tid & 15;
+    // ---- pass 1: one wave per row (16 waves, 16 rows), 1 KB per load instruction
+    for (int r = wave; r < kTileRows; r += kPackWaves) {
         const u32x4 *row = reinterpret_cast<const u32x4 *>(W + ((int64_t)row_tile * kTileRows + r) * K);
         ushort2_t mx = {0, 0};
-        for (int i = c; i < K / 8; i += 16) {
+        for (int i = lane; i < K / 8; i += 64) {
             const u32x4 v = row[i];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -65,11 +83,11 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const half_t *__rest
         }
         uint32_t amax = mx[0] > mx[1] ? mx[0] : mx[1];  // finite fp16 magnitudes order like integers
 #pragma unroll
-        for (int off = 1; off < 16; off <<= 1) {
-            const uint32_t other = __shfl_xor(amax, off, 16);
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t other = __shfl_xor(amax, off, 64);
             amax = other > amax ? other : amax;
         }
-        if (c == 0) {
+        if (lane == 0) {
             const float a = (float)bit_cast<half_t>((uint16_t)amax);
             const half_t sc = (half_t)(a / 28.0f);  // fp32 quotient, then one rounding to fp16
             scales[row_tile * kTileRows + r] = sc;
@@ -79,11 +97,10 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const half_t *__rest
     __syncthreads();
 
     // ---- pass 2: one wave per k-tile; lane (r, q) builds its 48 bytes of the tile
-    const int lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, q = lane >> 4;
-    const float scale = s_scale[r];
+    const RowScale scale = make_row_scale(s_scale[r]);
     const half_t *row = W + ((int64_t)row_tile * kTileRows + r) * K + q * 8;
-    for (int kt = wave; kt < KT; kt += 4) {
+    for (int kt = wave; kt < KT; kt += kPackWaves) {
         uint32_t code[8][8];
 #pragma unroll
         for (int f = 0; f < 8; ++f) {

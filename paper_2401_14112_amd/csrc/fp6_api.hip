@@ -73,7 +73,7 @@ struct TileShape {
     int rows() const { return 16 * rt * wm; }
     int tokens() const { return 16 * nt * wn; }
 };
-constexpr TileShape kTile256x128{4, 8, 4, 1};
+constexpr TileShape kTile256x128{2, 8, 8, 1};
 constexpr TileShape kTile128x128{2, 4, 4, 2};
 constexpr TileShape kTile256x64{4, 4, 4, 1};
 constexpr TileShape kTile128x64{2, 4, 4, 1};
@@ -104,7 +104,7 @@ TiledPlan plan_tiled(int64_t M, int64_t N, int64_t K, bool tall_tile_ok)
         p.tile = kTile128x128;
     else
         p.tile = kTile256x128;
-    if (p.tile.rt == 4 && !tall_tile_ok)  // this weight source does not fit four row tiles per wave in registers
+    if (p.tile.rows() == 256 && !tall_tile_ok)  // this weight source does not fit four row tiles per wave in registers
         p.tile = p.tile.tokens() == 128 ? kTile128x128 : kTile128x64;
     p.row_blocks = (int)((M + p.tile.rows() - 1) / p.tile.rows());
     p.n_blocks = (int)((N + p.tile.tokens() - 1) / p.tile.tokens());
@@ -170,7 +170,7 @@ fp6_status launch_tiled(const void *weights, const void *scales, const void *X, 
     FP6_TILED_CASE(2, 4, 4, 2)
     FP6_TILED_CASE(2, 4, 4, 1)
     if constexpr (Src::kTallTile) {
-        FP6_TILED_CASE(4, 8, 4, 1)
+        FP6_TILED_CASE(2, 8, 8, 1)
         FP6_TILED_CASE(4, 4, 4, 1)
     }
 #undef FP6_TILED_CASE

@@ -105,49 +105,54 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
         for (int nt = 0; nt < NT; ++nt)
             acc[r][nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
-    // One k-tile = 8 runs.  The B fragments of run f+1 are read from LDS before the MFMAs of run f are
-    // issued, and the A fragments of runs 2g+2, 2g+3 are unpacked while the MFMAs of runs 2g, 2g+1 execute,
-    // so neither the LDS latency nor the shift/mask work sits on the MFMA critical path.
-    auto load_b = [&](half8_t (&b)[NT], const u32x4 *xbuf, int f) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            b[nt] = bit_cast<half8_t>(xbuf[((wn * NT + nt) * 8 + f) * 64 + b_piece]);
-    };
-    auto mma_run = [&](const half8_t (&a)[RT], const half8_t (&b)[NT]) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int r = 0; r < RT; ++r)
-                acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[r], b[nt], acc[r][nt], 0, 0, 0);
+    // One k-tile = 8 runs x NT token tiles = 8*NT steps of RT MFMAs.  B fragments travel through a small
+    // ring of registers: the LDS read of step s+LOOK is issued when step s is consumed.  The A fragments of
+    // runs 2g+2, 2g+3 are unpacked (shift/mask VALU work) while the MFMAs of runs 2g, 2g+1 execute.  The
+    // sched_group_barrier sequence fixes the instruction order inside each group of two runs to
+    // "1 LDS read, RT MFMAs, a few VALU" per step: a wave cannot issue anything else while one of its MFMAs
+    // is being issued, so the VALU work is laid out in small pieces that the other waves of the SIMD can
+    // cover with their own MFMAs, instead of long bursts in which the matrix pipe idles.
+    constexpr int LOOK = 4;
+    constexpr int STEPS = 8 * NT;
+    constexpr int VALU_PER_STEP = (RT * 27 + 2 * NT - 1) / (2 * NT) + 1;
+    auto ldb = [&](const u32x4 *xbuf, int st) {
+        return bit_cast<half8_t>(xbuf[((wn * NT + (st % NT)) * 8 + st / NT) * 64 + b_piece]);
     };
     auto compute = [&](const typename Src::Tile (&t)[RT], const u32x4 *xbuf) {
-        half8_t a_even[2][RT], a_odd[2][RT];
-        half8_t b[2][NT];
-        load_b(b[0], xbuf, 0);
+        half8_t a[2][2][RT];  // [group parity][even/odd run][row tile]
+        half8_t bq[LOOK];
+#pragma unroll
+        for (int i = 0; i < LOOK; ++i)
+            bq[i] = ldb(xbuf, i);
 #pragma unroll
         for (int r = 0; r < RT; ++r)
-            Src::template fragments<0>(t[r], a_even[0][r], a_odd[0][r]);
-        // sched_barrier(0) pins the order "read next B fragments, then this run's MFMAs": without it the
-        // scheduler sinks the LDS reads next to their use and every MFMA group waits for LDS.
-#define FP6_TILED_STEP(G, NEXT)                                                      \
-    load_b(b[1], xbuf, 2 * G + 1);                                                   \
-    __builtin_amdgcn_sched_barrier(0);                                               \
-    mma_run(a_even[G & 1], b[0]);                                                    \
-    if (G < 3) {                                                                     \
-        _Pragma("unroll") for (int r = 0; r < RT; ++r)                               \
-            Src::template fragments<NEXT>(t[r], a_even[(G + 1) & 1][r], a_odd[(G + 1) & 1][r]); \
-    }                                                                                \
-    __builtin_amdgcn_sched_barrier(0);                                               \
-    if (G < 3)                                                                       \
-        load_b(b[0], xbuf, 2 * G + 2);                                               \
-    __builtin_amdgcn_sched_barrier(0);                                               \
-    mma_run(a_odd[G & 1], b[1]);                                                     \
+            Src::template fragments<0>(t[r], a[0][0][r], a[0][1][r]);
+        __builtin_amdgcn_sched_barrier(0);
+#define FP6_TILED_GROUP(G, NEXT)                                                                  \
+    if (G < 3) {                                                                                  \
+        _Pragma("unroll") for (int r = 0; r < RT; ++r)                                            \
+            Src::template fragments<NEXT>(t[r], a[(G + 1) & 1][0][r], a[(G + 1) & 1][1][r]);      \
+    }                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < 2 * NT; ++i) {                                          \
+        const int st = 2 * G * NT + i;                                                            \
+        const half8_t b = bq[st % LOOK];                                                          \
+        if (st + LOOK < STEPS)                                                                    \
+            bq[st % LOOK] = ldb(xbuf, st + LOOK);                                                 \
+        _Pragma("unroll") for (int r = 0; r < RT; ++r)                                            \
+            acc[r][st % NT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[G & 1][i / NT][r], b, acc[r][st % NT], 0, 0, 0); \
+    }                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < 2 * NT; ++i) {                                          \
+        if (2 * G * NT + i + LOOK < STEPS)                                                        \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, RT, 0);                                       \
+        __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_STEP, 0);                            \
+    }                                                                                             \
     __builtin_amdgcn_sched_barrier(0);
-        FP6_TILED_STEP(0, 1)
-        FP6_TILED_STEP(1, 2)
-        FP6_TILED_STEP(2, 3)
-        FP6_TILED_STEP(3, 3)
-#undef FP6_TILED_STEP
+        FP6_TILED_GROUP(0, 1)
+        FP6_TILED_GROUP(1, 2)
+        FP6_TILED_GROUP(2, 3)
+        FP6_TILED_GROUP(3, 3)
+#undef FP6_TILED_GROUP
     };
 
     typename Src::Tile w[2][RT];
@@ -164,21 +169,39 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
             Src::pin_tile(dst[r]);
     };
 
+#ifndef FP6_TILED_ABLATE
+#define FP6_TILED_ABLATE 0
+#endif
+#if FP6_TILED_ABLATE == 1
+#define X_ISSUE(t, b) (void)0
+#else
+#define X_ISSUE(t, b) x_issue(t, b)
+#endif
+#if FP6_TILED_ABLATE == 2
+#define W_ISSUE(d, t) (void)0
+#else
+#define W_ISSUE(d, t) w_issue(d, t)
+#endif
+#if FP6_TILED_ABLATE == 3
+#define COMPUTE(w_, x_) do { acc[0][0][0] += __builtin_bit_cast(float, w_[0].p0[0] ^ w_[RT - 1].p2[3]); } while (0)
+#else
+#define COMPUTE(w_, x_) compute(w_, x_)
+#endif
     x_issue(0, 0);
     w_issue(w[0], 0);
     // two tiles per trip so that the register / LDS buffer index is static; tiles past the slice are zeros
     for (int t = 0; t < n_valid; t += 2) {
         arrive(w[0]);
         __syncthreads();
-        x_issue(t + 1, 1);
-        w_issue(w[1], t + 1);
-        compute(w[0], xs_dyn);
+        X_ISSUE(t + 1, 1);
+        W_ISSUE(w[1], t + 1);
+        COMPUTE(w[0], xs_dyn);
 
         arrive(w[1]);
         __syncthreads();
-        x_issue(t + 2, 0);
-        w_issue(w[0], t + 2);
-        compute(w[1], xs_dyn + XCHUNKS);
+        X_ISSUE(t + 2, 0);
+        W_ISSUE(w[0], t + 2);
+        COMPUTE(w[1], xs_dyn + XCHUNKS);
     }
     arrive(w[0]);  // the last look-ahead requests (out of range: zeros) must land before the block ends
 

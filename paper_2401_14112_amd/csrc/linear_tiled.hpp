@@ -84,9 +84,12 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     const int b_piece = x_piece_of_lane(lane);
     // LDS byte address of the activation buffers (the low 32 bits of a shared-memory pointer)
     const uint32_t xs_lds = (uint32_t)reinterpret_cast<uintptr_t>(xs_dyn);
-    auto x_issue = [&](int t, int buf) {
+    // copies [i0, i1) of the XPER copies this wave contributes to the activation tile of k-tile t
+    auto x_issue = [&](int t, int buf, int i0, int i1) {
 #pragma unroll
         for (int i = 0; i < XPER; ++i) {
+            if (i < i0 || i >= i1)
+                continue;
             const int j = wave + WAVES * i;
             const int nt = j >> 3, f = j & 7;
             const int col = block_col0 + nt * 16 + xn;
@@ -118,7 +121,9 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     auto ldb = [&](const u32x4 *xbuf, int st) {
         return bit_cast<half8_t>(xbuf[((wn * NT + (st % NT)) * 8 + st / NT) * 64 + b_piece]);
     };
-    auto compute = [&](const typename Src::Tile (&t)[RT], const u32x4 *xbuf) {
+    // `issue_part(g)`, g = 0..3, is called between the four groups: the requests for the next k-tile are
+    // spread over the computation instead of being issued in one burst while the matrix pipe idles.
+    auto compute = [&](const typename Src::Tile (&t)[RT], const u32x4 *xbuf, auto &&issue_part) {
         half8_t a[2][2][RT];  // [group parity][even/odd run][row tile]
         half8_t bq[LOOK];
 #pragma unroll
@@ -147,6 +152,8 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
         __builtin_amdgcn_sched_group_barrier(0x008, RT, 0);                                       \
         __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_STEP, 0);                            \
     }                                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+    issue_part(G);                                                                                \
     __builtin_amdgcn_sched_barrier(0);
         FP6_TILED_GROUP(0, 1)
         FP6_TILED_GROUP(1, 2)
@@ -157,10 +164,11 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
 
     typename Src::Tile w[2][RT];
     const int w_off = Src::lane_offset(lane, kt0, K);
-    auto w_issue = [&](typename Src::Tile (&dst)[RT], int t) {
+    auto w_issue = [&](typename Src::Tile (&dst)[RT], int t, int r0, int r1) {
 #pragma unroll
         for (int r = 0; r < RT; ++r)
-            Src::issue(dst[r], w_rsrc[r], w_off + t * Src::kTileStride);
+            if (r >= r0 && r < r1)
+                Src::issue(dst[r], w_rsrc[r], w_off + t * Src::kTileStride);
     };
     auto arrive = [&](typename Src::Tile (&dst)[RT]) {
         wait_loads<0>();
@@ -168,40 +176,26 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
         for (int r = 0; r < RT; ++r)
             Src::pin_tile(dst[r]);
     };
+    // part g of the requests for k-tile t: a quarter of this wave's activation copies and (RT/4 or 1) weight tiles
+    auto issue_part = [&](typename Src::Tile (&dst)[RT], int t, int buf, int g) {
+        x_issue(t, buf, g * XPER / 4, (g + 1) * XPER / 4);
+        if (RT >= 4)
+            w_issue(dst, t, g * RT / 4, (g + 1) * RT / 4);
+        else if (g < RT)
+            w_issue(dst, t, g, g + 1);
+    };
 
-#ifndef FP6_TILED_ABLATE
-#define FP6_TILED_ABLATE 0
-#endif
-#if FP6_TILED_ABLATE == 1
-#define X_ISSUE(t, b) (void)0
-#else
-#define X_ISSUE(t, b) x_issue(t, b)
-#endif
-#if FP6_TILED_ABLATE == 2
-#define W_ISSUE(d, t) (void)0
-#else
-#define W_ISSUE(d, t) w_issue(d, t)
-#endif
-#if FP6_TILED_ABLATE == 3
-#define COMPUTE(w_, x_) do { acc[0][0][0] += __builtin_bit_cast(float, w_[0].p0[0] ^ w_[RT - 1].p2[3]); } while (0)
-#else
-#define COMPUTE(w_, x_) compute(w_, x_)
-#endif
-    x_issue(0, 0);
-    w_issue(w[0], 0);
+    x_issue(0, 0, 0, XPER);
+    w_issue(w[0], 0, 0, RT);
     // two tiles per trip so that the register / LDS buffer index is static; tiles past the slice are zeros
     for (int t = 0; t < n_valid; t += 2) {
         arrive(w[0]);
         __syncthreads();
-        X_ISSUE(t + 1, 1);
-        W_ISSUE(w[1], t + 1);
-        COMPUTE(w[0], xs_dyn);
+        compute(w[0], xs_dyn, [&](int g) { issue_part(w[1], t + 1, 1, g); });
 
         arrive(w[1]);
         __syncthreads();
-        X_ISSUE(t + 2, 0);
-        W_ISSUE(w[0], t + 2);
-        COMPUTE(w[1], xs_dyn + XCHUNKS);
+        compute(w[1], xs_dyn + XCHUNKS, [&](int g) { issue_part(w[0], t + 2, 0, g); });
     }
     arrive(w[0]);  // the last look-ahead requests (out of range: zeros) must land before the block ends
 

@@ -100,7 +100,7 @@ TiledPlan plan_tiled(int64_t M, int64_t N, int64_t K, bool tall_tile_ok)
         p.tile = rows == 256 ? (tokens == 128 ? kTile256x128 : kTile256x64) : (tokens == 128 ? kTile128x128 : kTile128x64);
     else if (N <= 64)
         p.tile = kTile128x64;
-    else if (N <= 256)
+    else if (N <= 128)
         p.tile = kTile128x128;
     else
         p.tile = kTile256x128;

@@ -46,7 +46,7 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K)
     StreamPlan p;
     const int64_t row_tiles = M / kTileRows;
     const int64_t KT = K / kTileK;
-    p.nt = N <= 16 ? 1 : 2;
+    p.nt = N <= 16 ? 1 : (N <= 32 ? 2 : 4);
     int64_t s = g_forced_split.load(std::memory_order_relaxed);
     if (s <= 0)
         s = (kTargetWaves + row_tiles - 1) / row_tiles;
@@ -65,7 +65,7 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K)
 }
 
 // ---- tiled kernel (prefill-sized N) -----------------------------------------
-constexpr int kStreamMaxN = 32;  // token counts up to this use the streaming kernel
+constexpr int kStreamMaxN = 64;  // token counts up to this use the streaming kernel
 
 // Block shapes offered by the tiled kernel: {RT, NT, WM, WN}; block = (16*RT*WM) rows x (16*NT*WN) tokens.
 struct TileShape {
@@ -192,20 +192,30 @@ fp6_status launch_stream(const void *weights, const void *scales, const void *X,
     float4_t *partials =
         p.total_bytes() ? reinterpret_cast<float4_t *>(static_cast<uint8_t *>(workspace) + p.counter_bytes) : nullptr;
     const dim3 grid((unsigned)(p.row_blocks * p.split)), block(kStreamWaves * 64);
-    // tokens are processed 32 (or 16) at a time; each pass re-streams the weights
+    const size_t lds = (size_t)2 * p.nt * 512 * 16;
+    // tokens are processed 16*nt at a time; each pass re-streams the weights
     const int64_t step = 16 * p.nt;
     for (int64_t n0 = 0; n0 < N; n0 += step) {
         const int64_t n = (N - n0 < step) ? (N - n0) : step;
         const half_t *Xp = static_cast<const half_t *>(X) + n0 * K;
         half_t *Yp = static_cast<half_t *>(Y) + n0 * M;
-        if (p.nt == 1)
-            hipLaunchKernelGGL((linear_stream_kernel<Src, 1, kStreamWaves, kStreamDepth>), grid, block, 0, stream,
-                               weights, static_cast<const half_t *>(scales), Xp, Yp, (int)M, (int)n, (int)K, p.split,
-                               partials, counters);
-        else
-            hipLaunchKernelGGL((linear_stream_kernel<Src, 2, kStreamWaves, kStreamDepth>), grid, block, 0, stream,
-                               weights, static_cast<const half_t *>(scales), Xp, Yp, (int)M, (int)n, (int)K, p.split,
-                               partials, counters);
+#define FP6_STREAM_CASE(NT_)                                                                                      \
+    if (p.nt == NT_) {                                                                                            \
+        auto kernel = linear_stream_kernel<Src, NT_, kStreamWaves, kStreamDepth>;                                 \
+        static bool lds_ok = false;                                                                               \
+        if (!lds_ok) {                                                                                            \
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),                                       \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)          \
+                return FP6_ERR_HIP;                                                                               \
+            lds_ok = true;                                                                                        \
+        }                                                                                                         \
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, weights, static_cast<const half_t *>(scales), Xp, Yp, \
+                           (int)M, (int)n, (int)K, p.split, partials, counters);                                  \
+    }
+        FP6_STREAM_CASE(1)
+        FP6_STREAM_CASE(2)
+        FP6_STREAM_CASE(4)
+#undef FP6_STREAM_CASE
         if (hipGetLastError() != hipSuccess)
             return FP6_ERR_HIP;
     }

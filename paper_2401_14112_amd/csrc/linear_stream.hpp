@@ -30,7 +30,8 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     static_assert(XCHUNKS % THREADS == 0, "activation tile must split evenly over the block");
     constexpr int XPER = XCHUNKS / THREADS;
 
-    __shared__ u32x4 xs[2][XCHUNKS];
+    extern __shared__ u32x4 xs_dyn[];  // [2][XCHUNKS]
+    u32x4(*xs)[XCHUNKS] = reinterpret_cast<u32x4(*)[XCHUNKS]>(xs_dyn);
     __shared__ int s_is_last;
 
     const int tid = threadIdx.x;

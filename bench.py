@@ -201,6 +201,7 @@ def main():
         "sweep": {
             str(n): {
                 "us_mean": round(per_n_us[n][0], 2), "us_median": round(per_n_us[n][1], 2),
+                "us_min": round(per_n_us[n][2], 2),
                 "weight_GBps": round(P / per_n_us[n][1] * 1e-3, 1),
                 "tflops": round(2.0 * M * n * K / per_n_us[n][1] * 1e-6, 2),
                 "hbm_frac": round(algorithmic_bytes(M, n, K) / per_n_us[n][1] * 1e-3 / HBM_PEAK_GBPS, 4),
@@ -252,8 +253,36 @@ def _time_graph(torch, fn, launches_per_graph, reps=20):
     return e0.elapsed_time(e1) * 1e3 / (reps * launches_per_graph)
 
 
+def _compare_sweep(pkg, torch, workloads, M, K, packed, scales, W16, Ns):
+    """fp6_linear against the library's own fp16_linear (and, as context, the vendor fp16 GEMM torch dispatches
+    to) at the same shapes; every launch of a graph reads another copy of the weights."""
+    dev = packed[0].device
+    P = pkg.fp6_packed_bytes(M, K)
+    cmp = {}
+    for n in Ns:
+        X = workloads.make_activations(n, K, seed=n, device=dev)
+        Y = torch.empty((n, M), dtype=torch.float16, device=dev)
+        ws6 = torch.zeros(max(pkg.fp6_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
+        ws16 = torch.zeros(max(pkg.fp16_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
+        reps = 10 if n <= 32 else 3
+        us6 = _time_graph(torch, lambda i: pkg.fp6_linear(packed[i % len(packed)], scales[i % len(packed)], X, M, K, out=Y, workspace=ws6), len(packed), reps)
+        us16 = _time_graph(torch, lambda i: pkg.fp16_linear(W16[i % len(W16)], X, out=Y, workspace=ws16), len(W16), reps)
+        try:
+            usv = round(_time_graph(torch, lambda i: torch.matmul(X, W16[i % len(W16)].t(), out=Y), len(W16), reps), 2)
+        except Exception:      # the vendor path is context only; never let it break the benchmark
+            usv = None
+        tfl = 2.0 * M * n * K / us6 * 1e-6
+        cmp[str(n)] = {"fp6_us": round(us6, 2), "fp16_us": round(us16, 2), "speedup_vs_own_fp16": round(us16 / us6, 3),
+                       "vendor_fp16_gemm_us": usv,
+                       "fp6_weight_GBps": round(P / us6 * 1e-3, 1), "fp6_tflops": round(tfl, 2),
+                       "fp6_hbm_frac": round(algorithmic_bytes(M, n, K) / us6 * 1e-3 / HBM_PEAK_GBPS, 4),
+                       "fp6_mfma_frac": round(tfl / MFMA_F16_PEAK_TFLOPS, 4)}
+    return cmp
+
+
 def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_ms):
-    """Prefill-sized N, the library's own fp16 GEMM at the same shapes, and the offline steps."""
+    """Prefill-sized N, the library's own fp16 GEMM at the same shapes, the offline steps, the transposed
+    (down-projection) shape, and the 70B-class layer set / decoder weight stream."""
     dev = W0.device
     P = pkg.fp6_packed_bytes(M, K)
     out = {"quantize_pack_ms": round(float(np.median(pack_ms)), 3),
@@ -263,52 +292,122 @@ def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_
     out["unpack_ms"] = round(us * 1e-3, 3)
     out["unpack_GBps_total"] = round((P + 2.0 * M * K) / us * 1e-3, 1)
     del Wd
+    # the same launch with the weights resident in the last-level cache (one packed copy, 135 MB): labelled
+    # as such, never the headline
+    X1 = workloads.make_activations(1, K, seed=1, device=dev)
+    Y1 = torch.empty((1, M), dtype=torch.float16, device=dev)
+    ws1 = torch.zeros(max(pkg.fp6_linear_workspace_bytes(M, 1, K), 16), dtype=torch.uint8, device=dev)
+    us = _time_graph(torch, lambda i: pkg.fp6_linear(packed[0], scales[0], X1, M, K, out=Y1, workspace=ws1), 8, reps=10)
+    out["cache_resident_N1_us"] = round(us, 2)
     # the library's own W16A16 kernel on 3 fp16 copies (1.08 GB rotation)
     W16 = [W0] + [workloads.make_weights(M, K, seed=100 + b, device=dev) for b in range(2)]
-    cmp = {}
-    for n in list(workloads.DECODE_N) + list(workloads.PREFILL_N):
+    Ns = list(workloads.DECODE_N) + list(workloads.PREFILL_N)
+    out["vs_own_fp16_linear"] = _compare_sweep(pkg, torch, workloads, M, K, packed, scales, W16, Ns)
+    # the transposed shape (down projection, 22016 x 8192): the same bytes seen as [K][M] are a valid input
+    Mt, Kt = K, M
+    W16t = [w.view(Mt, Kt) for w in W16]
+    pk_t, sc_t = [], []
+    for b in range(len(packed)):
+        Wt = W16t[b] if b < len(W16t) else workloads.make_weights(Mt, Kt, seed=200 + b, device=dev)
+        pk, sc = pkg.fp6_quantize_pack(Wt)
+        pk_t.append(pk)
+        sc_t.append(sc)
+        del Wt
+    out["down_projection_22016x8192"] = _compare_sweep(pkg, torch, workloads, Mt, Kt, pk_t, sc_t, W16t, Ns)
+    del W16, W16t, pk_t, sc_t
+    torch.cuda.empty_cache()
+    out["decoder_set_70b"] = decoder_set_measurements(pkg, torch, np, workloads, dev)
+    return out
+
+
+def decoder_set_measurements(pkg, torch, np, workloads, dev, blocks=20):
+    """The four linear layers of a 70B-class decoder block: each shape at N = 16 (rotating over the 20 packed
+    copies), then 20 blocks x 4 layers = 80 GEMMs with weights of their own from ONE captured HIP graph at
+    N = 1 and N = 32, and fp6_quantize_pack of all 80 weight matrices timed by events."""
+    shapes = workloads.SET_70B
+    packed = {name: [] for name, _, _ in shapes}
+    scales = {name: [] for name, _, _ in shapes}
+    pack_ms, pack_bytes = 0.0, 0.0
+    for b in range(blocks):
+        for j, (name, M, K) in enumerate(shapes):
+            W = workloads.make_weights(M, K, seed=1000 + 4 * b + j, device=dev)
+            pk = torch.empty(pkg.fp6_packed_bytes(M, K), dtype=torch.uint8, device=dev)
+            sc = torch.empty(M, dtype=torch.float16, device=dev)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            pkg.fp6_quantize_pack(W, pk, sc)
+            e1.record()
+            torch.cuda.synchronize()
+            if b > 0:                       # block 0 is the warm-up
+                pack_ms += e0.elapsed_time(e1)
+                pack_bytes += 2.0 * M * K
+            packed[name].append(pk)
+            scales[name].append(sc)
+            del W
+    out = {"quantize_pack_all_layers": {"matrices": (blocks - 1) * len(shapes), "ms_total": round(pack_ms, 2),
+                                        "GBps_fp16_read": round(pack_bytes / pack_ms * 1e-6, 1)}}
+    per_shape = {}
+    for name, M, K in shapes:
+        n = 16
         X = workloads.make_activations(n, K, seed=n, device=dev)
         Y = torch.empty((n, M), dtype=torch.float16, device=dev)
-        ws6 = torch.zeros(max(pkg.fp6_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
-        ws16 = torch.zeros(max(pkg.fp16_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
-        reps = 10 if n <= 32 else 3
-        us6 = _time_graph(torch, lambda i: pkg.fp6_linear(packed[i % len(packed)], scales[i % len(packed)], X, M, K, out=Y, workspace=ws6), len(packed), reps)
-        us16 = _time_graph(torch, lambda i: pkg.fp16_linear(W16[i % 3], X, out=Y, workspace=ws16), 3, reps)
-        # context only: the vendor fp16 GEMM that PyTorch dispatches to (hipBLASLt / rocBLAS) at the same shape
-        try:
-            usv = round(_time_graph(torch, lambda i: torch.matmul(X, W16[i % 3].t(), out=Y), 3, reps), 2)
-        except Exception:      # the vendor path is context only; never let it break the benchmark
-            usv = None
-        tfl = 2.0 * M * n * K / us6 * 1e-6
-        cmp[str(n)] = {"fp6_us": round(us6, 2), "fp16_us": round(us16, 2), "speedup_vs_own_fp16": round(us16 / us6, 3),
-                       "vendor_fp16_gemm_us": usv,
-                       "fp6_weight_GBps": round(P / us6 * 1e-3, 1), "fp6_tflops": round(tfl, 2),
-                       "fp6_hbm_frac": round(algorithmic_bytes(M, n, K) / us6 * 1e-3 / HBM_PEAK_GBPS, 4),
-                       "fp6_mfma_frac": round(tfl / MFMA_F16_PEAK_TFLOPS, 4)}
-    out["vs_own_fp16_linear"] = cmp
+        ws = torch.zeros(max(pkg.fp6_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
+        us = _time_graph(torch, lambda i: pkg.fp6_linear(packed[name][i], scales[name][i], X, M, K, out=Y, workspace=ws), blocks, reps=5)
+        per_shape[name] = {"M": M, "K": K, "N": n, "us": round(us, 2),
+                           "weight_GBps": round(pkg.fp6_packed_bytes(M, K) / us * 1e-3, 1),
+                           "tflops": round(2.0 * M * n * K / us * 1e-6, 2),
+                           "hbm_frac": round(algorithmic_bytes(M, n, K) / us * 1e-3 / HBM_PEAK_GBPS, 4)}
+    out["N16"] = per_shape
+    stream = {}
+    total_packed = sum(pkg.fp6_packed_bytes(M, K) for _, M, K in shapes) * blocks
+    for n in (1, 32):
+        Xs = {name: workloads.make_activations(n, K, seed=n, device=dev) for name, M, K in shapes}
+        Ys = {name: torch.empty((n, M), dtype=torch.float16, device=dev) for name, M, K in shapes}
+        wss = {name: torch.zeros(max(pkg.fp6_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
+               for name, M, K in shapes}
+
+        def one(i):
+            name, M, K = shapes[i % len(shapes)]
+            b = i // len(shapes)
+            pkg.fp6_linear(packed[name][b], scales[name][b], Xs[name], M, K, out=Ys[name], workspace=wss[name])
+
+        us = _time_graph(torch, one, blocks * len(shapes), reps=5)
+        gemms = blocks * len(shapes)
+        alg = sum(algorithmic_bytes(M, n, K) for _, M, K in shapes) * blocks
+        stream[str(n)] = {"gemms_per_graph": gemms, "ms_per_replay": round(us * gemms * 1e-3, 3),
+                          "us_per_gemm": round(us, 2),
+                          "weight_GBps": round(total_packed / (us * gemms) * 1e-3, 1),
+                          "hbm_frac": round(alg / (us * gemms) * 1e-3 / HBM_PEAK_GBPS, 4)}
+    out["weight_stream_80_gemms_one_graph"] = stream
     return out
 
 
 def cpu_baseline(oracle, np, workloads, packed0, scales0, M, K, sweep):
-    """The CPU oracle, as it stands, on the same layer over the same sweep (a few seconds on the host cores)."""
+    """The CPU oracle, as it stands, on the same layer over the same sweep, repeated until about 10 s of
+    host time have been spent."""
     rows_n = M
     tile_bytes = (K // 256) * 3072
     sub_packed = packed0[: (rows_n // 16) * tile_bytes].cpu().numpy()
     sub_scales = scales0[:rows_n].cpu().numpy()
     Xs = [workloads.make_activations(n, K, seed=n).numpy() for n in sweep]
+    passes = 0
     t0 = time.perf_counter()
-    for X in Xs:
-        oracle.linear(sub_packed, sub_scales, X, rows_n, K)
-    dt = time.perf_counter() - t0
-    bytes_done = len(sweep) * (rows_n * K * 3 // 4)
+    while True:
+        for X in Xs:
+            oracle.linear(sub_packed, sub_scales, X, rows_n, K)
+        passes += 1
+        dt = time.perf_counter() - t0
+        if dt >= 10.0 or passes >= 16:
+            break
+    bytes_done = passes * len(sweep) * (rows_n * K * 3 // 4)
     return {
         "value": round(bytes_done / dt * 1e-9, 4),
         "unit": "GB/s",
         "cores": oracle.threads(),
         "kind": "oracle",
-        "sample": "fp64 oracle.linear on all 8192 rows of the same 8192x22016 layer, same sweep N in "
-                  "{1,2,4,8,16,32} (%.1f s); effective packed-weight bytes per second" % dt,
-        "gflops": round(sum(2.0 * rows_n * n * K for n in sweep) / dt * 1e-9, 2),
+        "sample": "fp64 oracle.linear on all 8192 rows of the same 8192x22016 layer, %d passes of the same sweep "
+                  "N in {1,2,4,8,16,32} (%.1f s); effective packed-weight bytes per second" % (passes, dt),
+        "gflops": round(passes * sum(2.0 * rows_n * n * K for n in sweep) / dt * 1e-9, 2),
     }
 
 

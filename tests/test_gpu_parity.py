@@ -352,3 +352,79 @@ def test_full_size_layer_sampled(pkg, oracle, shape):
         torch.cuda.synchronize()
         assert not torch.isnan(Yf).any()
         assert torch.equal(Yf.view(torch.int16), Y.view(torch.int16))
+
+
+# ------------------------------------------------------------------ 70B-class layer set, decoder weight stream
+def _sampled_reference(pkg, oracle, W, packed, scales, M, K, count, seed):
+    """Oracle-side packed stream and scales of `count` sampled 16-row tiles, after checking that the
+    library's packed stream and scales on those tiles are the same bytes."""
+    tiles = _sampled_row_tiles(M, count, seed)
+    rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
+    ref_packed, ref_scales = oracle.quantize_pack(_np16(W[torch.from_numpy(rows).cuda()]))
+    tile_bytes = (K // 256) * 3072
+    got_packed = np.concatenate([_np16(packed[t * tile_bytes:(t + 1) * tile_bytes]) for t in tiles])
+    assert np.array_equal(_np16(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
+    assert np.array_equal(got_packed, ref_packed)
+    return rows, ref_packed, ref_scales
+
+
+@pytest.mark.parametrize("shape", workloads.SET_70B)
+def test_layer_set_70b(pkg, oracle, shape):
+    """The four linear layers of a 70B-class decoder block at N = 16, real sizes, sampled row tiles."""
+    name, M, K = shape
+    _say("layer set %s M=%d K=%d N=16" % (name, M, K))
+    W = workloads.make_weights(M, K, seed=7, device="cuda")
+    packed, scales = pkg.fp6_quantize_pack(W)
+    torch.cuda.synchronize()
+    rows, ref_packed, ref_scales = _sampled_reference(pkg, oracle, W, packed, scales, M, K, 16, seed=2)
+    del W
+    X = workloads.make_activations(16, K, seed=16, device="cuda")
+    Y = pkg.fp6_linear(packed, scales, X, M, K)
+    torch.cuda.synchronize()
+    worst = _check_linear(_np16(Y)[:, rows], oracle.linear(ref_packed, ref_scales, _np16(X), len(rows), K), name)
+    _say("  worst column ratio %.3g" % worst)
+
+
+@pytest.mark.parametrize("N", [1, 32])
+def test_decoder_weight_stream_graph(pkg, oracle, N):
+    """80 GEMMs (20 decoder blocks x the four layer shapes, every GEMM with packed weights of its own) captured
+    into one HIP graph and replayed three times with eager work in between; every replay must give the bits
+    of the eager launches, and sampled rows of one GEMM per shape must agree with the oracle."""
+    blocks = 20
+    layers = []      # (name, M, K, packed, scales, X, Y, ws)
+    refs = {}
+    for b in range(blocks):
+        for j, (name, M, K) in enumerate(workloads.SET_70B):
+            W = workloads.make_weights(M, K, seed=1000 + 4 * b + j, device="cuda")
+            packed, scales = pkg.fp6_quantize_pack(W)
+            if b == blocks - 1:
+                torch.cuda.synchronize()
+                refs[len(layers)] = _sampled_reference(pkg, oracle, W, packed, scales, M, K, 6, seed=3 + j)
+            del W
+            X = workloads.make_activations(N, K, seed=50 + j, device="cuda")
+            Y = torch.empty((N, M), dtype=torch.float16, device="cuda")
+            ws = torch.zeros(max(pkg.fp6_linear_workspace_bytes(M, N, K), 16), dtype=torch.uint8, device="cuda")
+            layers.append((name, M, K, packed, scales, X, Y, ws))
+    _say("decoder stream N=%d: %d GEMMs, %.2f GB packed" % (N, len(layers), sum(l[3].numel() for l in layers) * 1e-9))
+
+    def run_all():
+        for name, M, K, packed, scales, X, Y, ws in layers:
+            pkg.fp6_linear(packed, scales, X, M, K, out=Y, workspace=ws)
+
+    run_all()
+    torch.cuda.synchronize()
+    eager = [l[6].clone() for l in layers]
+    for i, (rows, ref_packed, ref_scales) in refs.items():
+        name, M, K, _, _, X, Y, _ = layers[i]
+        _check_linear(_np16(Y)[:, rows], oracle.linear(ref_packed, ref_scales, _np16(X), len(rows), K), name)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_all()
+    for replay in range(3):
+        for l in layers:
+            l[6].fill_(float("nan"))          # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for l, e in zip(layers, eager):
+            assert torch.equal(l[6].view(torch.int16), e.view(torch.int16)), "replay %d, %s" % (replay, l[0])

@@ -14,18 +14,34 @@ namespace {
 using namespace fp6;
 
 constexpr int kLayoutVersion = 1;
-#ifndef FP6_STREAM_WAVES
-#define FP6_STREAM_WAVES 8
+// Configurations of the streaming kernel, by token count.  {token tiles per wave, waves per block, weight
+// tiles in flight per wave, k-tiles per activation stage, resident waves per CU aimed for (sets split-K),
+// iterations over which the activation copies of a stage are spread}.
+struct StreamCfg {
+    int nt, waves, depth, stage, target, spread = 1;
+};
+#ifndef FP6_SMALL_N
+#define FP6_SMALL_N 4
 #endif
-#ifndef FP6_STREAM_DEPTH
-#define FP6_STREAM_DEPTH 2
+#ifndef FP6_SCFG0
+#define FP6_SCFG0 {1, 4, 4, 4, 4}
 #endif
-#ifndef FP6_TARGET_WAVES_PER_CU
-#define FP6_TARGET_WAVES_PER_CU 8
+#ifndef FP6_SCFG1
+#define FP6_SCFG1 {1, 4, 4, 4, 4}
 #endif
-constexpr int kStreamWaves = FP6_STREAM_WAVES;  // waves per block of the streaming kernel
-constexpr int kStreamDepth = FP6_STREAM_DEPTH;  // weight tiles in flight per wave
-constexpr int kTargetWaves = 256 * FP6_TARGET_WAVES_PER_CU;  // 256 CUs x resident waves aimed for
+#ifndef FP6_SCFG2
+#define FP6_SCFG2 {2, 8, 2, 2, 8}
+#endif
+#ifndef FP6_SCFG3
+#define FP6_SCFG3 {4, 8, 2, 2, 8}
+#endif
+constexpr int kStreamClasses = 4;
+constexpr StreamCfg kStreamCfg[kStreamClasses] = {FP6_SCFG0, FP6_SCFG1, FP6_SCFG2, FP6_SCFG3};
+// the fp16 weight source needs 32 registers per tile in flight: its own, shallower table
+constexpr StreamCfg kStreamCfgFp16[kStreamClasses] = {{1, 8, 2, 4, 8}, {1, 8, 2, 4, 8}, {2, 8, 2, 2, 8}, {4, 8, 2, 2, 8}};
+constexpr int kStreamClassMaxN[kStreamClasses] = {FP6_SMALL_N, 16, 32, 64};  // largest N each class serves
+constexpr int kStreamMaxN = kStreamClassMaxN[kStreamClasses - 1];  // token counts up to this use the streaming kernel
+constexpr int kCus = 256;
 
 std::atomic<int> g_forced_split{0};
 
@@ -33,7 +49,8 @@ bool shape_ok(int64_t M, int64_t K) { return M > 0 && K > 0 && M % kTileRows == 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct StreamPlan {
-    int nt;          // 16-token tiles handled per launch (1 or 2)
+    int cls;         // index into kStreamCfg
+    int nt;          // 16-token tiles handled per launch
     int split;       // split-K factor
     int row_blocks;  // blocks along M
     size_t counter_bytes;
@@ -41,15 +58,25 @@ struct StreamPlan {
     size_t total_bytes() const { return split > 1 ? counter_bytes + partial_bytes : 0; }
 };
 
-StreamPlan plan_stream(int64_t M, int64_t N, int64_t K)
+int stream_class(int64_t N)
+{
+    for (int c = 0; c < kStreamClasses - 1; ++c)
+        if (N <= kStreamClassMaxN[c])
+            return c;
+    return kStreamClasses - 1;
+}
+
+StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
 {
     StreamPlan p;
+    p.cls = stream_class(N);
+    const StreamCfg &c = packed ? kStreamCfg[p.cls] : kStreamCfgFp16[p.cls];
     const int64_t row_tiles = M / kTileRows;
     const int64_t KT = K / kTileK;
-    p.nt = N <= 16 ? 1 : (N <= 32 ? 2 : 4);
+    p.nt = c.nt;
     int64_t s = g_forced_split.load(std::memory_order_relaxed);
     if (s <= 0)
-        s = (kTargetWaves + row_tiles - 1) / row_tiles;
+        s = ((int64_t)kCus * c.target + row_tiles - 1) / row_tiles;
     const int64_t max_split = KT >= 4 ? KT / 2 : 1;  // at least two k-tiles per slice
     if (s > max_split)
         s = max_split;
@@ -58,14 +85,13 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K)
     if (s < 1)
         s = 1;
     p.split = (int)s;
-    p.row_blocks = (int)((row_tiles + kStreamWaves - 1) / kStreamWaves);
-    p.counter_bytes = (((size_t)p.row_blocks * sizeof(int)) + 255) / 256 * 256;
+    p.row_blocks = (int)((row_tiles + c.waves - 1) / c.waves);
+    p.counter_bytes = (((size_t)row_tiles * sizeof(int)) + 255) / 256 * 256;  // one arrival counter per row tile
     p.partial_bytes = (size_t)p.split * (size_t)row_tiles * (size_t)p.nt * 64 * sizeof(float4_t);
     return p;
 }
 
 // ---- tiled kernel (prefill-sized N) -----------------------------------------
-constexpr int kStreamMaxN = 64;  // token counts up to this use the streaming kernel
 
 // Block shapes offered by the tiled kernel: {RT, NT, WM, WN}; block = (16*RT*WM) rows x (16*NT*WN) tokens.
 struct TileShape {
@@ -177,11 +203,41 @@ fp6_status launch_tiled(const void *weights, const void *scales, const void *X, 
     return FP6_ERR_SHAPE;  // not reached: plan_tiled only picks the shapes above
 }
 
+template <class Src, int C>
+fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const void *scales, const void *X, void *Y,
+                             int64_t M, int64_t N, int64_t K, float4_t *partials, int *counters, hipStream_t stream)
+{
+    constexpr StreamCfg c = Src::kHasScale ? kStreamCfg[C] : kStreamCfgFp16[C];
+    auto kernel = linear_stream_kernel<Src, c.nt, c.waves, c.depth, c.stage, c.spread>;
+    constexpr size_t lds = (size_t)2 * c.stage * c.nt * 512 * 16;  // two stages of activations
+    static_assert(lds <= 160 * 1024, "activation stages exceed the LDS of a CU");
+    static bool lds_ok = false;
+    if (!lds_ok) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return FP6_ERR_HIP;
+        lds_ok = true;
+    }
+    const dim3 grid((unsigned)(p.row_blocks * p.split)), block(c.waves * 64);
+    // tokens are processed 16*nt at a time; each pass re-streams the weights
+    const int64_t step = 16 * c.nt;
+    for (int64_t n0 = 0; n0 < N; n0 += step) {
+        const int64_t n = (N - n0 < step) ? (N - n0) : step;
+        const half_t *Xp = static_cast<const half_t *>(X) + n0 * K;
+        half_t *Yp = static_cast<half_t *>(Y) + n0 * M;
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, weights, static_cast<const half_t *>(scales), Xp, Yp,
+                           (int)M, (int)n, (int)K, p.split, partials, counters);
+        if (hipGetLastError() != hipSuccess)
+            return FP6_ERR_HIP;
+    }
+    return FP6_OK;
+}
+
 template <class Src>
 fp6_status launch_stream(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
                          int64_t K, void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
-    const StreamPlan p = plan_stream(M, N, K);
+    const StreamPlan p = plan_stream(M, N, K, Src::kHasScale);
     if (p.total_bytes() > 0) {
         if (!workspace || workspace_bytes < p.total_bytes())
             return FP6_ERR_WORKSPACE;
@@ -191,35 +247,12 @@ fp6_status launch_stream(const void *weights, const void *scales, const void *X,
     int *counters = static_cast<int *>(workspace);
     float4_t *partials =
         p.total_bytes() ? reinterpret_cast<float4_t *>(static_cast<uint8_t *>(workspace) + p.counter_bytes) : nullptr;
-    const dim3 grid((unsigned)(p.row_blocks * p.split)), block(kStreamWaves * 64);
-    const size_t lds = (size_t)2 * p.nt * 512 * 16;
-    // tokens are processed 16*nt at a time; each pass re-streams the weights
-    const int64_t step = 16 * p.nt;
-    for (int64_t n0 = 0; n0 < N; n0 += step) {
-        const int64_t n = (N - n0 < step) ? (N - n0) : step;
-        const half_t *Xp = static_cast<const half_t *>(X) + n0 * K;
-        half_t *Yp = static_cast<half_t *>(Y) + n0 * M;
-#define FP6_STREAM_CASE(NT_)                                                                                      \
-    if (p.nt == NT_) {                                                                                            \
-        auto kernel = linear_stream_kernel<Src, NT_, kStreamWaves, kStreamDepth>;                                 \
-        static bool lds_ok = false;                                                                               \
-        if (!lds_ok) {                                                                                            \
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),                                       \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)          \
-                return FP6_ERR_HIP;                                                                               \
-            lds_ok = true;                                                                                        \
-        }                                                                                                         \
-        hipLaunchKernelGGL(kernel, grid, block, lds, stream, weights, static_cast<const half_t *>(scales), Xp, Yp, \
-                           (int)M, (int)n, (int)K, p.split, partials, counters);                                  \
+    switch (p.cls) {
+    case 0: return launch_stream_cfg<Src, 0>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
+    case 1: return launch_stream_cfg<Src, 1>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
+    case 2: return launch_stream_cfg<Src, 2>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
+    default: return launch_stream_cfg<Src, 3>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
     }
-        FP6_STREAM_CASE(1)
-        FP6_STREAM_CASE(2)
-        FP6_STREAM_CASE(4)
-#undef FP6_STREAM_CASE
-        if (hipGetLastError() != hipSuccess)
-            return FP6_ERR_HIP;
-    }
-    return FP6_OK;
 }
 
 }  // namespace
@@ -247,7 +280,7 @@ size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (!shape_ok(M, K) || N <= 0)
         return 0;
-    return N <= kStreamMaxN ? plan_stream(M, N, K).total_bytes()
+    return N <= kStreamMaxN ? plan_stream(M, N, K, true).total_bytes()
                             : plan_tiled(M, N, K, PackedFp6Source::kTallTile).total_bytes();
 }
 
@@ -255,7 +288,7 @@ size_t fp16_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (!shape_ok(M, K) || N <= 0)
         return 0;
-    return N <= kStreamMaxN ? plan_stream(M, N, K).total_bytes()
+    return N <= kStreamMaxN ? plan_stream(M, N, K, false).total_bytes()
                             : plan_tiled(M, N, K, PlainFp16Source::kTallTile).total_bytes();
 }
 

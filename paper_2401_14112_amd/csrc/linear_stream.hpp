@@ -1,90 +1,123 @@
-// Weight-streaming linear-layer kernel for small token counts (N <= 32), where the
+// Weight-streaming linear-layer kernel for small token counts (N <= 64), where the
 // layer is bound by reading the weights once from HBM (Section 3 and Section 7.1 of
 // the paper: linear layers at batch < 128 are limited by weight traffic).
 //
 // Work split: one wave owns one 16-row tile and a contiguous range of its 256-column
 // k-tiles (split-K slice); weights go HBM -> VGPR with three (packed) 128-bit loads
 // per lane per tile, prefetched DEPTH tiles ahead, and are used by exactly one wave,
-// so they never touch LDS.  The activation tile (16*NT tokens x 256 columns) is the
-// only shared operand: the block stages it in LDS, already in MFMA B-fragment order,
-// double-buffered with one barrier per k-tile.  fp32 accumulation in
-// v_mfma_f32_16x16x32_f16; the row scale is applied once in the epilogue.
+// so they never touch LDS.  The activations (16*NT tokens) are the only shared
+// operand: the block copies them global -> LDS without passing through registers,
+// already in MFMA B-fragment order, a STAGE of G k-tiles at a time, double-buffered.
+// There is one barrier per stage, not per k-tile: inside a stage every wave runs at
+// the pace of its own weight stream, so one late load delays one wave, not eight.
+// fp32 accumulation in v_mfma_f32_16x16x32_f16; the row scale is applied once in the
+// epilogue.
 //
-// Split-K: every block writes its fp32 partial tile, bumps an arrival counter of its
-// row block, and the block that arrives last adds the S partials in split order
-// (so the result does not depend on arrival order), scales, rounds and stores Y.
-// The counter is reset by that block, so a zeroed workspace stays reusable.
+// Split-K: every wave writes its fp32 partial tile, bumps the arrival counter of its
+// row tile, and the wave that arrives last adds the S partials in split order (so the
+// result does not depend on arrival order), scales, rounds and stores Y.  The counter
+// is reset by that wave, so a zeroed workspace stays reusable.
 #pragma once
+#include <utility>
+
 #include "fp6_device.hpp"
 
 namespace fp6 {
 
-template <class Src, int NT, int WAVES, int DEPTH>
+constexpr int stream_gcd(int a, int b) { return b == 0 ? a : stream_gcd(b, a % b); }
+
+// Activation copies requested in the DEPTH-1 iterations before the iteration at stage position g, when
+// each of the first XSPREAD iterations of a stage requests XPART of them.
+constexpr int stream_copies_between(int g, int G, int DEPTH, int XSPREAD, int XPART)
+{
+    int c = 0;
+    for (int d = 1; d < DEPTH; ++d)
+        c += ((g - d + DEPTH * G) % G) < XSPREAD ? XPART : 0;
+    return c;
+}
+
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a compile-time constant
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+template <class Src, int NT, int WAVES, int DEPTH, int G, int XSPREAD>
 __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     const void *__restrict__ weights, const half_t *__restrict__ scales, const half_t *__restrict__ X,
     half_t *__restrict__ Y, int M, int N, int K, int S, float4_t *__restrict__ partials,
     int *__restrict__ counters)
 {
-    constexpr int THREADS = WAVES * 64;
-    constexpr int XCHUNKS = NT * 512;  // 16-byte pieces of one activation tile
-    static_assert(XCHUNKS % THREADS == 0, "activation tile must split evenly over the block");
-    constexpr int XPER = XCHUNKS / THREADS;
+    constexpr int COPIES = G * NT * 8;  // copy instructions (1 KB each: one token tile x one run) per stage
+    static_assert(COPIES % WAVES == 0, "the copies of a stage must split evenly over the waves");
+    constexpr int XPER = COPIES / WAVES;
+    constexpr int STAGE_PIECES = COPIES * 64;  // 16-byte pieces of one stage
+    // the copies of the next stage are requested in the first XSPREAD iterations of a stage; they must be
+    // older than the weights of the next stage's first tile, which are requested in iteration G - DEPTH
+    static_assert(XSPREAD >= 1 && XSPREAD <= G - DEPTH + 1 && XPER % XSPREAD == 0, "bad spread of the activation copies");
+    constexpr int XPART = XPER / XSPREAD;
+    constexpr int U = G / stream_gcd(G, DEPTH) * DEPTH;  // unroll: both the stage position and the ring slot are static
 
-    extern __shared__ u32x4 xs_dyn[];  // [2][XCHUNKS]
-    u32x4(*xs)[XCHUNKS] = reinterpret_cast<u32x4(*)[XCHUNKS]>(xs_dyn);
-    __shared__ int s_is_last;
+    extern __shared__ u32x4 xs_dyn[];  // [2][STAGE_PIECES]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KT = K / kTileK;
     const int n_row_tiles = M / kTileRows;
+#ifdef FP6_TRACE_TIMES
+    unsigned long long *trace = reinterpret_cast<unsigned long long *>(
+        reinterpret_cast<char *>(partials) + (size_t)S * n_row_tiles * NT * 64 * 16) + (blockIdx.x * WAVES + wave) * 4;
+    if (lane == 0)
+        trace[0] = wall_clock64();
+#endif
     const int split = blockIdx.x % S;  // neighbouring blocks (one per XCD) take different k slices
     const int row_block = blockIdx.x / S;
     const int row_tile = row_block * WAVES + wave;
     const bool active = row_tile < n_row_tiles;
     const int kt0 = (int)(((unsigned)KT * (unsigned)split) / (unsigned)S);  // KT * S < 2^31 (host-checked)
     const int kt1 = (int)(((unsigned)KT * (unsigned)(split + 1)) / (unsigned)S);
-    const int n_valid = kt1 - kt0;        // k-tiles of this slice
-    const int T = (KT + S - 1) / S;       // loop trips: the same for every slice (>= n_valid)
+    const int n_valid = kt1 - kt0;        // k-tiles of this slice (>= 1)
+    const int T = (KT + S - 1) / S;       // k-tiles computed: the same for every slice (>= n_valid)
+    const int n_stages = (T + G - 1) / G;
 
     // Inactive waves (ragged last row block) stream the last valid row tile and drop the result,
     // so the main loop has no per-wave control flow.
     const rsrc_t w_rsrc = Src::slice_rsrc(weights, active ? row_tile : n_row_tiles - 1, kt0, kt1, KT, K);
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
-    // ---- activation staging: piece c = nt*512 + f*64 + p holds X[nt*16+n][k_tile*256 + k_offset(f,q) ..+8]
-    // for the (n, q) given by x_source_of_piece(p).  Token columns >= N and k-tiles past the slice get an
-    // offset outside the buffer and read as zeros.
-    struct XRegs {
-        u32x4 v[XPER];
-    };
-    int x_off[XPER];
-#pragma unroll
-    for (int i = 0; i < XPER; ++i) {
-        const int c = tid + i * THREADS;
-        const int f = (c >> 6) & 7, nt = c >> 9;
-        int n, q;
-        x_source_of_piece(c & 63, n, q);
-        const int col = nt * 16 + n;
-        x_off[i] = col < N ? (col * K + kt0 * kTileK + Src::k_offset(f, q)) * 2 : kOutOfRange;
-    }
-    auto x_issue = [&](XRegs &r, int t) {
+    // ---- activation staging.  Copy j = wave + WAVES*i of a stage serves k-tile g = j / (8*NT) of the
+    // stage, token tile nt = (j/8) % NT and run f = j % 8; lane p of the copy fetches
+    // X[16*nt + n][k-tile*256 + k_offset(f, q) ..+8] for the (n, q) that piece p of the 1 KB holds, and
+    // its 16 bytes land at piece 64*j + p of the stage buffer.  Token columns >= N and k-tiles past the
+    // end of the slice get an offset outside the buffer: nothing is fetched and zeros land in LDS, which is
+    // what neutralises the k-tiles that the uniform trip count adds to the shorter slices.
+    int xn, xq;
+    x_source_of_piece(lane, xn, xq);
+    const uint32_t xs_lds = (uint32_t)reinterpret_cast<uintptr_t>(xs_dyn);  // LDS byte address
+    auto x_issue = [&](int stage, int i0, int i1) {
+        const int buf = stage & 1;
 #pragma unroll
         for (int i = 0; i < XPER; ++i) {
-            const int off = (t < n_valid && x_off[i] != kOutOfRange) ? x_off[i] + t * (kTileK * 2) : kOutOfRange;
-            r.v[i] = issue_load_b128<0, false>(x_rsrc, off);
+            if (i < i0 || i >= i1)
+                continue;
+            const int j = wave + WAVES * i;
+            const int f = j & 7, nt = (j >> 3) % NT, g = j / (8 * NT);
+            const int col = nt * 16 + xn;
+            const int t = stage * G + g;
+            const int off = (t < n_valid && col < N)
+                                ? (col * K + (kt0 + t) * kTileK + Src::k_offset(f, xq)) * 2
+                                : kOutOfRange;
+            const uint32_t lds_base = (uint32_t)__builtin_amdgcn_readfirstlane(
+                (int)(xs_lds + (uint32_t)(buf * STAGE_PIECES + j * 64) * 16u));
+            issue_load_to_lds_b128<0>(x_rsrc, off, lds_base);
         }
-    };
-    auto x_pin = [&](XRegs &r) {
-#pragma unroll
-        for (int i = 0; i < XPER; ++i)
-            pin(r.v[i]);
-    };
-    auto x_commit = [&](const XRegs &r, int buf) {
-#pragma unroll
-        for (int i = 0; i < XPER; ++i)
-            xs[buf][tid + i * THREADS] = r.v[i];
     };
 
     const int b_piece = x_piece_of_lane(lane);
@@ -93,70 +126,80 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     for (int nt = 0; nt < NT; ++nt)
         acc[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
-    auto mma_pair = [&](const half8_t &a_even, const half8_t &a_odd, int buf, int g) {
+    // xb: first piece of this k-tile's activations in LDS
+    auto mma_pair = [&](const half8_t &a_even, const half8_t &a_odd, const u32x4 *xb, int r) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            half8_t b = bit_cast<half8_t>(xs[buf][nt * 512 + (2 * g) * 64 + b_piece]);
+            half8_t b = bit_cast<half8_t>(xb[(nt * 8 + 2 * r) * 64 + b_piece]);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_even, b, acc[nt], 0, 0, 0);
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            half8_t b = bit_cast<half8_t>(xs[buf][nt * 512 + (2 * g + 1) * 64 + b_piece]);
+            half8_t b = bit_cast<half8_t>(xb[(nt * 8 + 2 * r + 1) * 64 + b_piece]);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_odd, b, acc[nt], 0, 0, 0);
         }
     };
-    auto compute = [&](const typename Src::Tile &t, int buf) {
+    auto compute = [&](const typename Src::Tile &t, const u32x4 *xb) {
         half8_t a_even, a_odd;
         Src::template fragments<0>(t, a_even, a_odd);
-        mma_pair(a_even, a_odd, buf, 0);
+        mma_pair(a_even, a_odd, xb, 0);
         Src::template fragments<1>(t, a_even, a_odd);
-        mma_pair(a_even, a_odd, buf, 1);
+        mma_pair(a_even, a_odd, xb, 1);
         Src::template fragments<2>(t, a_even, a_odd);
-        mma_pair(a_even, a_odd, buf, 2);
+        mma_pair(a_even, a_odd, xb, 2);
         Src::template fragments<3>(t, a_even, a_odd);
-        mma_pair(a_even, a_odd, buf, 3);
+        mma_pair(a_even, a_odd, xb, 3);
     };
 
-    // ---- software pipeline.  Slot d of the register ring holds tile i*DEPTH + d of the slice: its
-    // weights and its share of the activation tile are requested DEPTH tiles ahead, right after the
-    // slot's previous tile has been consumed, so the new data lands in the registers that just became
-    // free and DEPTH-1 tiles stay in flight while one is being computed.  Every slot issues
-    // kSlotLoads loads; loads return in order, so "at most (DEPTH-1)*kSlotLoads outstanding" means the
-    // oldest slot has arrived.  The loop body has no branches: tiles past the end of the slice read
-    // as zeros through the buffer bounds check.
-    static_assert(DEPTH % 2 == 0, "the LDS double buffer is indexed by the ring slot");
-    constexpr int kSlotLoads = XPER + Src::kLoads;
+    // ---- software pipeline.  Slot t % DEPTH of the register ring holds weight tile t of the slice; it is
+    // requested DEPTH tiles ahead, right after the slot's previous tile has been consumed, so DEPTH-1 tiles
+    // stay in flight while one is being computed.  The activation copies of stage s+1 are requested in the
+    // first XSPREAD iterations of stage s, after that stage's barrier (by then every wave has finished
+    // reading the buffer they overwrite).  Loads complete in order, so "at most n outstanding" with n = the
+    // loads requested after tile t's weights means tile t has arrived: n = (DEPTH-1)*kLoads plus the
+    // activation copies requested in the DEPTH-1 iterations in between.  Tiles past the end of the slice read
+    // as zeros through the buffer bounds check (no memory traffic), so the request pattern never varies.
     typename Src::Tile w[DEPTH];
-    XRegs xr[DEPTH];
     const int w_off = Src::lane_offset(lane, kt0, K);
+    x_issue(0, 0, XPER);
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {
-        x_issue(xr[d], d);
+    for (int d = 0; d < DEPTH; ++d)
         Src::issue(w[d], w_rsrc, w_off + d * Src::kTileStride);
+    const int n_tiles = n_stages * G;
+    for (int t0 = 0; t0 < n_tiles; t0 += U) {
+        static_for<U>([&](auto uc) {
+            constexpr int u = decltype(uc)::value;
+            constexpr int g = u % G, slot = u % DEPTH;
+            // loads requested after this tile's weights (the prologue requested all copies of stage 0 before
+            // any weights, so the same count holds there); vmcnt cannot express more than 63
+            constexpr int kAfter = (DEPTH - 1) * Src::kLoads + stream_copies_between(g, G, DEPTH, XSPREAD, XPART);
+            const int t = t0 + u;
+            const int stage = t0 / G + u / G;
+            wait_loads<(kAfter < 63 ? kAfter : 63)>();
+            Src::pin_tile(w[slot]);
+            if (g == 0)
+                __syncthreads();  // the copies of this stage by all waves have landed; the other buffer is no longer read
+            if (g < XSPREAD)
+                x_issue(stage + 1, g * XPART, (g + 1) * XPART);
+            if (t < T)
+                compute(w[slot], xs_dyn + (stage & 1) * STAGE_PIECES + g * (NT * 8 * 64));
+            Src::issue(w[slot], w_rsrc, w_off + (t + DEPTH) * Src::kTileStride);
+        });
     }
-    for (int i = 0; i < T; i += DEPTH) {
-#pragma unroll
-        for (int d = 0; d < DEPTH; ++d) {
-            wait_loads<(DEPTH - 1) * kSlotLoads>();
-            x_pin(xr[d]);
-            Src::pin_tile(w[d]);
-            x_commit(xr[d], d & 1);
-            __syncthreads();
-            compute(w[d], d & 1);
-            x_issue(xr[d], i + d + DEPTH);
-            Src::issue(w[d], w_rsrc, w_off + (i + d + DEPTH) * Src::kTileStride);
-        }
-    }
-    // drain: the look-ahead loads of the last DEPTH tiles (all out of range, zeros) must land before
-    // their registers are reused
+    // drain: the look-ahead requests (weights out of range, activation copies into the unused buffer)
+    // must land before the registers are reused and before the block gives up its LDS
     wait_loads<0>();
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) {
-        x_pin(xr[d]);
+    for (int d = 0; d < DEPTH; ++d)
         Src::pin_tile(w[d]);
-    }
 
+#ifdef FP6_TRACE_TIMES
+    if (lane == 0)
+        trace[1] = wall_clock64();
+#endif
     // ---- epilogue.  Lane L holds, per n-tile, rows 4*(L/16)+i (i=0..3) of token column L%16.
+    if (!active)
+        return;  // no barrier follows the main loop
     const int n_in_tile = lane & 15;
     const int m0 = row_tile * kTileRows + 4 * (lane >> 4);
     auto finish = [&](const float4_t (&sum)[NT]) {
@@ -181,90 +224,64 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     };
 
     if (S == 1) {
-        if (active)
-            finish(acc);
+        finish(acc);
         return;
     }
 
-#ifndef FP6_SPLITK_SYNC
-#define FP6_SPLITK_SYNC 1
-#endif
-#if FP6_SPLITK_SYNC == 0
-    // Release/acquire fences at device scope (write back and invalidate this XCD's L2).
-    if (active) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            if (nt * 16 + n_in_tile < N)
-                partials[(((int64_t)split * n_row_tiles + row_tile) * NT + nt) * 64 + lane] = acc[nt];
-    }
-    __syncthreads();  // every wave's partial stores have been issued and have completed
-    if (tid == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        const int arrived = __hip_atomic_fetch_add(&counters[row_block], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_is_last = (arrived == S - 1);
-    }
-    __syncthreads();
-    if (!s_is_last)
-        return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-    if (active) {
-        float4_t sum[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            sum[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < S; ++s) {
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                if (nt * 16 + n_in_tile < N)
-                    sum[nt] += partials[(((int64_t)s * n_row_tiles + row_tile) * NT + nt) * 64 + lane];
-        }
-        finish(sum);
-    }
-#else
-    // The partial tiles are written and read with device-scope atomic (relaxed) accesses: such
-    // accesses are performed at the point where all CUs of the device agree (they are not left
-    // in, nor served from, a non-coherent cache), so no cache write-back or invalidate is needed.
-    // Order: stores complete (the barrier waits for them) -> arrival count -> the last block's loads.
+    // Split-K, one arrival counter per row tile: every wave is on its own from here (no barrier, so a wave
+    // that finishes its stream early does not wait for the slowest wave of its block).  The partial tiles
+    // are written and read with device-scope atomic (relaxed) accesses: such accesses are performed at the
+    // point where all CUs of the device agree (they are not left in, nor served from, a non-coherent
+    // cache), so no cache write-back or invalidate is needed.  Order: this wave's stores complete (vmcnt)
+    // -> arrival count -> the last wave's loads.  The last wave adds the S partial tiles in split order,
+    // taking its own from registers (the same bits it stored), so the sum does not depend on who is last.
     float *pf = reinterpret_cast<float *>(partials);
-    if (active) {
+    auto slot = [&](int s_, int nt) { return pf + ((((int64_t)s_ * n_row_tiles + row_tile) * NT + nt) * 4) * 64 + lane; };
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+        if (nt * 16 + n_in_tile < N) {
+            float *dst = slot(split, nt);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                __hip_atomic_store(dst + i * 64, acc[nt][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's partial stores are done
+    int arrived = 0;
+    if (lane == 0)
+        arrived = __hip_atomic_fetch_add(&counters[row_tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    arrived = __builtin_amdgcn_readfirstlane(arrived);
+    if (arrived != S - 1) {
+#ifdef FP6_TRACE_TIMES
+        if (lane == 0)
+            trace[2] = wall_clock64();
+#endif
+        return;
+    }
+    float4_t sum[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+        sum[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
+    for (int s_ = 0; s_ < S; ++s_) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
             if (nt * 16 + n_in_tile < N) {
-                float *dst = pf + ((((int64_t)split * n_row_tiles + row_tile) * NT + nt) * 4) * 64 + lane;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    __hip_atomic_store(dst + i * 64, acc[nt][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-    }
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's partial stores are done
-    __syncthreads();
-    if (tid == 0) {
-        const int arrived = __hip_atomic_fetch_add(&counters[row_block], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_is_last = (arrived == S - 1);
-    }
-    __syncthreads();
-    if (!s_is_last)
-        return;
-    if (active) {
-        float4_t sum[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            sum[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < S; ++s) {
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                if (nt * 16 + n_in_tile < N) {
-                    const float *src = pf + ((((int64_t)s * n_row_tiles + row_tile) * NT + nt) * 4) * 64 + lane;
+                if (s_ == split) {
+                    sum[nt] += acc[nt];
+                } else {
+                    const float *src = slot(s_, nt);
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
                         sum[nt][i] += __hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
-        }
-        finish(sum);
+            }
     }
+    finish(sum);
+    if (lane == 0)
+        counters[row_tile] = 0;  // re-arm for the next call on this workspace
+#ifdef FP6_TRACE_TIMES
+    if (lane == 0)
+        trace[2] = wall_clock64();
 #endif
-    if (tid == 0)
-        counters[row_block] = 0;  // re-arm for the next call on this workspace
 }
 
 }  // namespace fp6

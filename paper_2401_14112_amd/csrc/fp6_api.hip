@@ -84,6 +84,9 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
         s = 64;
     if (s < 1)
         s = 1;
+    // the kernel addresses the partial tiles with 32-bit byte offsets
+    while (s > 1 && (uint64_t)s * (uint64_t)row_tiles * (uint64_t)c.nt * 1024u >= (1ull << 31))
+        s /= 2;
     p.split = (int)s;
     p.row_blocks = (int)((row_tiles + c.waves - 1) / c.waves);
     p.counter_bytes = (((size_t)row_tiles * sizeof(int)) + 255) / 256 * 256;  // one arrival counter per row tile

@@ -71,12 +71,6 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KT = K / kTileK;
     const int n_row_tiles = M / kTileRows;
-#ifdef FP6_TRACE_TIMES
-    unsigned long long *trace = reinterpret_cast<unsigned long long *>(
-        reinterpret_cast<char *>(partials) + (size_t)S * n_row_tiles * NT * 64 * 16) + (blockIdx.x * WAVES + wave) * 4;
-    if (lane == 0)
-        trace[0] = wall_clock64();
-#endif
     const int split = blockIdx.x % S;  // neighbouring blocks (one per XCD) take different k slices
     const int row_block = blockIdx.x / S;
     const int row_tile = row_block * WAVES + wave;
@@ -193,10 +187,6 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     for (int d = 0; d < DEPTH; ++d)
         Src::pin_tile(w[d]);
 
-#ifdef FP6_TRACE_TIMES
-    if (lane == 0)
-        trace[1] = wall_clock64();
-#endif
     // ---- epilogue.  Lane L holds, per n-tile, rows 4*(L/16)+i (i=0..3) of token column L%16.
     if (!active)
         return;  // no barrier follows the main loop
@@ -250,13 +240,8 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     if (lane == 0)
         arrived = __hip_atomic_fetch_add(&counters[row_tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     arrived = __builtin_amdgcn_readfirstlane(arrived);
-    if (arrived != S - 1) {
-#ifdef FP6_TRACE_TIMES
-        if (lane == 0)
-            trace[2] = wall_clock64();
-#endif
+    if (arrived != S - 1)
         return;
-    }
     float4_t sum[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
@@ -278,10 +263,6 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     finish(sum);
     if (lane == 0)
         counters[row_tile] = 0;  // re-arm for the next call on this workspace
-#ifdef FP6_TRACE_TIMES
-    if (lane == 0)
-        trace[2] = wall_clock64();
-#endif
 }
 
 }  // namespace fp6

@@ -14,33 +14,29 @@ namespace {
 using namespace fp6;
 
 constexpr int kLayoutVersion = 1;
-// Configurations of the streaming kernel, by token count.  {token tiles per wave, waves per block, weight
-// tiles in flight per wave, k-tiles per activation stage, resident waves per CU aimed for (sets split-K),
-// iterations over which the activation copies of a stage are spread}.
+// Configurations of the streaming kernel: {token tiles per wave, waves per block, weight tiles in flight per
+// wave, k-tiles per activation stage, iterations over which the activation copies of a stage are spread}.
+// For N <= 16 there are two block heights; the plan takes the one that fills the chip best for the shape.
 struct StreamCfg {
-    int nt, waves, depth, stage, target, spread = 1;
+    int nt, waves, depth, stage, spread = 1;
 };
-#ifndef FP6_SMALL_N
-#define FP6_SMALL_N 4
-#endif
 #ifndef FP6_SCFG0
-#define FP6_SCFG0 {1, 4, 4, 4, 4}
+#define FP6_SCFG0 {1, 4, 4, 4}
 #endif
 #ifndef FP6_SCFG1
-#define FP6_SCFG1 {1, 4, 4, 4, 4}
+#define FP6_SCFG1 {1, 8, 4, 4}
 #endif
 #ifndef FP6_SCFG2
-#define FP6_SCFG2 {2, 8, 2, 2, 8}
+#define FP6_SCFG2 {2, 8, 2, 2}
 #endif
 #ifndef FP6_SCFG3
-#define FP6_SCFG3 {4, 8, 2, 2, 8}
+#define FP6_SCFG3 {4, 8, 2, 2}
 #endif
-constexpr int kStreamClasses = 4;
-constexpr StreamCfg kStreamCfg[kStreamClasses] = {FP6_SCFG0, FP6_SCFG1, FP6_SCFG2, FP6_SCFG3};
+constexpr int kStreamCfgs = 4;
+constexpr StreamCfg kStreamCfg[kStreamCfgs] = {FP6_SCFG0, FP6_SCFG1, FP6_SCFG2, FP6_SCFG3};
 // the fp16 weight source needs 32 registers per tile in flight: its own, shallower table
-constexpr StreamCfg kStreamCfgFp16[kStreamClasses] = {{1, 8, 2, 4, 8}, {1, 8, 2, 4, 8}, {2, 8, 2, 2, 8}, {4, 8, 2, 2, 8}};
-constexpr int kStreamClassMaxN[kStreamClasses] = {FP6_SMALL_N, 16, 32, 64};  // largest N each class serves
-constexpr int kStreamMaxN = kStreamClassMaxN[kStreamClasses - 1];  // token counts up to this use the streaming kernel
+constexpr StreamCfg kStreamCfgFp16[kStreamCfgs] = {{1, 8, 2, 4}, {1, 8, 2, 4}, {2, 8, 2, 2}, {4, 8, 2, 2}};
+constexpr int kStreamMaxN = 64;  // token counts up to this use the streaming kernel
 constexpr int kCus = 256;
 
 std::atomic<int> g_forced_split{0};
@@ -49,7 +45,7 @@ bool shape_ok(int64_t M, int64_t K) { return M > 0 && K > 0 && M % kTileRows == 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct StreamPlan {
-    int cls;         // index into kStreamCfg
+    int cfg;         // index into kStreamCfg / kStreamCfgFp16
     int nt;          // 16-token tiles handled per launch
     int split;       // split-K factor
     int row_blocks;  // blocks along M
@@ -58,37 +54,61 @@ struct StreamPlan {
     size_t total_bytes() const { return split > 1 ? counter_bytes + partial_bytes : 0; }
 };
 
-int stream_class(int64_t N)
-{
-    for (int c = 0; c < kStreamClasses - 1; ++c)
-        if (N <= kStreamClassMaxN[c])
-            return c;
-    return kStreamClasses - 1;
-}
-
+// The layer is bound by memory, every block streams the same number of bytes, and one block per CU is
+// resident: the launch should be ONE round of at most 256 blocks, as many as possible.  Measured on the
+// 70B-class shapes at N = 16: 240 blocks of 8 waves beat 320 or 480 blocks of 4 waves by 15-20 %, and 172
+// blocks in one round beat 344 blocks in two.  So: for every available block height, the largest split-K
+// factor that keeps row blocks x S <= 256 (at least two k-tiles per slice); take the candidate with the
+// most blocks, on a tie the one with the smaller S (longer streams, fewer partial tiles).
 StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
 {
-    StreamPlan p;
-    p.cls = stream_class(N);
-    const StreamCfg &c = packed ? kStreamCfg[p.cls] : kStreamCfgFp16[p.cls];
+    const StreamCfg *table = packed ? kStreamCfg : kStreamCfgFp16;
     const int64_t row_tiles = M / kTileRows;
     const int64_t KT = K / kTileK;
-    p.nt = c.nt;
-    int64_t s = g_forced_split.load(std::memory_order_relaxed);
-    if (s <= 0)
-        s = ((int64_t)kCus * c.target + row_tiles - 1) / row_tiles;
+    const int first = N <= 16 ? 0 : (N <= 32 ? 2 : 3);
+    const int last = N <= 16 ? 1 : first;
+    const int64_t forced = g_forced_split.load(std::memory_order_relaxed);
     const int64_t max_split = KT >= 4 ? KT / 2 : 1;  // at least two k-tiles per slice
-    if (s > max_split)
-        s = max_split;
-    if (s > 64)
-        s = 64;
-    if (s < 1)
-        s = 1;
-    // the kernel addresses the partial tiles with 32-bit byte offsets
-    while (s > 1 && (uint64_t)s * (uint64_t)row_tiles * (uint64_t)c.nt * 1024u >= (1ull << 31))
-        s /= 2;
-    p.split = (int)s;
-    p.row_blocks = (int)((row_tiles + c.waves - 1) / c.waves);
+    int best = first;
+    int64_t best_s = 1, best_blocks = -1;
+    bool best_single = false;
+    for (int c = first; c <= last; ++c) {
+        const int64_t rb = (row_tiles + table[c].waves - 1) / table[c].waves;
+        int64_t s = forced > 0 ? forced : kCus / rb;
+        if (s > max_split)
+            s = max_split;
+        if (s > 64)
+            s = 64;
+        if (s < 1)
+            s = 1;
+        // the kernel addresses the partial tiles with 32-bit byte offsets
+        while (s > 1 && (uint64_t)s * (uint64_t)row_tiles * (uint64_t)table[c].nt * 1024u >= (1ull << 31))
+            s /= 2;
+        const int64_t blocks = rb * s;
+        const bool single = blocks <= kCus;
+        bool better;
+        if (best_blocks < 0)
+            better = true;
+        else if (single != best_single)
+            better = single;
+        else if (single)
+            better = blocks > best_blocks || (blocks == best_blocks && s < best_s);
+        else
+            better = blocks < best_blocks;  // several rounds either way: the fewer, taller blocks
+        if (better) {
+            best = c;
+            best_s = s;
+            best_blocks = blocks;
+            best_single = single;
+        }
+        if (forced > 0)
+            break;  // the tuning hook pins the first candidate, so that tests reach every split factor
+    }
+    StreamPlan p;
+    p.cfg = best;
+    p.nt = table[best].nt;
+    p.split = (int)best_s;
+    p.row_blocks = (int)((row_tiles + table[best].waves - 1) / table[best].waves);
     p.counter_bytes = (((size_t)row_tiles * sizeof(int)) + 255) / 256 * 256;  // one arrival counter per row tile
     p.partial_bytes = (size_t)p.split * (size_t)row_tiles * (size_t)p.nt * 64 * sizeof(float4_t);
     return p;
@@ -250,7 +270,7 @@ fp6_status launch_stream(const void *weights, const void *scales, const void *X,
     int *counters = static_cast<int *>(workspace);
     float4_t *partials =
         p.total_bytes() ? reinterpret_cast<float4_t *>(static_cast<uint8_t *>(workspace) + p.counter_bytes) : nullptr;
-    switch (p.cls) {
+    switch (p.cfg) {
     case 0: return launch_stream_cfg<Src, 0>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
     case 1: return launch_stream_cfg<Src, 1>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
     case 2: return launch_stream_cfg<Src, 2>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);

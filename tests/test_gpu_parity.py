@@ -172,6 +172,19 @@ def test_linear_token_counts(pkg, oracle, N):
     _check_linear(Y, Y_ref, "N=%d" % N)
 
 
+@pytest.mark.parametrize("M,K,N", [(10256, 1536, 5), (10240, 1536, 16), (28672, 512, 3)])
+def test_linear_tall_stream_blocks(pkg, oracle, M, K, N):
+    """Shapes for which the plan takes the 8-wave block of the N <= 16 streaming kernel (more blocks fit one
+    round than with 4-wave blocks), with and without a ragged last block and with / without split-K."""
+    _say("tall stream blocks M=%d K=%d N=%d" % (M, K, N))
+    W = workloads.make_weights(M, K, seed=11)
+    packed, scales = oracle.quantize_pack(_np16(W))
+    X = workloads.make_activations(N, K, seed=N)
+    Y = pkg.fp6_linear(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), X.cuda(), M, K)
+    torch.cuda.synchronize()
+    _check_linear(_np16(Y), oracle.linear(packed, scales, _np16(X), M, K), "tall blocks")
+
+
 @pytest.mark.parametrize("split", [1, 2, 3, 5, 64])
 @pytest.mark.parametrize("N", [5, 32])
 def test_linear_split_k(pkg, oracle, split, N):

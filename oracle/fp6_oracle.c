@@ -338,6 +338,258 @@ void fp6o_linear_f16(const uint16_t *W, const uint16_t *X, int64_t M, int64_t N,
     }
 }
 
+/* ====================================================================== *
+ * The 5-bit variant (W5A16).  The paper presents its scheme as independent of
+ * the bit-width (Section 1: "6-bit, 5-bit, 3-bit, etc."; Section 5.2: the
+ * pre-packing applies to any x; Section 5.3: the cast of Eq. 3 applies to any
+ * bit-width).  FP5 is read as e2m2: code = s e1 e0 m1 m0, Eq. 1 with
+ * bias = 2^(2-1)-1 = 1, the E = 0 binade subnormal (0.M * 2^(1-bias)) and E = 3
+ * an ordinary binade, exactly as for e3m2: values 0 .25 .5 .75 | 1 1.25 1.5 1.75
+ * | 2 2.5 3 3.5 | 4 5 6 7.  Quantizer: the same recipe with 7 in place of 28.
+ * Everything below mirrors the 6-bit functions above, written out again.
+ * ====================================================================== */
+
+#define FP5O_TILE_BYTES 2560 /* 16 * 256 * 5 / 8 */
+
+double fp5o_decode(int code)
+{
+    int S = (code >> 4) & 1;
+    int E = (code >> 2) & 3;
+    int M = code & 3;
+    double mag;
+    if (E == 0)
+        mag = ldexp(M / 4.0, 1 - 1); /* 0.M * 2^(1-bias) */
+    else
+        mag = ldexp(1.0 + M / 4.0, E - 1); /* 1.M * 2^(E-bias) */
+    return S ? -mag : mag;
+}
+
+/* fp16 nearest to amax/7 (ties to even), decided with exact arithmetic. */
+uint16_t fp5o_scale_for_amax(uint16_t amax_bits)
+{
+    double a = fp6o_half_to_double((uint16_t)(amax_bits & 0x7fffu));
+    uint16_t guess = fp6o_double_to_half(a / 7.0);
+    int lo = guess > 0 ? guess - 1 : 0;
+    int hi = guess + 1;
+    int best = -1;
+    double best_err = 0.0;
+    for (int h = lo; h <= hi; ++h) {
+        double err = fabs(7.0 * fp6o_half_to_double((uint16_t)h) - a); /* exact */
+        if (best < 0 || err < best_err || (err == best_err && (h & 1) == 0 && (best & 1) == 1)) {
+            best = h;
+            best_err = err;
+        }
+    }
+    return (uint16_t)best;
+}
+
+/* Sign bit copied, magnitude = grid point nearest to |w|/scale, ties to the even code,
+ * beyond the grid saturates at 7; the differences are exact in double. */
+int fp5o_quantize_one(uint16_t w_bits, uint16_t scale_bits)
+{
+    int sign = (w_bits >> 15) & 1;
+    double a = fp6o_half_to_double((uint16_t)(w_bits & 0x7fffu));
+    double s = fp6o_half_to_double((uint16_t)(scale_bits & 0x7fffu));
+    if (s == 0.0)
+        return sign << 4;
+    int best = 0;
+    double best_err = fabs(a - fp5o_decode(0) * s);
+    for (int g = 1; g < 16; ++g) {
+        double err = fabs(a - fp5o_decode(g) * s);
+        if (err < best_err || (err == best_err && (g & 1) == 0)) {
+            best = g;
+            best_err = err;
+        }
+    }
+    return (sign << 4) | best;
+}
+
+int fp5o_quantize(const uint16_t *W, int64_t M, int64_t K, uint8_t *codes, uint16_t *scales)
+{
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        uint16_t amax = 0;
+        for (int64_t k = 0; k < K; ++k) {
+            uint16_t mag = (uint16_t)(W[m * K + k] & 0x7fffu);
+            if (mag >= 0x7c00u)
+                bad |= 1;
+            if (mag > amax)
+                amax = mag;
+        }
+        uint16_t sc = fp5o_scale_for_amax(amax);
+        scales[m] = sc;
+        for (int64_t k = 0; k < K; ++k)
+            codes[m * K + k] = (uint8_t)fp5o_quantize_one(W[m * K + k], sc);
+    }
+    return bad;
+}
+
+int64_t fp5o_packed_bytes(int64_t M, int64_t K) { return M * K * 5 / 8; }
+
+/*
+ * Bit address, in the packed 5-bit stream, of bit b of the code of weight (m, k);
+ * b = 0..4 = m0, m1, e0, e1, s.
+ *
+ * Tiles of 16 rows x 256 columns, row-tile major, 2560 bytes each.  A tile is two
+ * planes of 1024 bytes (64 slots of 16 bytes) followed by one plane of 512 bytes
+ * (64 slots of 8 bytes); slot = 16*q + r as in the 6-bit layout.  The slot owns
+ * ten 32-bit words: words 0..3 in plane 0, 4..7 in plane 1, 8..9 in plane 2.
+ * Words 0..4 (D0..D4) serve column runs 0..3, words 5..9 runs 4..7.  The 32 codes
+ * of four runs, index i = 8*(run%4) + j, are placed so that shifts and masks on
+ * whole words rebuild four codes at a time (Section 5.3): code i < 20 sits in
+ * place in byte i%4 of D[i/4] as  s . . . e1 e0 m1 m0  (sign at bit 7, the rest at
+ * bits 3..0, i.e. the top byte of the fp16 that Eq. 3 asks for); that leaves bits
+ * 6, 5, 4 of all twenty bytes free, and the remaining twelve codes (i = 20..31,
+ * byte lane i%4, group g = (i-20)/4) are spread over them:
+ *   g = 0:  s -> D0.6   e1 -> D0.5   e0 -> D0.4   m1 -> D1.6   m0 -> D1.5
+ *   g = 1:  s -> D1.4   e1 -> D2.6   e0 -> D2.5   m1 -> D2.4   m0 -> D3.6
+ *   g = 2:  s -> D3.5   e1 -> D3.4   e0 -> D4.6   m1 -> D4.5   m0 -> D4.4
+ * (Dn.x = bit x of the byte of lane i%4 in word Dn).
+ */
+uint64_t fp5o_pos(int64_t K, int64_t m, int64_t k, int b)
+{
+    static const int spread_word[3][5] = { /* indexed [g][b], b = m0 m1 e0 e1 s */
+        {1, 1, 0, 0, 0}, {3, 2, 2, 2, 1}, {4, 4, 4, 3, 3}};
+    static const int spread_bit[3][5] = {
+        {5, 6, 4, 5, 6}, {6, 4, 5, 6, 4}, {4, 5, 6, 4, 5}};
+    int64_t row_tile = m / FP6O_TILE_ROWS;
+    int r = (int)(m % FP6O_TILE_ROWS);
+    int64_t k_tile = k / FP6O_TILE_K;
+    int kk = (int)(k % FP6O_TILE_K);
+    int run = kk / 32;
+    int q = (kk % 32) / 8;
+    int j = kk % 8;
+    int slot = 16 * q + r;
+    int half = run / 4;           /* 0: words 0..4, 1: words 5..9 */
+    int i = 8 * (run % 4) + j;    /* index among the 32 codes of the four runs */
+    int lane_byte = i % 4;
+    int word, bit;
+    if (i < 20) {
+        word = i / 4;
+        bit = (b == 4) ? 7 : b;
+    } else {
+        int g = (i - 20) / 4;
+        word = spread_word[g][b];
+        bit = spread_bit[g][b];
+    }
+    int d = 5 * half + word;      /* word of the slot, 0..9 */
+    uint64_t tile = (uint64_t)(row_tile * (K / FP6O_TILE_K) + k_tile);
+    uint64_t in_tile = d < 8 ? (uint64_t)(d / 4) * 1024u + (uint64_t)slot * 16u + (uint64_t)(d % 4) * 4u
+                             : 2048u + (uint64_t)slot * 8u + (uint64_t)(d - 8) * 4u;
+    return (tile * FP5O_TILE_BYTES + in_tile + (uint64_t)lane_byte) * 8u + (uint64_t)bit;
+}
+
+void fp5o_pack(const uint8_t *codes, int64_t M, int64_t K, uint8_t *packed)
+{
+    memset(packed, 0, (size_t)fp5o_packed_bytes(M, K));
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k)
+            for (int b = 0; b < 5; ++b)
+                if ((codes[m * K + k] >> b) & 1) {
+                    uint64_t p = fp5o_pos(K, m, k, b);
+                    packed[p >> 3] |= (uint8_t)(1u << (p & 7));
+                }
+}
+
+void fp5o_unpack_codes(const uint8_t *packed, int64_t M, int64_t K, uint8_t *codes)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            int c = 0;
+            for (int b = 0; b < 5; ++b) {
+                uint64_t p = fp5o_pos(K, m, k, b);
+                c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
+            }
+            codes[m * K + k] = (uint8_t)c;
+        }
+}
+
+int fp5o_quantize_pack(const uint16_t *W, int64_t M, int64_t K, uint8_t *packed, uint16_t *scales)
+{
+    uint8_t *codes = (uint8_t *)malloc((size_t)(M * K));
+    if (!codes)
+        return 2;
+    int bad = fp5o_quantize(W, M, K, codes, scales);
+    fp5o_pack(codes, M, K, packed);
+    free(codes);
+    return bad;
+}
+
+/* nearest fp16 to decode(code)*scale: the product is exact in double, rounded once. */
+int fp5o_unpack(const uint8_t *packed, const uint16_t *scales, int64_t M, int64_t K, uint16_t *W)
+{
+    uint8_t *codes = (uint8_t *)malloc((size_t)(M * K));
+    if (!codes)
+        return 2;
+    fp5o_unpack_codes(packed, M, K, codes);
+    for (int64_t m = 0; m < M; ++m) {
+        double s = fp6o_half_to_double(scales[m]);
+        for (int64_t k = 0; k < K; ++k)
+            W[m * K + k] = fp6o_double_to_half(fp5o_decode(codes[m * K + k]) * s);
+    }
+    free(codes);
+    return 0;
+}
+
+/* Y[n][i] = scale * sum_k decode(code[row][k]) * X[n][k], k ascending, in double. */
+void fp5o_linear_codes(const uint8_t *codes, const uint16_t *scales, const uint16_t *X, int64_t M,
+                       int64_t N, int64_t K, const int64_t *rows, int64_t nrows, double *Y)
+{
+    if (!rows)
+        nrows = M;
+    double *Xd = (double *)malloc((size_t)(N * K) * sizeof(double));
+    for (int64_t i = 0; i < N * K; ++i)
+        Xd[i] = fp6o_half_to_double(X[i]);
+    double table[32];
+    for (int c = 0; c < 32; ++c)
+        table[c] = fp5o_decode(c);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t m = rows ? rows[i] : i;
+        double s = fp6o_half_to_double(scales[m]);
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += table[codes[m * K + k]] * Xd[n * K + k];
+            Y[n * nrows + i] = s * acc;
+        }
+    }
+    free(Xd);
+}
+
+int fp5o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X, int64_t M,
+                int64_t N, int64_t K, const int64_t *rows, int64_t nrows, double *Y)
+{
+    if (!rows)
+        nrows = M;
+    uint8_t *codes = (uint8_t *)malloc((size_t)(nrows * K));
+    uint16_t *sc = (uint16_t *)malloc((size_t)nrows * sizeof(uint16_t));
+    if (!codes || !sc) {
+        free(codes);
+        free(sc);
+        return 2;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t m = rows ? rows[i] : i;
+        sc[i] = scales[m];
+        for (int64_t k = 0; k < K; ++k) {
+            int c = 0;
+            for (int b = 0; b < 5; ++b) {
+                uint64_t p = fp5o_pos(K, m, k, b);
+                c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
+            }
+            codes[i * K + k] = (uint8_t)c;
+        }
+    }
+    fp5o_linear_codes(codes, sc, X, nrows, N, K, NULL, nrows, Y);
+    free(codes);
+    free(sc);
+    return 0;
+}
+
 #ifdef _OPENMP
 #include <omp.h>
 int fp6o_threads(void) { return omp_get_max_threads(); }

@@ -124,14 +124,36 @@ fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Tuning hook for benchmarks: force the split-K factor used by fp6_linear and
- * fp16_linear (0 = choose automatically, the default).  Process-wide; affects the
+ * The same three calls for 5-bit weights (W5A16).  The paper presents its pre-packing
+ * and its cast to fp16 as independent of the bit-width (Section 1: "6-bit, 5-bit,
+ * 3-bit, etc."; Sections 5.2 and 5.3).  FP5 is e2m2: code = s e1 e0 m1 m0, Eq. 1 with
+ * bias 2^(2-1)-1 = 1, subnormal E = 0 binade, no inf/NaN: magnitudes 0 .25 .5 .75,
+ * 1 .. 1.75, 2 .. 3.5, 4 .. 7.  Quantizer: scale[m] = fp16_rne(max_k |W[m][k]| / 7),
+ * nearest e2m2 magnitude of |W| / scale, ties to the even code, saturating at 7.
+ * The packed stream has fp5_packed_bytes(M, K) = 5*M*K/8 bytes (tiles of 2560 bytes)
+ * and is de-quantized in registers with whole-word shifts and masks and the
+ * exponent-bias multiply of Eq. 3, the gfx950 having no conversion for this format.
+ * Arguments, layouts of W, X, Y, scales, workspace rules, shapes, alignment and error
+ * behaviour are those of the fp6_ calls; the workspace size is that of fp6_linear.
+ */
+size_t fp5_packed_bytes(int64_t M, int64_t K);
+size_t fp5_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
+fp6_status fp5_quantize_pack(const void *W_f16, int64_t M, int64_t K, void *packed, void *scales_f16,
+                             void *stream);
+fp6_status fp5_unpack(const void *packed, const void *scales_f16, int64_t M, int64_t K, void *W_f16_out,
+                      void *stream);
+fp6_status fp5_linear(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                      int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Tuning hook for benchmarks: force the split-K factor used by fp6_linear, fp5_linear
+ * and fp16_linear (0 = choose automatically, the default).  Process-wide; affects the
  * workspace size queries as well.  Values the shape cannot honour are clamped.
  */
 void fp6_tuning_set_split_k(int split_k);
 
 /*
- * Tuning hook for benchmarks: force the block tile of the kernel used for N > 32:
+ * Tuning hook for benchmarks: force the block tile of the kernel used for N > 64:
  * block_rows in {128, 256} output channels x block_tokens in {64, 128} tokens; any
  * other pair restores the automatic choice.  fp16_linear uses 128 rows where 256 is
  * asked for.  Process-wide; affects the workspace size queries as well.

@@ -55,6 +55,16 @@ def load_library():
     L.fp6_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
     L.fp16_linear.restype = ci
     L.fp16_linear.argtypes = [vp, vp, vp, i64, i64, i64, vp, sz, vp]
+    L.fp5_packed_bytes.restype = sz
+    L.fp5_packed_bytes.argtypes = [i64, i64]
+    L.fp5_linear_workspace_bytes.restype = sz
+    L.fp5_linear_workspace_bytes.argtypes = [i64, i64, i64]
+    L.fp5_quantize_pack.restype = ci
+    L.fp5_quantize_pack.argtypes = [vp, i64, i64, vp, vp, vp]
+    L.fp5_unpack.restype = ci
+    L.fp5_unpack.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.fp5_linear.restype = ci
+    L.fp5_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
     L.fp6_tuning_set_split_k.restype = None
     L.fp6_tuning_set_split_k.argtypes = [ci]
     L.fp6_tuning_set_tile.restype = None
@@ -117,15 +127,13 @@ def _new_workspace(nbytes: int, device) -> Optional[torch.Tensor]:
     return torch.zeros(nbytes, dtype=torch.uint8, device=device)
 
 
-def fp6_quantize_pack(W: torch.Tensor, packed: Optional[torch.Tensor] = None,
-                      scales: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
-    """fp16 [M][K] -> (packed uint8 [3MK/4], scales fp16 [M])."""
+def _quantize_pack(prefix: str, W, packed, scales):
     L = load_library()
     _dev(W, torch.float16, "W")
     if W.dim() != 2:
         raise Fp6Error("W must be [M][K]")
     M, K = W.shape
-    nbytes = L.fp6_packed_bytes(M, K)
+    nbytes = getattr(L, prefix + "_packed_bytes")(M, K)
     if nbytes == 0:
         _check(2)
     if packed is None:
@@ -136,32 +144,29 @@ def fp6_quantize_pack(W: torch.Tensor, packed: Optional[torch.Tensor] = None,
     _dev(scales, torch.float16, "scales")
     if packed.numel() != nbytes or scales.numel() != M:
         raise Fp6Error("packed/scales have the wrong size")
-    _check(L.fp6_quantize_pack(W.data_ptr(), M, K, packed.data_ptr(), scales.data_ptr(), _stream()))
+    _check(getattr(L, prefix + "_quantize_pack")(W.data_ptr(), M, K, packed.data_ptr(), scales.data_ptr(), _stream()))
     return packed, scales
 
 
-def fp6_unpack(packed: torch.Tensor, scales: torch.Tensor, M: int, K: int,
-               out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """packed + scales -> fp16 [M][K]."""
+def _unpack(prefix: str, packed, scales, M, K, out):
     L = load_library()
     _dev(packed, torch.uint8, "packed")
     _dev(scales, torch.float16, "scales")
-    if L.fp6_packed_bytes(M, K) == 0:
+    nbytes = getattr(L, prefix + "_packed_bytes")(M, K)
+    if nbytes == 0:
         _check(2)
-    if packed.numel() != L.fp6_packed_bytes(M, K) or scales.numel() != M:
+    if packed.numel() != nbytes or scales.numel() != M:
         raise Fp6Error("packed/scales do not match M, K")
     if out is None:
         out = torch.empty((M, K), dtype=torch.float16, device=packed.device)
     _dev(out, torch.float16, "out")
     if out.numel() != M * K:
         raise Fp6Error("out has the wrong size")
-    _check(L.fp6_unpack(packed.data_ptr(), scales.data_ptr(), M, K, out.data_ptr(), _stream()))
+    _check(getattr(L, prefix + "_unpack")(packed.data_ptr(), scales.data_ptr(), M, K, out.data_ptr(), _stream()))
     return out
 
 
-def fp6_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
-               out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Y[N][M] = X[N][K] @ dequant(packed, scales)[M][K]^T  (fp16 in, fp16 out)."""
+def _linear(prefix: str, packed, scales, X, M, K, out, workspace):
     L = load_library()
     _dev(packed, torch.uint8, "packed")
     _dev(scales, torch.float16, "scales")
@@ -169,9 +174,10 @@ def fp6_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: i
     if X.dim() != 2 or X.shape[1] != K:
         raise Fp6Error("X must be [N][K]")
     N = X.shape[0]
-    if L.fp6_packed_bytes(M, K) == 0 or N == 0:
+    nbytes = getattr(L, prefix + "_packed_bytes")(M, K)
+    if nbytes == 0 or N == 0:
         _check(2)
-    if packed.numel() != L.fp6_packed_bytes(M, K) or scales.numel() != M:
+    if packed.numel() != nbytes or scales.numel() != M:
         raise Fp6Error("packed/scales do not match M, K")
     if out is None:
         out = torch.empty((N, M), dtype=torch.float16, device=X.device)
@@ -179,11 +185,53 @@ def fp6_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: i
     if out.numel() != N * M:
         raise Fp6Error("out has the wrong size")
     if workspace is None:
-        workspace = _new_workspace(L.fp6_linear_workspace_bytes(M, N, K), X.device)
+        workspace = _new_workspace(getattr(L, prefix + "_linear_workspace_bytes")(M, N, K), X.device)
     ws_ptr, ws_len = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
-    _check(L.fp6_linear(packed.data_ptr(), scales.data_ptr(), X.data_ptr(), out.data_ptr(), M, N, K,
-                        ws_ptr, ws_len, _stream()))
+    _check(getattr(L, prefix + "_linear")(packed.data_ptr(), scales.data_ptr(), X.data_ptr(), out.data_ptr(), M, N, K,
+                                          ws_ptr, ws_len, _stream()))
     return out
+
+
+def fp6_quantize_pack(W: torch.Tensor, packed: Optional[torch.Tensor] = None,
+                      scales: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """fp16 [M][K] -> (packed uint8 [3MK/4], scales fp16 [M])."""
+    return _quantize_pack("fp6", W, packed, scales)
+
+
+def fp6_unpack(packed: torch.Tensor, scales: torch.Tensor, M: int, K: int,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """packed + scales -> fp16 [M][K]."""
+    return _unpack("fp6", packed, scales, M, K, out)
+
+
+def fp6_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
+               out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y[N][M] = X[N][K] @ dequant(packed, scales)[M][K]^T  (fp16 in, fp16 out)."""
+    return _linear("fp6", packed, scales, X, M, K, out, workspace)
+
+
+def fp5_packed_bytes(M: int, K: int) -> int:
+    return int(load_library().fp5_packed_bytes(M, K))
+
+
+def fp5_linear_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load_library().fp5_linear_workspace_bytes(M, N, K))
+
+
+def fp5_quantize_pack(W: torch.Tensor, packed: Optional[torch.Tensor] = None,
+                      scales: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """fp16 [M][K] -> (packed uint8 [5MK/8], scales fp16 [M]), e2m2 codes."""
+    return _quantize_pack("fp5", W, packed, scales)
+
+
+def fp5_unpack(packed: torch.Tensor, scales: torch.Tensor, M: int, K: int,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    return _unpack("fp5", packed, scales, M, K, out)
+
+
+def fp5_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
+               out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    return _linear("fp5", packed, scales, X, M, K, out, workspace)
 
 
 def fp16_linear(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] = None,

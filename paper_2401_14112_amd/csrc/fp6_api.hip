@@ -284,6 +284,54 @@ fp6_status launch_stream(const void *weights, const void *scales, const void *X,
     }
 }
 
+template <class Fmt>
+fp6_status quantize_pack_impl(const void *W_f16, int64_t M, int64_t K, void *packed, void *scales_f16, void *stream)
+{
+    if (!W_f16 || !packed || !scales_f16)
+        return FP6_ERR_NULL;
+    if (!shape_ok(M, K))
+        return FP6_ERR_SHAPE;
+    if (!aligned16(W_f16) || !aligned16(packed) || !aligned16(scales_f16))
+        return FP6_ERR_ALIGN;
+    hipLaunchKernelGGL(quantize_pack_kernel<Fmt>, dim3((unsigned)(M / kTileRows)), dim3(kPackWaves * 64), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const half_t *>(W_f16), (int)M, (int)K,
+                       static_cast<uint8_t *>(packed), static_cast<half_t *>(scales_f16));
+    return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+}
+
+template <class Src>
+fp6_status unpack_impl(const void *packed, const void *scales_f16, int64_t M, int64_t K, void *W_f16_out, void *stream)
+{
+    if (!packed || !scales_f16 || !W_f16_out)
+        return FP6_ERR_NULL;
+    if (!shape_ok(M, K))
+        return FP6_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(W_f16_out))
+        return FP6_ERR_ALIGN;
+    const int64_t tiles = (M / kTileRows) * (K / kTileK);
+    hipLaunchKernelGGL(unpack_kernel<Src>, dim3((unsigned)((tiles + 3) / 4)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const uint8_t *>(packed),
+                       static_cast<const half_t *>(scales_f16), (int)M, (int)K, static_cast<half_t *>(W_f16_out));
+    return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+}
+
+template <class Src>
+fp6_status packed_linear_impl(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                              int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!packed || !scales_f16 || !X_f16 || !Y_f16)
+        return FP6_ERR_NULL;
+    if (!shape_ok(M, K) || N <= 0 || N >= (1ll << 31))
+        return FP6_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(X_f16) || !aligned16(Y_f16))
+        return FP6_ERR_ALIGN;
+    if (N > kStreamMaxN)
+        return launch_tiled<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
+                                 static_cast<hipStream_t>(stream));
+    return launch_stream<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
+                              static_cast<hipStream_t>(stream));
+}
+
 }  // namespace
 
 extern "C" {
@@ -345,47 +393,40 @@ fp6_status fp6_workspace_init(void *workspace, size_t workspace_bytes, void *str
 
 fp6_status fp6_quantize_pack(const void *W_f16, int64_t M, int64_t K, void *packed, void *scales_f16, void *stream)
 {
-    if (!W_f16 || !packed || !scales_f16)
-        return FP6_ERR_NULL;
-    if (!shape_ok(M, K))
-        return FP6_ERR_SHAPE;
-    if (!aligned16(W_f16) || !aligned16(packed) || !aligned16(scales_f16))
-        return FP6_ERR_ALIGN;
-    hipLaunchKernelGGL(quantize_pack_kernel, dim3((unsigned)(M / kTileRows)), dim3(kPackWaves * 64), 0,
-                       static_cast<hipStream_t>(stream), static_cast<const half_t *>(W_f16), (int)M, (int)K,
-                       static_cast<uint8_t *>(packed), static_cast<half_t *>(scales_f16));
-    return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+    return quantize_pack_impl<E3M2Format>(W_f16, M, K, packed, scales_f16, stream);
 }
 
 fp6_status fp6_unpack(const void *packed, const void *scales_f16, int64_t M, int64_t K, void *W_f16_out, void *stream)
 {
-    if (!packed || !scales_f16 || !W_f16_out)
-        return FP6_ERR_NULL;
-    if (!shape_ok(M, K))
-        return FP6_ERR_SHAPE;
-    if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(W_f16_out))
-        return FP6_ERR_ALIGN;
-    const int64_t tiles = (M / kTileRows) * (K / kTileK);
-    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((tiles + 3) / 4)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), static_cast<const uint8_t *>(packed),
-                       static_cast<const half_t *>(scales_f16), (int)M, (int)K, static_cast<half_t *>(W_f16_out));
-    return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+    return unpack_impl<PackedFp6Source>(packed, scales_f16, M, K, W_f16_out, stream);
 }
 
 fp6_status fp6_linear(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N,
                       int64_t K, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!packed || !scales_f16 || !X_f16 || !Y_f16)
-        return FP6_ERR_NULL;
-    if (!shape_ok(M, K) || N <= 0 || N >= (1ll << 31))
-        return FP6_ERR_SHAPE;
-    if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(X_f16) || !aligned16(Y_f16))
-        return FP6_ERR_ALIGN;
-    if (N > kStreamMaxN)
-        return launch_tiled<PackedFp6Source>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
-                                             static_cast<hipStream_t>(stream));
-    return launch_stream<PackedFp6Source>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
-                                          static_cast<hipStream_t>(stream));
+    return packed_linear_impl<PackedFp6Source>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
+                                               stream);
+}
+
+size_t fp5_packed_bytes(int64_t M, int64_t K) { return shape_ok(M, K) ? (size_t)(M * K / 8 * 5) : 0; }
+
+size_t fp5_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) { return fp6_linear_workspace_bytes(M, N, K); }
+
+fp6_status fp5_quantize_pack(const void *W_f16, int64_t M, int64_t K, void *packed, void *scales_f16, void *stream)
+{
+    return quantize_pack_impl<E2M2Format>(W_f16, M, K, packed, scales_f16, stream);
+}
+
+fp6_status fp5_unpack(const void *packed, const void *scales_f16, int64_t M, int64_t K, void *W_f16_out, void *stream)
+{
+    return unpack_impl<PackedFp5Source>(packed, scales_f16, M, K, W_f16_out, stream);
+}
+
+fp6_status fp5_linear(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N,
+                      int64_t K, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return packed_linear_impl<PackedFp5Source>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
+                                               stream);
 }
 
 fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N, int64_t K,

@@ -110,6 +110,17 @@ __device__ __forceinline__ void wait_loads()
 }
 
 __device__ __forceinline__ void pin(u32x4 &v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void pin(u32x2 &v) { asm volatile("" : "+v"(v)); }
+
+// 64-bit variant of issue_load_b128 (streaming policy), for planes that hold 8 bytes per lane.
+template <int IMM>
+__device__ __forceinline__ u32x2 issue_load_b64(rsrc_t rsrc, int lane_off)
+{
+    u32x2 r;
+    asm volatile("buffer_load_dwordx2 %0, %1, %2, 0 offen offset:%3 nt"
+                 : "=v"(r) : "v"(lane_off), "s"(rsrc), "n"(IMM) : "memory");
+    return r;
+}
 
 // Global -> LDS copy without passing through registers: lane i's 16 bytes land at LDS byte address
 // lds_base + IMM + 16*i (lds_base wave-uniform, placed in M0).  Counted by vmcnt like any other load;
@@ -193,6 +204,89 @@ struct PackedFp6Source {
         constexpr int o = (G & 1) * 16;
         even_run = (half8_t){h[o + 0], h[o + 1], h[o + 2], h[o + 3], h[o + 4], h[o + 5], h[o + 6], h[o + 7]};
         odd_run = (half8_t){h[o + 8], h[o + 9], h[o + 10], h[o + 11], h[o + 12], h[o + 13], h[o + 14], h[o + 15]};
+    }
+};
+
+// ---- 5-bit (e2m2) weights: the paper's scheme for a width the hardware cannot convert -------------
+// The paper presents its pre-packing and its cast as independent of the bit-width (Sections 5.2, 5.3).
+// CDNA4 has no conversion for e2m2, so this source de-quantizes the way Section 5.3 does, with shifts and
+// masks on whole words (four codes per 32-bit operation) and the exponent-bias multiply of Eq. 3.
+// Tile: 16 rows x 256 columns = 2560 bytes = two planes of 16 bytes per lane and one of 8 bytes per lane;
+// lane L = 16q + r owns ten words, D0..D4 for runs 0..3 and another five for runs 4..7.  Of the 32 codes
+// of four runs (index i = 8*(run%4) + j), the first twenty sit in place in byte i%4 of D[i/4] as
+// "s...EEMM" - the top byte of the fp16 that Eq. 3 asks for - and the other twelve are spread over the
+// free bits 6, 5, 4 of the twenty bytes:
+//   codes 20..23:  s -> D0.6  e1 e0 -> D0.5 D0.4  m1 m0 -> D1.6 D1.5
+//   codes 24..27:  s -> D1.4  e1 e0 m1 -> D2.6 D2.5 D2.4  m0 -> D3.6
+//   codes 28..31:  s -> D3.5  e1 -> D3.4  e0 m1 m0 -> D4.6 D4.5 D4.4
+// Unpack per 32 codes: 5 ANDs, 3 three-term stitches, then per four codes two byte permutes and two
+// packed multiplies by 2^(15-1) (exact, the subnormal binade included).
+__device__ __forceinline__ half8_t e2m2_bytes_to_fragment(uint32_t b_lo, uint32_t b_hi)
+{
+    const half2_t k = {(half_t)16384.0f, (half_t)16384.0f};
+    u32x4 r;
+    r[0] = bit_cast<uint32_t>(bit_cast<half2_t>(__builtin_amdgcn_perm(0u, b_lo, 0x010c000cu)) * k);  // [b1 0 b0 0]
+    r[1] = bit_cast<uint32_t>(bit_cast<half2_t>(__builtin_amdgcn_perm(0u, b_lo, 0x030c020cu)) * k);  // [b3 0 b2 0]
+    r[2] = bit_cast<uint32_t>(bit_cast<half2_t>(__builtin_amdgcn_perm(0u, b_hi, 0x010c000cu)) * k);
+    r[3] = bit_cast<uint32_t>(bit_cast<half2_t>(__builtin_amdgcn_perm(0u, b_hi, 0x030c020cu)) * k);
+    return bit_cast<half8_t>(r);
+}
+
+struct PackedFp5Source {
+    struct Tile {
+        u32x4 p0, p1;
+        u32x2 p2;
+    };
+    static constexpr bool kHasScale = true;
+    static constexpr bool kTallTile = true;
+    static constexpr int kLoads = 3;
+    static constexpr int kTileBytes5 = 2560;
+    static constexpr int kTileStride = kTileBytes5;
+    __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
+    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
+                                                        int64_t KT, int64_t /*K*/)
+    {
+        return make_rsrc(static_cast<const uint8_t *>(base) + (row_tile * KT + kt0) * kTileBytes5,
+                         (uint32_t)(kt1 - kt0) * kTileBytes5);
+    }
+    __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
+    __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
+    {
+        // the third plane holds 8 bytes per lane: its offset is the tile's base + 2048 + 8 * lane
+        const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        t.p0 = issue_load_b128<0, true>(r, off);
+        t.p1 = issue_load_b128<1024, true>(r, off);
+        t.p2 = issue_load_b64<2048>(r, off - 8 * lane);
+    }
+    __device__ static __forceinline__ void pin_tile(Tile &t)
+    {
+        pin(t.p0);
+        pin(t.p1);
+        pin(t.p2);
+    }
+    // A fragments of runs 2G (even) and 2G+1 (odd).  Runs 0..3 come from D = (p0[0..3], p1[0]), runs 4..7
+    // from D = (p1[1..3], p2[0..1]); inside a group of four runs, runs 0 and 1 are the in-place words
+    // D0..D3, run 2 is D4 and the first stitched word, run 3 the other two stitched words.
+    template <int G>
+    __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
+    {
+        uint32_t d0, d1, d2, d3, d4;
+        if (G < 2) {
+            d0 = t.p0[0], d1 = t.p0[1], d2 = t.p0[2], d3 = t.p0[3], d4 = t.p1[0];
+        } else {
+            d0 = t.p1[1], d1 = t.p1[2], d2 = t.p1[3], d3 = t.p2[0], d4 = t.p2[1];
+        }
+        constexpr uint32_t kInPlace = 0x8f8f8f8fu;
+        if ((G & 1) == 0) {
+            even_run = e2m2_bytes_to_fragment(d0 & kInPlace, d1 & kInPlace);
+            odd_run = e2m2_bytes_to_fragment(d2 & kInPlace, d3 & kInPlace);
+        } else {
+            const uint32_t s0 = ((d0 << 1) & 0x80808080u) | ((d0 >> 2) & 0x0c0c0c0cu) | ((d1 >> 5) & 0x03030303u);
+            const uint32_t s1 = ((d1 << 3) & 0x80808080u) | ((d2 >> 3) & 0x0e0e0e0eu) | ((d3 >> 6) & 0x01010101u);
+            const uint32_t s2 = ((d3 << 2) & 0x80808080u) | ((d3 >> 1) & 0x08080808u) | ((d4 >> 4) & 0x07070707u);
+            even_run = e2m2_bytes_to_fragment(d4 & kInPlace, s0);
+            odd_run = e2m2_bytes_to_fragment(s1, s2);
+        }
     }
 };
 

@@ -47,17 +47,105 @@ __device__ __forceinline__ RowScale make_row_scale(float scale)
 // grid midpoint m (the only case where the last bit matters), q = m(1+e), the fused remainder a - q*scale
 // is exact and the corrected value m(1+O(e^2)) rounds to m itself; everywhere else the exact quotient is
 // at least 2^-16 (relative) away from every midpoint, far more than the error of q.
+template <class Fmt>
 __device__ __forceinline__ uint32_t quantize_code(uint32_t w_bits, RowScale rs)
 {
     const uint32_t sign = (w_bits >> 15) & 1u;
     const float a = (float)bit_cast<half_t>((uint16_t)(w_bits & 0x7fffu));
     const float q = a * rs.inv;
     const float ratio = __builtin_fmaf(__builtin_fmaf(-q, rs.scale, a), rs.inv, q);
-    return (sign << 5) | e3m2_magnitude_code(ratio);  // zero scale: inv = 0 -> ratio = 0 -> sign-only code
+    return (sign << Fmt::kSignShift) | Fmt::magnitude_code(ratio);  // zero scale: inv = 0 -> ratio = 0 -> sign-only code
 }
+
+// ---- the two weight formats as the encoder sees them ---------------------------------------------
+// magnitude_code(ratio): grid point of |w|/scale (round to nearest, ties to the even code, saturating);
+// store_tile(): the lane's codes [run][j] (columns run*32 + 8q + j of its row) -> the lane's bytes of the tile.
+struct E3M2Format {
+    static constexpr float kMax = 28.0f;
+    static constexpr int kSignShift = 5;
+    static constexpr int kTileBytes = 3072;
+    __device__ static __forceinline__ uint32_t magnitude_code(float ratio) { return e3m2_magnitude_code(ratio); }
+    __device__ static __forceinline__ void store_tile(const uint32_t (&code)[8][8], uint8_t *tile, int lane)
+    {
+        // two dense streams: code i = 8*(run%4) + j at bits [6i, 6i+6) of stream run/4
+        uint32_t d[12];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            uint64_t a[4] = {0, 0, 0, 0};  // 192 bits (+ spill-over slot)
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                const uint64_t cd = code[4 * c + i / 8][i % 8];
+                const int pos = 6 * i, wd = pos >> 6, sh = pos & 63;
+                a[wd] |= cd << sh;
+                if (sh > 58)
+                    a[wd + 1] |= cd >> (64 - sh);
+            }
+#pragma unroll
+            for (int h = 0; h < 3; ++h) {
+                d[6 * c + 2 * h] = (uint32_t)a[h];
+                d[6 * c + 2 * h + 1] = (uint32_t)(a[h] >> 32);
+            }
+        }
+        u32x4 *t = reinterpret_cast<u32x4 *>(tile) + lane;
+        t[0] = (u32x4){d[0], d[1], d[2], d[3]};
+        t[64] = (u32x4){d[4], d[5], d[6], d[7]};
+        t[128] = (u32x4){d[8], d[9], d[10], d[11]};
+    }
+};
+
+// e2m2: grid 0 .25 .5 .75 | 1 .. 1.75 | 2 .. 3.5 | 4 .. 7 (Eq. 1 with bias 1, subnormal E = 0 binade).
+struct E2M2Format {
+    static constexpr float kMax = 7.0f;
+    static constexpr int kSignShift = 4;
+    static constexpr int kTileBytes = 2560;
+    __device__ static __forceinline__ uint32_t magnitude_code(float ratio)
+    {
+        uint32_t g;
+        if (ratio < 1.0f) {
+            g = (uint32_t)__builtin_rintf(ratio * 4.0f);  // subnormal binade: multiples of 1/4
+        } else {
+            uint32_t u = bit_cast<uint32_t>(ratio);
+            u += 0x000fffffu + ((u >> 21) & 1u);  // round the mantissa to 2 bits, half to even
+            g = (u >> 21) - (126u << 2);          // exponent field - 127 + bias 1, then 2 mantissa bits
+        }
+        return g < 15u ? g : 15u;
+    }
+    // code s e1 e0 m1 m0 -> byte s 0 0 0 e1 e0 m1 m0
+    __device__ static __forceinline__ uint32_t in_place(uint32_t c) { return ((c & 0x10u) << 3) | (c & 0x0fu); }
+    __device__ static __forceinline__ void store_tile(const uint32_t (&code)[8][8], uint8_t *tile, int lane)
+    {
+        uint32_t d[10];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            uint32_t w[5] = {0, 0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < 20; ++i)  // in place: byte i%4 of word i/4
+                w[i / 4] |= in_place(code[4 * c + i / 8][i % 8]) << (8 * (i % 4));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {  // byte lane b of the three spread groups (codes 20+b, 24+b, 28+b)
+                const uint32_t c0 = code[4 * c + 2][4 + b], c1 = code[4 * c + 3][b], c2 = code[4 * c + 3][4 + b];
+                const int sh = 8 * b;
+                // bits of a code: 4 = s, 3 = e1, 2 = e0, 1 = m1, 0 = m0
+                w[0] |= ((((c0 >> 4) & 1u) << 6) | (((c0 >> 2) & 3u) << 4)) << sh;                       // s, e1 e0
+                w[1] |= (((c0 & 3u) << 5) | (((c1 >> 4) & 1u) << 4)) << sh;                              // m1 m0 | s
+                w[2] |= (((c1 >> 1) & 7u) << 4) << sh;                                                   // e1 e0 m1
+                w[3] |= (((c1 & 1u) << 6) | (((c2 >> 4) & 1u) << 5) | (((c2 >> 3) & 1u) << 4)) << sh;    // m0 | s | e1
+                w[4] |= ((c2 & 7u) << 4) << sh;                                                          // e0 m1 m0
+            }
+#pragma unroll
+            for (int i = 0; i < 5; ++i)
+                d[5 * c + i] = w[i];
+        }
+        u32x4 *t = reinterpret_cast<u32x4 *>(tile) + lane;
+        t[0] = (u32x4){d[0], d[1], d[2], d[3]};
+        t[64] = (u32x4){d[4], d[5], d[6], d[7]};
+        reinterpret_cast<u32x2 *>(tile + 2048)[lane] = (u32x2){d[8], d[9]};
+    }
+};
 
 constexpr int kPackWaves = 16;  // waves per block of quantize_pack_kernel
 
+template <class Fmt>
 __global__ __launch_bounds__(kPackWaves * 64) void quantize_pack_kernel(const half_t *__restrict__ W, int M, int K,
                                                                         uint8_t *__restrict__ packed,
                                                                         half_t *__restrict__ scales)
@@ -86,7 +174,7 @@ __global__ __launch_bounds__(kPackWaves * 64) void quantize_pack_kernel(const ha
         }
         if (lane == 0) {
             const float a = (float)bit_cast<half_t>((uint16_t)amax);
-            const half_t sc = (half_t)(a / 28.0f);  // fp32 quotient, then one rounding to fp16
+            const half_t sc = (half_t)(a / Fmt::kMax);  // fp32 quotient, then one rounding to fp16
             scales[row_tile * kTileRows + r] = sc;
             s_scale[r] = (float)sc;
         }
@@ -104,37 +192,15 @@ __global__ __launch_bounds__(kPackWaves * 64) void quantize_pack_kernel(const ha
             const u32x4 v = *reinterpret_cast<const u32x4 *>(row + (int64_t)kt * kTileK + f * 32);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                code[f][2 * j] = quantize_code(v[j] & 0xffffu, scale);
-                code[f][2 * j + 1] = quantize_code(v[j] >> 16, scale);
+                code[f][2 * j] = quantize_code<Fmt>(v[j] & 0xffffu, scale);
+                code[f][2 * j + 1] = quantize_code<Fmt>(v[j] >> 16, scale);
             }
         }
-        // the lane's two dense streams: code i = 8*(run%4) + j at bits [6i, 6i+6) of stream run/4
-        uint32_t d[12];
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            uint64_t a[4] = {0, 0, 0, 0};  // 192 bits (+ spill-over slot)
-#pragma unroll
-            for (int i = 0; i < 32; ++i) {
-                const uint64_t cd = code[4 * c + i / 8][i % 8];
-                const int pos = 6 * i, wd = pos >> 6, sh = pos & 63;
-                a[wd] |= cd << sh;
-                if (sh > 58)
-                    a[wd + 1] |= cd >> (64 - sh);
-            }
-#pragma unroll
-            for (int h = 0; h < 3; ++h) {
-                d[6 * c + 2 * h] = (uint32_t)a[h];
-                d[6 * c + 2 * h + 1] = (uint32_t)(a[h] >> 32);
-            }
-        }
-        const u32x4 p0 = {d[0], d[1], d[2], d[3]}, p1 = {d[4], d[5], d[6], d[7]}, p2 = {d[8], d[9], d[10], d[11]};
-        u32x4 *tile = reinterpret_cast<u32x4 *>(packed + ((int64_t)row_tile * KT + kt) * kTileBytes) + lane;
-        tile[0] = p0;
-        tile[64] = p1;
-        tile[128] = p2;
+        Fmt::store_tile(code, packed + ((int64_t)row_tile * KT + kt) * Fmt::kTileBytes, lane);
     }
 }
 
+template <class Src>
 __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__ packed,
                                                      const half_t *__restrict__ scales, int M, int K,
                                                      half_t *__restrict__ W_out)
@@ -146,18 +212,18 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
         return;
     const int64_t row_tile = tile / KT, kt = tile % KT;
     const int r = lane & 15, q = lane >> 4;
-    const rsrc_t rs = PackedFp6Source::slice_rsrc(packed, row_tile, (int)kt, (int)kt + 1, KT, K);
-    PackedFp6Source::Tile t;
-    PackedFp6Source::issue(t, rs, PackedFp6Source::lane_offset(lane, 0, K));
+    const rsrc_t rs = Src::slice_rsrc(packed, row_tile, (int)kt, (int)kt + 1, KT, K);
+    typename Src::Tile t;
+    Src::issue(t, rs, Src::lane_offset(lane, 0, K));
     wait_loads<0>();
-    PackedFp6Source::pin_tile(t);
+    Src::pin_tile(t);
     const float scale = (float)scales[row_tile * kTileRows + r];
     half_t *out = W_out + (row_tile * kTileRows + r) * K + kt * kTileK + q * 8;
     half8_t frag[8];
-    PackedFp6Source::fragments<0>(t, frag[0], frag[1]);
-    PackedFp6Source::fragments<1>(t, frag[2], frag[3]);
-    PackedFp6Source::fragments<2>(t, frag[4], frag[5]);
-    PackedFp6Source::fragments<3>(t, frag[6], frag[7]);
+    Src::template fragments<0>(t, frag[0], frag[1]);
+    Src::template fragments<1>(t, frag[2], frag[3]);
+    Src::template fragments<2>(t, frag[4], frag[5]);
+    Src::template fragments<3>(t, frag[6], frag[7]);
 #pragma unroll
     for (int f = 0; f < 8; ++f) {
         half8_t y;

@@ -20,14 +20,16 @@ def lib():
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "fp6.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(fp6_\w+|fp16_\w+)\s*\(", text)
+    names = re.findall(r"\b(fp6_\w+|fp5_\w+|fp16_\w+)\s*\(", text)
     return sorted(set(names))
 
 
 def test_exports_every_declared_symbol(lib):
     names = _declared_functions()
     for expected in ("fp6_quantize_pack", "fp6_unpack", "fp6_linear", "fp16_linear", "fp6_packed_bytes",
-                     "fp6_linear_workspace_bytes", "fp6_workspace_init", "fp6_status_str", "fp6_layout_version"):
+                     "fp6_linear_workspace_bytes", "fp6_workspace_init", "fp6_status_str", "fp6_layout_version",
+                     "fp16_linear_workspace_bytes", "fp6_tuning_set_split_k", "fp6_tuning_set_tile",
+                     "fp5_quantize_pack", "fp5_unpack", "fp5_linear", "fp5_packed_bytes", "fp5_linear_workspace_bytes"):
         assert expected in names
     for n in names:
         assert hasattr(lib, n), "library does not export %s" % n
@@ -37,7 +39,8 @@ def test_binding_has_the_same_names():
     import paper_2401_14112_amd as pkg
 
     for n in ("fp6_quantize_pack", "fp6_unpack", "fp6_linear", "fp16_linear", "fp6_packed_bytes",
-              "fp6_linear_workspace_bytes", "fp6_workspace_init", "fp6_layout_version"):
+              "fp6_linear_workspace_bytes", "fp6_workspace_init", "fp6_layout_version",
+              "fp5_quantize_pack", "fp5_unpack", "fp5_linear", "fp5_packed_bytes", "fp5_linear_workspace_bytes"):
         assert callable(getattr(pkg, n))
 
 
@@ -46,6 +49,8 @@ def test_size_queries(lib):
     assert lib.fp6_packed_bytes(8192, 22016) == 135266304          # 3*M*K/4
     assert lib.fp6_packed_bytes(256, 512) == 98304
     assert lib.fp6_packed_bytes(16, 256) == 3072
+    assert lib.fp5_packed_bytes(16, 256) == 2560 and lib.fp5_packed_bytes(8192, 22016) == 112721920
+    assert lib.fp5_packed_bytes(15, 256) == 0
     assert lib.fp6_packed_bytes(15, 256) == 0 and lib.fp6_packed_bytes(16, 128) == 0
     assert lib.fp6_packed_bytes(0, 256) == 0 and lib.fp6_packed_bytes(-16, 256) == 0
     for (M, N, K) in [(8192, 1, 22016), (8192, 32, 22016), (256, 8, 512), (22016, 16, 8192)]:

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     constexpr int LOOK = 4;
     constexpr int STEPS = 8 * NT;
 #ifndef FP6_TILED_VALU
-#define FP6_TILED_VALU ((RT * 27 + 2 * NT - 1) / (2 * NT) + 1)
+#define FP6_TILED_VALU 2  // VALU instructions the scheduler may place after the MFMAs of a step
 #endif
 #ifndef FP6_TILED_PARTS
 #define FP6_TILED_PARTS 4

@@ -71,8 +71,11 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KT = K / kTileK;
     const int n_row_tiles = M / kTileRows;
-    const int split = blockIdx.x % S;  // neighbouring blocks (one per XCD) take different k slices
-    const int row_block = blockIdx.x / S;
+    // consecutive blocks take consecutive row blocks of the same k slice (measured a few per cent better at
+    // N = 32, 64 than alternating the slices, no difference below)
+    const int n_row_blocks = gridDim.x / S;
+    const int row_block = blockIdx.x % n_row_blocks;
+    const int split = blockIdx.x / n_row_blocks;
     const int row_tile = row_block * WAVES + wave;
     const bool active = row_tile < n_row_tiles;
     const int kt0 = (int)(((unsigned)KT * (unsigned)split) / (unsigned)S);  // KT * S < 2^31 (host-checked)

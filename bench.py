@@ -45,8 +45,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the prefill / fp16 / offline side measurements")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the layer is a single-GPU kernel; see DESIGN.md "
-              "for how it would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the layer is a single-GPU kernel and nothing here "
+              "uses a second GPU); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

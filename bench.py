@@ -339,47 +339,53 @@ def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_
         sc_t.append(sc)
         del Wt
     out["down_projection_22016x8192"] = _compare_sweep(pkg, torch, workloads, Mt, Kt, pk_t, sc_t, W16t, Ns)
-    out["w5a16_e2m2"] = fp5_sweep(pkg, torch, workloads, M, K, W16, Ns)
+    out["w5a16_e2m2"] = narrow_sweep(pkg, "fp5", torch, workloads, M, K, W16, Ns)
+    out["w4a16_e2m1"] = narrow_sweep(pkg, "fp4", torch, workloads, M, K, W16, Ns)
     del W16, W16t, pk_t, sc_t
     torch.cuda.empty_cache()
     out["decoder_set_70b"] = decoder_set_measurements(pkg, torch, np, workloads, dev)
     return out
 
 
-def fp5_sweep(pkg, torch, workloads, M, K, W16, Ns):
-    """The 5-bit variant (e2m2 weights, 5MK/8 bytes) on the same layer: fp5_linear at every N, rotating over 8
-    packed copies, plus fp5_quantize_pack and fp5_unpack once."""
+def narrow_sweep(pkg, prefix, torch, workloads, M, K, W16, Ns):
+    """A narrower weight format (prefix "fp5": e2m2, 5MK/8 bytes; "fp4": e2m1, MK/2 bytes) on the same layer:
+    its linear call at every N, rotating over 8 packed copies, plus its quantize_pack and unpack once."""
     dev = W16[0].device
-    P5 = pkg.fp5_packed_bytes(M, K)
+    packed_bytes = getattr(pkg, prefix + "_packed_bytes")
+    quantize_pack = getattr(pkg, prefix + "_quantize_pack")
+    unpack = getattr(pkg, prefix + "_unpack")
+    linear = getattr(pkg, prefix + "_linear")
+    workspace_bytes = getattr(pkg, prefix + "_linear_workspace_bytes")
+    P = packed_bytes(M, K)
     packed, scales, pack_ms = [], [], []
     for b in range(N_BUFFERS):
         W = W16[b] if b < len(W16) else workloads.make_weights(M, K, seed=300 + b, device=dev)
-        pk = torch.empty(P5, dtype=torch.uint8, device=dev)
+        pk = torch.empty(P, dtype=torch.uint8, device=dev)
         sc = torch.empty(M, dtype=torch.float16, device=dev)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        pkg.fp5_quantize_pack(W, pk, sc)
+        quantize_pack(W, pk, sc)
         e1.record()
         torch.cuda.synchronize()
         pack_ms.append(e0.elapsed_time(e1))
         packed.append(pk)
         scales.append(sc)
         del W
-    out = {"packed_bytes": P5, "quantize_pack_ms": round(sorted(pack_ms)[len(pack_ms) // 2], 3)}
+    out = {"packed_bytes": P, "quantize_pack_ms": round(sorted(pack_ms)[len(pack_ms) // 2], 3)}
     Wd = torch.empty((M, K), dtype=torch.float16, device=dev)
-    us = _time_graph(torch, lambda i: pkg.fp5_unpack(packed[i % len(packed)], scales[i % len(packed)], M, K, out=Wd), 4, reps=5)
+    us = _time_graph(torch, lambda i: unpack(packed[i % len(packed)], scales[i % len(packed)], M, K, out=Wd), 4, reps=5)
     out["unpack_ms"] = round(us * 1e-3, 3)
     del Wd
     per_n = {}
     for n in Ns:
         X = workloads.make_activations(n, K, seed=n, device=dev)
         Y = torch.empty((n, M), dtype=torch.float16, device=dev)
-        ws = torch.zeros(max(pkg.fp5_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
-        us = _time_graph(torch, lambda i: pkg.fp5_linear(packed[i % len(packed)], scales[i % len(packed)], X, M, K, out=Y, workspace=ws),
+        ws = torch.zeros(max(workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
+        us = _time_graph(torch, lambda i: linear(packed[i % len(packed)], scales[i % len(packed)], X, M, K, out=Y, workspace=ws),
                          len(packed), 10 if n <= 32 else 3)
-        alg = P5 + 2 * M + 2 * K * n + 2 * M * n
+        alg = P + 2 * M + 2 * K * n + 2 * M * n
         tfl = 2.0 * M * n * K / us * 1e-6
-        per_n[str(n)] = {"us": round(us, 2), "weight_GBps": round(P5 / us * 1e-3, 1), "tflops": round(tfl, 2),
+        per_n[str(n)] = {"us": round(us, 2), "weight_GBps": round(P / us * 1e-3, 1), "tflops": round(tfl, 2),
                          "hbm_frac": round(alg / us * 1e-3 / HBM_PEAK_GBPS, 4), "mfma_frac": round(tfl / MFMA_F16_PEAK_TFLOPS, 4)}
     out["linear"] = per_n
     return out

@@ -146,8 +146,25 @@ fp6_status fp5_linear(const void *packed, const void *scales_f16, const void *X_
                       int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Tuning hook for benchmarks: force the split-K factor used by fp6_linear, fp5_linear
- * and fp16_linear (0 = choose automatically, the default).  Process-wide; affects the
+ * And for 4-bit weights (W4A16): FP4 is e2m1, code = s e1 e0 m0, Eq. 1 with bias 1,
+ * subnormal E = 0 binade, no inf/NaN: magnitudes 0 .5 1 1.5 2 3 4 6 (the FP4 element
+ * type of the OCP microscaling formats, which the gfx950 converts to fp16 itself).
+ * Quantizer: scale[m] = fp16_rne(max_k |W[m][k]| / 6), nearest magnitude, ties to the
+ * even code, saturating at 6.  fp4_packed_bytes(M, K) = M*K/2 (tiles of 2048 bytes).
+ * Everything else as for the fp6_ calls.
+ */
+size_t fp4_packed_bytes(int64_t M, int64_t K);
+size_t fp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
+fp6_status fp4_quantize_pack(const void *W_f16, int64_t M, int64_t K, void *packed, void *scales_f16,
+                             void *stream);
+fp6_status fp4_unpack(const void *packed, const void *scales_f16, int64_t M, int64_t K, void *W_f16_out,
+                      void *stream);
+fp6_status fp4_linear(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                      int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Tuning hook for benchmarks: force the split-K factor used by fp6_linear, fp5_linear,
+ * fp4_linear and fp16_linear (0 = choose automatically, the default).  Process-wide; affects the
  * workspace size queries as well.  Values the shape cannot honour are clamped.
  */
 void fp6_tuning_set_split_k(int split_k);

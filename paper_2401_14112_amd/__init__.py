@@ -5,6 +5,11 @@ is the thin Python binding over it.  PyTorch is used for device memory and strea
 only - every step of the path runs in the library's HIP kernels.
 """
 from .binding import (  # noqa: F401
+    fp4_linear,
+    fp4_linear_workspace_bytes,
+    fp4_packed_bytes,
+    fp4_quantize_pack,
+    fp4_unpack,
     fp5_linear,
     fp5_linear_workspace_bytes,
     fp5_packed_bytes,

@@ -65,6 +65,16 @@ def load_library():
     L.fp5_unpack.argtypes = [vp, vp, i64, i64, vp, vp]
     L.fp5_linear.restype = ci
     L.fp5_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
+    L.fp4_packed_bytes.restype = sz
+    L.fp4_packed_bytes.argtypes = [i64, i64]
+    L.fp4_linear_workspace_bytes.restype = sz
+    L.fp4_linear_workspace_bytes.argtypes = [i64, i64, i64]
+    L.fp4_quantize_pack.restype = ci
+    L.fp4_quantize_pack.argtypes = [vp, i64, i64, vp, vp, vp]
+    L.fp4_unpack.restype = ci
+    L.fp4_unpack.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.fp4_linear.restype = ci
+    L.fp4_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
     L.fp6_tuning_set_split_k.restype = None
     L.fp6_tuning_set_split_k.argtypes = [ci]
     L.fp6_tuning_set_tile.restype = None
@@ -232,6 +242,30 @@ def fp5_unpack(packed: torch.Tensor, scales: torch.Tensor, M: int, K: int,
 def fp5_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
                out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     return _linear("fp5", packed, scales, X, M, K, out, workspace)
+
+
+def fp4_packed_bytes(M: int, K: int) -> int:
+    return int(load_library().fp4_packed_bytes(M, K))
+
+
+def fp4_linear_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load_library().fp4_linear_workspace_bytes(M, N, K))
+
+
+def fp4_quantize_pack(W: torch.Tensor, packed: Optional[torch.Tensor] = None,
+                      scales: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """fp16 [M][K] -> (packed uint8 [MK/2], scales fp16 [M]), e2m1 codes."""
+    return _quantize_pack("fp4", W, packed, scales)
+
+
+def fp4_unpack(packed: torch.Tensor, scales: torch.Tensor, M: int, K: int,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    return _unpack("fp4", packed, scales, M, K, out)
+
+
+def fp4_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
+               out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    return _linear("fp4", packed, scales, X, M, K, out, workspace)
 
 
 def fp16_linear(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] = None,

@@ -290,6 +290,56 @@ struct PackedFp5Source {
     }
 };
 
+// ---- 4-bit (e2m1) weights ------------------------------------------------------------------------
+// e2m1 (bias 1, subnormal E = 0 binade: 0 .5 1 1.5 2 3 4 6) is the FP4 element type of the OCP microscaling
+// formats; the chip converts two codes of a byte to two fp16 values with v_cvt_scalef32_pk_f16_fp4.
+// Tile: 16 rows x 256 columns = 2048 bytes = two planes of 16 bytes per lane; lane L = 16q + r owns eight
+// words, word d = run d (columns 32d + 8q + j), code j in bits [4j, 4j+4): one word is one A fragment.
+__device__ __forceinline__ half8_t e2m1_word_to_fragment(uint32_t w)
+{
+    const half2_t a = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 0);
+    const half2_t b = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 1);
+    const half2_t c = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 2);
+    const half2_t d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 3);
+    return (half8_t){a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
+
+struct PackedFp4Source {
+    struct Tile {
+        u32x4 p0, p1;
+    };
+    static constexpr bool kHasScale = true;
+    static constexpr bool kTallTile = true;
+    static constexpr int kLoads = 2;
+    static constexpr int kTileBytes4 = 2048;
+    static constexpr int kTileStride = kTileBytes4;
+    __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
+    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
+                                                        int64_t KT, int64_t /*K*/)
+    {
+        return make_rsrc(static_cast<const uint8_t *>(base) + (row_tile * KT + kt0) * kTileBytes4,
+                         (uint32_t)(kt1 - kt0) * kTileBytes4);
+    }
+    __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
+    __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
+    {
+        t.p0 = issue_load_b128<0, true>(r, off);
+        t.p1 = issue_load_b128<1024, true>(r, off);
+    }
+    __device__ static __forceinline__ void pin_tile(Tile &t)
+    {
+        pin(t.p0);
+        pin(t.p1);
+    }
+    template <int G>
+    __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
+    {
+        const u32x4 &p = G < 2 ? t.p0 : t.p1;
+        even_run = e2m1_word_to_fragment(p[2 * (G & 1)]);
+        odd_run = e2m1_word_to_fragment(p[2 * (G & 1) + 1]);
+    }
+};
+
 struct PlainFp16Source {
     struct Tile {
         u32x4 v[8];

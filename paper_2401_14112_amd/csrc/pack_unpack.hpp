@@ -143,6 +143,40 @@ struct E2M2Format {
     }
 };
 
+// e2m1: grid 0 .5 | 1 1.5 | 2 3 | 4 6 (Eq. 1 with bias 1, subnormal E = 0 binade).
+struct E2M1Format {
+    static constexpr float kMax = 6.0f;
+    static constexpr int kSignShift = 3;
+    static constexpr int kTileBytes = 2048;
+    __device__ static __forceinline__ uint32_t magnitude_code(float ratio)
+    {
+        uint32_t g;
+        if (ratio < 1.0f) {
+            g = (uint32_t)__builtin_rintf(ratio * 2.0f);  // subnormal binade: multiples of 1/2
+        } else {
+            uint32_t u = bit_cast<uint32_t>(ratio);
+            u += 0x001fffffu + ((u >> 22) & 1u);  // round the mantissa to 1 bit, half to even
+            g = (u >> 22) - (126u << 1);          // exponent field - 127 + bias 1, then 1 mantissa bit
+        }
+        return g < 7u ? g : 7u;
+    }
+    __device__ static __forceinline__ void store_tile(const uint32_t (&code)[8][8], uint8_t *tile, int lane)
+    {
+        uint32_t d[8];
+#pragma unroll
+        for (int run = 0; run < 8; ++run) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                w |= code[run][j] << (4 * j);
+            d[run] = w;
+        }
+        u32x4 *t = reinterpret_cast<u32x4 *>(tile) + lane;
+        t[0] = (u32x4){d[0], d[1], d[2], d[3]};
+        t[64] = (u32x4){d[4], d[5], d[6], d[7]};
+    }
+};
+
 constexpr int kPackWaves = 16;  // waves per block of quantize_pack_kernel
 
 template <class Fmt>

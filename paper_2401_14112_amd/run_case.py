@@ -1,4 +1,4 @@
-"""Runs one shape of fp6_linear (or fp5_linear, fp16_linear) a few times on cuda:0 and prints the time per launch.
+"""Runs one shape of fp6_linear (or fp5_linear, fp4_linear, fp16_linear) a few times on cuda:0 and prints the time per launch.
 
 Meant to be the program of a profiler run, e.g.
 
@@ -23,7 +23,7 @@ def main():
     ap.add_argument("--N", type=int, default=512)
     ap.add_argument("--reps", type=int, default=16)
     ap.add_argument("--buffers", type=int, default=8)
-    ap.add_argument("--which", choices=("fp6", "fp5", "fp16"), default="fp6")
+    ap.add_argument("--which", choices=("fp6", "fp5", "fp4", "fp16"), default="fp6")
     args = ap.parse_args()
 
     import torch
@@ -37,8 +37,7 @@ def main():
     weights = []
     for b in range(args.buffers):
         W = workloads.make_weights(M, K, seed=b, device=dev)
-        weights.append(pkg.fp6_quantize_pack(W) if args.which == "fp6" else
-                       pkg.fp5_quantize_pack(W) if args.which == "fp5" else (W,))
+        weights.append((W,) if args.which == "fp16" else getattr(pkg, args.which + "_quantize_pack")(W))
     X = workloads.make_activations(N, K, seed=N, device=dev)
     Y = torch.empty((N, M), dtype=torch.float16, device=dev)
     query = pkg.fp16_linear_workspace_bytes if args.which == "fp16" else pkg.fp6_linear_workspace_bytes
@@ -46,10 +45,8 @@ def main():
 
     def launch(i):
         w = weights[i % len(weights)]
-        if args.which == "fp6":
-            pkg.fp6_linear(w[0], w[1], X, M, K, out=Y, workspace=ws)
-        elif args.which == "fp5":
-            pkg.fp5_linear(w[0], w[1], X, M, K, out=Y, workspace=ws)
+        if args.which != "fp16":
+            getattr(pkg, args.which + "_linear")(w[0], w[1], X, M, K, out=Y, workspace=ws)
         else:
             pkg.fp16_linear(w[0], X, out=Y, workspace=ws)
 

@@ -20,7 +20,7 @@ def lib():
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "fp6.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(fp6_\w+|fp5_\w+|fp16_\w+)\s*\(", text)
+    names = re.findall(r"\b(fp6_\w+|fp5_\w+|fp4_\w+|fp16_\w+)\s*\(", text)
     return sorted(set(names))
 
 
@@ -29,7 +29,8 @@ def test_exports_every_declared_symbol(lib):
     for expected in ("fp6_quantize_pack", "fp6_unpack", "fp6_linear", "fp16_linear", "fp6_packed_bytes",
                      "fp6_linear_workspace_bytes", "fp6_workspace_init", "fp6_status_str", "fp6_layout_version",
                      "fp16_linear_workspace_bytes", "fp6_tuning_set_split_k", "fp6_tuning_set_tile",
-                     "fp5_quantize_pack", "fp5_unpack", "fp5_linear", "fp5_packed_bytes", "fp5_linear_workspace_bytes"):
+                     "fp5_quantize_pack", "fp5_unpack", "fp5_linear", "fp5_packed_bytes", "fp5_linear_workspace_bytes",
+                     "fp4_quantize_pack", "fp4_unpack", "fp4_linear", "fp4_packed_bytes", "fp4_linear_workspace_bytes"):
         assert expected in names
     for n in names:
         assert hasattr(lib, n), "library does not export %s" % n
@@ -51,6 +52,7 @@ def test_size_queries(lib):
     assert lib.fp6_packed_bytes(16, 256) == 3072
     assert lib.fp5_packed_bytes(16, 256) == 2560 and lib.fp5_packed_bytes(8192, 22016) == 112721920
     assert lib.fp5_packed_bytes(15, 256) == 0
+    assert lib.fp4_packed_bytes(16, 256) == 2048 and lib.fp4_packed_bytes(16, 128) == 0
     assert lib.fp6_packed_bytes(15, 256) == 0 and lib.fp6_packed_bytes(16, 128) == 0
     assert lib.fp6_packed_bytes(0, 256) == 0 and lib.fp6_packed_bytes(-16, 256) == 0
     for (M, N, K) in [(8192, 1, 22016), (8192, 32, 22016), (256, 8, 512), (22016, 16, 8192)]:

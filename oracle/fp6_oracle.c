@@ -339,6 +339,102 @@ void fp6o_linear_f16(const uint16_t *W, const uint16_t *X, int64_t M, int64_t N,
 }
 
 /* ====================================================================== *
+ * Group-wise scales (fine-grained quantization; Section 3 of the paper
+ * contrasts it with the coarse-grained, one-scale-per-channel scheme that FP6
+ * is used with, and Algorithm 1 multiplies the scales into the weights before
+ * the matrix multiplication, which is what a scale per group of columns needs).
+ * One fp16 scale per row and per group of `group` consecutive columns:
+ * scales is [M][K/group]; inside its group every weight is quantized exactly as
+ * in the per-row scheme (fp6o_scale_for_amax, fp6o_quantize_one).  The packed
+ * stream is the 6-bit one (fp6o_pos).
+ * ====================================================================== */
+
+int fp6go_quantize(const uint16_t *W, int64_t M, int64_t K, int64_t group, uint8_t *codes, uint16_t *scales)
+{
+    int bad = 0;
+    int64_t G = K / group;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t g = 0; g < G; ++g) {
+            uint16_t amax = 0;
+            for (int64_t k = g * group; k < (g + 1) * group; ++k) {
+                uint16_t mag = (uint16_t)(W[m * K + k] & 0x7fffu);
+                if (mag >= 0x7c00u)
+                    bad |= 1;
+                if (mag > amax)
+                    amax = mag;
+            }
+            uint16_t sc = fp6o_scale_for_amax(amax);
+            scales[m * G + g] = sc;
+            for (int64_t k = g * group; k < (g + 1) * group; ++k)
+                codes[m * K + k] = (uint8_t)fp6o_quantize_one(W[m * K + k], sc);
+        }
+    return bad;
+}
+
+int fp6go_quantize_pack(const uint16_t *W, int64_t M, int64_t K, int64_t group, uint8_t *packed, uint16_t *scales)
+{
+    uint8_t *codes = (uint8_t *)malloc((size_t)(M * K));
+    if (!codes)
+        return 2;
+    int bad = fp6go_quantize(W, M, K, group, codes, scales);
+    fp6o_pack(codes, M, K, packed);
+    free(codes);
+    return bad;
+}
+
+/* nearest fp16 to decode(code) * scale[m][k/group] (exact product, one rounding) */
+int fp6go_unpack(const uint8_t *packed, const uint16_t *scales, int64_t M, int64_t K, int64_t group, uint16_t *W)
+{
+    uint8_t *codes = (uint8_t *)malloc((size_t)(M * K));
+    if (!codes)
+        return 2;
+    int64_t G = K / group;
+    fp6o_unpack_codes(packed, M, K, codes);
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k)
+            W[m * K + k] = fp6o_double_to_half(fp6o_decode(codes[m * K + k]) * fp6o_half_to_double(scales[m * G + k / group]));
+    free(codes);
+    return 0;
+}
+
+/* Y[n][i] = sum_k scale[row][k/group] * decode(code[row][k]) * X[n][k], k ascending, in double. */
+int fp6go_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X, int64_t M, int64_t N,
+                 int64_t K, int64_t group, const int64_t *rows, int64_t nrows, double *Y)
+{
+    if (!rows)
+        nrows = M;
+    int64_t G = K / group;
+    double *Xd = (double *)malloc((size_t)(N * K) * sizeof(double));
+    if (!Xd)
+        return 2;
+    for (int64_t i = 0; i < N * K; ++i)
+        Xd[i] = fp6o_half_to_double(X[i]);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t m = rows ? rows[i] : i;
+        double *wd = (double *)malloc((size_t)K * sizeof(double));
+        for (int64_t k = 0; k < K; ++k) {
+            int c = 0;
+            for (int b = 0; b < 6; ++b) {
+                uint64_t p = fp6o_pos(K, m, k, b);
+                c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
+            }
+            wd[k] = fp6o_decode(c) * fp6o_half_to_double(scales[m * G + k / group]); /* exact */
+        }
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += wd[k] * Xd[n * K + k];
+            Y[n * nrows + i] = acc;
+        }
+        free(wd);
+    }
+    free(Xd);
+    return 0;
+}
+
+/* ====================================================================== *
  * The 5-bit variant (W5A16).  The paper presents its scheme as independent of
  * the bit-width (Section 1: "6-bit, 5-bit, 3-bit, etc."; Section 5.2: the
  * pre-packing applies to any x; Section 5.3: the cast of Eq. 3 applies to any

@@ -236,7 +236,7 @@ template <class Src, int C>
 fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const void *scales, const void *X, void *Y,
                              int64_t M, int64_t N, int64_t K, float4_t *partials, int *counters, hipStream_t stream)
 {
-    constexpr StreamCfg c = Src::kHasScale ? kStreamCfg[C] : kStreamCfgFp16[C];
+    constexpr StreamCfg c = Src::kPackedConfigs ? kStreamCfg[C] : kStreamCfgFp16[C];
     auto kernel = linear_stream_kernel<Src, c.nt, c.waves, c.depth, c.stage, c.spread>;
     constexpr size_t lds = (size_t)2 * c.stage * c.nt * 512 * 16;  // two stages of activations
     static_assert(lds <= 160 * 1024, "activation stages exceed the LDS of a CU");
@@ -266,7 +266,7 @@ template <class Src>
 fp6_status launch_stream(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
                          int64_t K, void *workspace, size_t workspace_bytes, hipStream_t stream)
 {
-    const StreamPlan p = plan_stream(M, N, K, Src::kHasScale);
+    const StreamPlan p = plan_stream(M, N, K, Src::kPackedConfigs);
     if (p.total_bytes() > 0) {
         if (!workspace || workspace_bytes < p.total_bytes())
             return FP6_ERR_WORKSPACE;

@@ -164,7 +164,28 @@ __device__ __forceinline__ void x_source_of_piece(int p, int &n, int &q)
 // k-tiles [kt0, kt1); issue() requests the tile at lane offset `off`
 // (= lane_offset + t * kTileStride for tile t of the slice) with kLoads loads.
 
+// What one wave keeps to fetch the tiles of its slice: init() once, then issue(tile, t) requests tile t of
+// the slice (t past the slice reads zeros).  SimpleStream serves every source whose tile comes from one
+// buffer; a source with a second input (per-group scales) defines its own.
+template <class Src>
+struct SimpleStream {
+    rsrc_t rsrc;
+    int off;
+    __device__ __forceinline__ void init(const void *weights, const half_t * /*scales*/, int64_t row_tile, int kt0,
+                                         int kt1, int64_t KT, int64_t K, int lane)
+    {
+        rsrc = Src::slice_rsrc(weights, row_tile, kt0, kt1, KT, K);
+        off = Src::lane_offset(lane, kt0, (int)K);
+    }
+    __device__ __forceinline__ void issue(typename Src::Tile &tile, int t) const
+    {
+        Src::issue(tile, rsrc, off + t * Src::kTileStride);
+    }
+};
+
 struct PackedFp6Source {
+    typedef SimpleStream<PackedFp6Source> Stream;
+    static constexpr bool kPackedConfigs = true;  // which table of kernel configurations the host uses
     struct Tile {
         u32x4 p0, p1, p2;
     };
@@ -233,6 +254,8 @@ __device__ __forceinline__ half8_t e2m2_bytes_to_fragment(uint32_t b_lo, uint32_
 }
 
 struct PackedFp5Source {
+    typedef SimpleStream<PackedFp5Source> Stream;
+    static constexpr bool kPackedConfigs = true;  // which table of kernel configurations the host uses
     struct Tile {
         u32x4 p0, p1;
         u32x2 p2;
@@ -305,6 +328,8 @@ __device__ __forceinline__ half8_t e2m1_word_to_fragment(uint32_t w)
 }
 
 struct PackedFp4Source {
+    typedef SimpleStream<PackedFp4Source> Stream;
+    static constexpr bool kPackedConfigs = true;  // which table of kernel configurations the host uses
     struct Tile {
         u32x4 p0, p1;
     };
@@ -341,6 +366,8 @@ struct PackedFp4Source {
 };
 
 struct PlainFp16Source {
+    typedef SimpleStream<PlainFp16Source> Stream;
+    static constexpr bool kPackedConfigs = false;  // which table of kernel configurations the host uses
     struct Tile {
         u32x4 v[8];
     };

@@ -86,7 +86,8 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
 
     // Inactive waves (ragged last row block) stream the last valid row tile and drop the result,
     // so the main loop has no per-wave control flow.
-    const rsrc_t w_rsrc = Src::slice_rsrc(weights, active ? row_tile : n_row_tiles - 1, kt0, kt1, KT, K);
+    typename Src::Stream w_stream;
+    w_stream.init(weights, scales, active ? row_tile : n_row_tiles - 1, kt0, kt1, KT, K, lane);
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
     // ---- activation staging.  Copy j = wave + WAVES*i of a stage serves k-tile g = j / (8*NT) of the
@@ -157,11 +158,10 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     // activation copies requested in the DEPTH-1 iterations in between.  Tiles past the end of the slice read
     // as zeros through the buffer bounds check (no memory traffic), so the request pattern never varies.
     typename Src::Tile w[DEPTH];
-    const int w_off = Src::lane_offset(lane, kt0, K);
     x_issue(0, 0, XPER);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
-        Src::issue(w[d], w_rsrc, w_off + d * Src::kTileStride);
+        w_stream.issue(w[d], d);
     const int n_tiles = n_stages * G;
     for (int t0 = 0; t0 < n_tiles; t0 += U) {
         static_for<U>([&](auto uc) {
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
                 x_issue(stage + 1, g * XPART, (g + 1) * XPART);
             if (t < T)
                 compute(w[slot], xs_dyn + (stage & 1) * STAGE_PIECES + g * (NT * 8 * 64));
-            Src::issue(w[slot], w_rsrc, w_off + (t + DEPTH) * Src::kTileStride);
+            w_stream.issue(w[slot], t + DEPTH);
         });
     }
     // drain: the look-ahead requests (weights out of range, activation copies into the unused buffer)

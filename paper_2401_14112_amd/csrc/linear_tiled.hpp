@@ -68,11 +68,11 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     const int kt1 = (int)(((unsigned)KT * (unsigned)(split + 1)) / (unsigned)S);
     const int n_valid = kt1 - kt0;
 
-    rsrc_t w_rsrc[RT];
+    typename Src::Stream w_stream[RT];
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
         const int rt = row_tile0 + r;
-        w_rsrc[r] = Src::slice_rsrc(weights, rt < n_row_tiles ? rt : n_row_tiles - 1, kt0, kt1, KT, K);
+        w_stream[r].init(weights, scales, rt < n_row_tiles ? rt : n_row_tiles - 1, kt0, kt1, KT, K, lane);
     }
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
@@ -169,12 +169,11 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     };
 
     typename Src::Tile w[2][RT];
-    const int w_off = Src::lane_offset(lane, kt0, K);
     auto w_issue = [&](typename Src::Tile (&dst)[RT], int t, int r0, int r1) {
 #pragma unroll
         for (int r = 0; r < RT; ++r)
             if (r >= r0 && r < r1)
-                Src::issue(dst[r], w_rsrc[r], w_off + t * Src::kTileStride);
+                w_stream[r].issue(dst[r], t);
     };
     auto arrive = [&](typename Src::Tile (&dst)[RT]) {
         wait_loads<0>();

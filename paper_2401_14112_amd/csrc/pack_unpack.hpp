@@ -246,9 +246,10 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
         return;
     const int64_t row_tile = tile / KT, kt = tile % KT;
     const int r = lane & 15, q = lane >> 4;
-    const rsrc_t rs = Src::slice_rsrc(packed, row_tile, (int)kt, (int)kt + 1, KT, K);
+    typename Src::Stream stream;
+    stream.init(packed, scales, row_tile, (int)kt, (int)kt + 1, KT, K, lane);
     typename Src::Tile t;
-    Src::issue(t, rs, Src::lane_offset(lane, 0, K));
+    stream.issue(t, 0);
     wait_loads<0>();
     Src::pin_tile(t);
     const float scale = (float)scales[row_tile * kTileRows + r];

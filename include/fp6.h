@@ -124,6 +124,27 @@ fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * 6-bit weights with group-wise scales (fine-grained quantization): one fp16 scale per
+ * row and per group of `group` consecutive columns instead of one per row - the scheme
+ * that Section 3 of the paper contrasts with the coarse-grained one, with the scales
+ * multiplied into the de-quantized weights before the matrix multiplication as in
+ * Algorithm 1.  scales is fp16 [M][K/group], row-major; inside a group the quantizer is
+ * that of fp6_quantize_pack (scale = fp16_rne(group max |W| / 28), ...).  The packed
+ * stream is the one of fp6_quantize_pack (fp6_packed_bytes).  Only group = 128 is
+ * supported (FP6_ERR_SHAPE otherwise).
+ *     fp6g_unpack:  W_out[m][k] = fp16_rne(e3m2_value(code) * scale[m][k/group])
+ *     fp6g_linear:  Y[n][m] = fp16_rne(sum_k fp16_rne(e3m2_value(code[m][k]) * scale[m][k/group]) * X[n][k]),
+ *                   accumulated in fp32 (each weight is rounded to fp16 once before it is used)
+ * Workspace: fp6_linear_workspace_bytes(M, N, K).  Everything else as for the fp6_ calls.
+ */
+fp6_status fp6g_quantize_pack(const void *W_f16, int64_t M, int64_t K, int64_t group, void *packed,
+                              void *scales_f16, void *stream);
+fp6_status fp6g_unpack(const void *packed, const void *scales_f16, int64_t M, int64_t K, int64_t group,
+                       void *W_f16_out, void *stream);
+fp6_status fp6g_linear(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                       int64_t N, int64_t K, int64_t group, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The same three calls for 5-bit weights (W5A16).  The paper presents its pre-packing
  * and its cast to fp16 as independent of the bit-width (Section 1: "6-bit, 5-bit,
  * 3-bit, etc."; Sections 5.2 and 5.3).  FP5 is e2m2: code = s e1 e0 m1 m0, Eq. 1 with

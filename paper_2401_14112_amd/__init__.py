@@ -15,6 +15,9 @@ from .binding import (  # noqa: F401
     fp5_packed_bytes,
     fp5_quantize_pack,
     fp5_unpack,
+    fp6g_linear,
+    fp6g_quantize_pack,
+    fp6g_unpack,
     fp6_layout_version,
     fp6_linear,
     fp6_linear_workspace_bytes,

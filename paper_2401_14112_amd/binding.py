@@ -75,6 +75,12 @@ def load_library():
     L.fp4_unpack.argtypes = [vp, vp, i64, i64, vp, vp]
     L.fp4_linear.restype = ci
     L.fp4_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
+    L.fp6g_quantize_pack.restype = ci
+    L.fp6g_quantize_pack.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    L.fp6g_unpack.restype = ci
+    L.fp6g_unpack.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    L.fp6g_linear.restype = ci
+    L.fp6g_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, sz, vp]
     L.fp6_tuning_set_split_k.restype = None
     L.fp6_tuning_set_split_k.argtypes = [ci]
     L.fp6_tuning_set_tile.restype = None
@@ -242,6 +248,75 @@ def fp5_unpack(packed: torch.Tensor, scales: torch.Tensor, M: int, K: int,
 def fp5_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
                out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     return _linear("fp5", packed, scales, X, M, K, out, workspace)
+
+
+def fp6g_quantize_pack(W: torch.Tensor, group: int = 128, packed: Optional[torch.Tensor] = None,
+                       scales: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """fp16 [M][K] -> (packed uint8 [3MK/4], scales fp16 [M][K/group]): one scale per row and column group."""
+    L = load_library()
+    _dev(W, torch.float16, "W")
+    if W.dim() != 2:
+        raise Fp6Error("W must be [M][K]")
+    M, K = W.shape
+    nbytes = L.fp6_packed_bytes(M, K)
+    if nbytes == 0 or group <= 0 or K % group:
+        _check(2)
+    if packed is None:
+        packed = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
+    if scales is None:
+        scales = torch.empty((M, K // group), dtype=torch.float16, device=W.device)
+    _dev(packed, torch.uint8, "packed")
+    _dev(scales, torch.float16, "scales")
+    if packed.numel() != nbytes or scales.numel() != M * (K // group):
+        raise Fp6Error("packed/scales have the wrong size")
+    _check(L.fp6g_quantize_pack(W.data_ptr(), M, K, group, packed.data_ptr(), scales.data_ptr(), _stream()))
+    return packed, scales
+
+
+def fp6g_unpack(packed: torch.Tensor, scales: torch.Tensor, M: int, K: int, group: int = 128,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    L = load_library()
+    _dev(packed, torch.uint8, "packed")
+    _dev(scales, torch.float16, "scales")
+    nbytes = L.fp6_packed_bytes(M, K)
+    if nbytes == 0 or group <= 0 or K % group:
+        _check(2)
+    if packed.numel() != nbytes or scales.numel() != M * (K // group):
+        raise Fp6Error("packed/scales do not match M, K, group")
+    if out is None:
+        out = torch.empty((M, K), dtype=torch.float16, device=packed.device)
+    _dev(out, torch.float16, "out")
+    if out.numel() != M * K:
+        raise Fp6Error("out has the wrong size")
+    _check(L.fp6g_unpack(packed.data_ptr(), scales.data_ptr(), M, K, group, out.data_ptr(), _stream()))
+    return out
+
+
+def fp6g_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int, group: int = 128,
+                out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    L = load_library()
+    _dev(packed, torch.uint8, "packed")
+    _dev(scales, torch.float16, "scales")
+    _dev(X, torch.float16, "X")
+    if X.dim() != 2 or X.shape[1] != K:
+        raise Fp6Error("X must be [N][K]")
+    N = X.shape[0]
+    nbytes = L.fp6_packed_bytes(M, K)
+    if nbytes == 0 or N == 0 or group <= 0 or K % group:
+        _check(2)
+    if packed.numel() != nbytes or scales.numel() != M * (K // group):
+        raise Fp6Error("packed/scales do not match M, K, group")
+    if out is None:
+        out = torch.empty((N, M), dtype=torch.float16, device=X.device)
+    _dev(out, torch.float16, "out")
+    if out.numel() != N * M:
+        raise Fp6Error("out has the wrong size")
+    if workspace is None:
+        workspace = _new_workspace(L.fp6_linear_workspace_bytes(M, N, K), X.device)
+    ws_ptr, ws_len = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
+    _check(L.fp6g_linear(packed.data_ptr(), scales.data_ptr(), X.data_ptr(), out.data_ptr(), M, N, K, group,
+                         ws_ptr, ws_len, _stream()))
+    return out
 
 
 def fp4_packed_bytes(M: int, K: int) -> int:

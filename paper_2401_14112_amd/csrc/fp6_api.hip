@@ -408,6 +408,39 @@ fp6_status fp6_linear(const void *packed, const void *scales_f16, const void *X_
                                                stream);
 }
 
+fp6_status fp6g_quantize_pack(const void *W_f16, int64_t M, int64_t K, int64_t group, void *packed, void *scales_f16,
+                              void *stream)
+{
+    if (!W_f16 || !packed || !scales_f16)
+        return FP6_ERR_NULL;
+    if (!shape_ok(M, K) || group != kGroupColumns)
+        return FP6_ERR_SHAPE;
+    if (!aligned16(W_f16) || !aligned16(packed) || !aligned16(scales_f16))
+        return FP6_ERR_ALIGN;
+    const int64_t tiles = (M / kTileRows) * (K / kTileK);
+    hipLaunchKernelGGL(quantize_pack_group_kernel, dim3((unsigned)((tiles + 3) / 4)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const half_t *>(W_f16), (int)M, (int)K,
+                       static_cast<uint8_t *>(packed), static_cast<half_t *>(scales_f16));
+    return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+}
+
+fp6_status fp6g_unpack(const void *packed, const void *scales_f16, int64_t M, int64_t K, int64_t group, void *W_f16_out,
+                       void *stream)
+{
+    if (group != kGroupColumns)
+        return FP6_ERR_SHAPE;
+    return unpack_impl<PackedFp6GroupSource>(packed, scales_f16, M, K, W_f16_out, stream);
+}
+
+fp6_status fp6g_linear(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N,
+                       int64_t K, int64_t group, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (group != kGroupColumns)
+        return FP6_ERR_SHAPE;
+    return packed_linear_impl<PackedFp6GroupSource>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace,
+                                                    workspace_bytes, stream);
+}
+
 size_t fp5_packed_bytes(int64_t M, int64_t K) { return shape_ok(M, K) ? (size_t)(M * K / 8 * 5) : 0; }
 
 size_t fp5_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) { return fp6_linear_workspace_bytes(M, N, K); }

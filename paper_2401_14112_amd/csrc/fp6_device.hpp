@@ -112,6 +112,17 @@ __device__ __forceinline__ void wait_loads()
 __device__ __forceinline__ void pin(u32x4 &v) { asm volatile("" : "+v"(v)); }
 __device__ __forceinline__ void pin(u32x2 &v) { asm volatile("" : "+v"(v)); }
 
+// 32-bit load through the caches (data that several lanes and waves share, e.g. group scales).
+template <int IMM>
+__device__ __forceinline__ uint32_t issue_load_b32(rsrc_t rsrc, int lane_off)
+{
+    uint32_t r;
+    asm volatile("buffer_load_dword %0, %1, %2, 0 offen offset:%3"
+                 : "=v"(r) : "v"(lane_off), "s"(rsrc), "n"(IMM) : "memory");
+    return r;
+}
+__device__ __forceinline__ void pin(uint32_t &v) { asm volatile("" : "+v"(v)); }
+
 // 64-bit variant of issue_load_b128 (streaming policy), for planes that hold 8 bytes per lane.
 template <int IMM>
 __device__ __forceinline__ u32x2 issue_load_b64(rsrc_t rsrc, int lane_off)
@@ -225,6 +236,68 @@ struct PackedFp6Source {
         constexpr int o = (G & 1) * 16;
         even_run = (half8_t){h[o + 0], h[o + 1], h[o + 2], h[o + 3], h[o + 4], h[o + 5], h[o + 6], h[o + 7]};
         odd_run = (half8_t){h[o + 8], h[o + 9], h[o + 10], h[o + 11], h[o + 12], h[o + 13], h[o + 14], h[o + 15]};
+    }
+};
+
+// ---- 6-bit weights with one scale per row and per group of 128 columns --------------------------------
+// Same packed stream as PackedFp6Source.  A group of 128 columns is exactly one of the two 32-code streams
+// a lane holds per tile, so the scale multiplies the 32 converted values of a stream before they go to the
+// matrix cores (the placement of Algorithm 1 of the paper); nothing is left for the epilogue.  The
+// products decode(code) * scale are exact in fp32 and rounded once to fp16 by the packed multiply.
+// scales: fp16 [M][K/128]; lane (r, q) fetches, with each tile, the two scales of its row for that tile.
+constexpr int kGroupColumns = 128;
+
+struct PackedFp6GroupSource {
+    static constexpr bool kPackedConfigs = true;
+    static constexpr bool kHasScale = false;  // no per-row factor in the epilogue
+    static constexpr bool kTallTile = true;
+    static constexpr int kLoads = 4;
+    struct Tile {
+        u32x4 p0, p1, p2;
+        uint32_t sc;  // two fp16: the scales of groups 2*kt and 2*kt + 1 of the lane's row
+    };
+    __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
+    struct Stream {
+        rsrc_t w_rsrc, s_rsrc;
+        int w_off, s_off;
+        __device__ __forceinline__ void init(const void *weights, const half_t *scales, int64_t row_tile, int kt0,
+                                             int kt1, int64_t KT, int64_t K, int lane)
+        {
+            w_rsrc = PackedFp6Source::slice_rsrc(weights, row_tile, kt0, kt1, KT, K);
+            w_off = lane * 16;
+            const int groups = (int)(K / kGroupColumns);  // per row; = 2 * KT
+            // the scales of the 16 rows of the row tile; a tile past the slice reads other finite scales or
+            // zeros, and its weights read as zeros
+            s_rsrc = make_rsrc(scales + row_tile * kTileRows * groups, (uint32_t)(kTileRows * groups * 2));
+            s_off = ((lane & 15) * groups + 2 * kt0) * 2;
+        }
+        __device__ __forceinline__ void issue(Tile &t, int i) const
+        {
+            const int off = w_off + i * kTileBytes;
+            t.p0 = issue_load_b128<0, true>(w_rsrc, off);
+            t.p1 = issue_load_b128<1024, true>(w_rsrc, off);
+            t.p2 = issue_load_b128<2048, true>(w_rsrc, off);
+            t.sc = issue_load_b32<0>(s_rsrc, s_off + i * 4);
+        }
+    };
+    __device__ static __forceinline__ void pin_tile(Tile &t)
+    {
+        pin(t.p0);
+        pin(t.p1);
+        pin(t.p2);
+        pin(t.sc);
+    }
+    template <int G>
+    __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
+    {
+        const u32x6 d = G < 2 ? (u32x6){t.p0[0], t.p0[1], t.p0[2], t.p0[3], t.p1[0], t.p1[1]}
+                              : (u32x6){t.p1[2], t.p1[3], t.p2[0], t.p2[1], t.p2[2], t.p2[3]};
+        const half32_t h = dequant_stream(d);
+        const half2_t both = bit_cast<half2_t>(t.sc);
+        const half_t s = G < 2 ? both[0] : both[1];
+        constexpr int o = (G & 1) * 16;
+        even_run = (half8_t){h[o + 0], h[o + 1], h[o + 2], h[o + 3], h[o + 4], h[o + 5], h[o + 6], h[o + 7]} * s;
+        odd_run = (half8_t){h[o + 8], h[o + 9], h[o + 10], h[o + 11], h[o + 12], h[o + 13], h[o + 14], h[o + 15]} * s;
     }
 };
 

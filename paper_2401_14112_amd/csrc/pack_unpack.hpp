@@ -234,6 +234,59 @@ __global__ __launch_bounds__(kPackWaves * 64) void quantize_pack_kernel(const ha
     }
 }
 
+// Group-wise scales (one per row and per 128 columns): a group lies inside one tile and inside one of a
+// lane's two streams, so row maxima need only a reduction over the four lanes (q = 0..3) that share a row:
+// one pass over W, one wave per tile.  scales: fp16 [M][K/128].
+__global__ __launch_bounds__(256) void quantize_pack_group_kernel(const half_t *__restrict__ W, int M, int K,
+                                                                  uint8_t *__restrict__ packed,
+                                                                  half_t *__restrict__ scales)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int KT = K / kTileK;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+    if (tile >= (int64_t)(M / kTileRows) * KT)
+        return;
+    const int64_t row_tile = tile / KT, kt = tile % KT;
+    const int r = lane & 15, q = lane >> 4;
+    const half_t *row = W + (row_tile * kTileRows + r) * K + kt * kTileK + q * 8;
+    u32x4 v[8];
+#pragma unroll
+    for (int f = 0; f < 8; ++f)
+        v[f] = *reinterpret_cast<const u32x4 *>(row + f * 32);
+    uint32_t code[8][8];
+    uint32_t scale_bits[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        ushort2_t mx = {0, 0};
+#pragma unroll
+        for (int f = 4 * c; f < 4 * c + 4; ++f)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                mx = __builtin_elementwise_max(mx, bit_cast<ushort2_t>(v[f][j] & 0x7fff7fffu));
+        uint32_t amax = mx[0] > mx[1] ? mx[0] : mx[1];  // finite fp16 magnitudes order like integers
+#pragma unroll
+        for (int off = 16; off < 64; off <<= 1) {        // the four lanes of a row
+            const uint32_t other = __shfl_xor(amax, off, 64);
+            amax = other > amax ? other : amax;
+        }
+        const half_t sc = (half_t)((float)bit_cast<half_t>((uint16_t)amax) / E3M2Format::kMax);
+        scale_bits[c] = bit_cast<uint16_t>(sc);
+        const RowScale scale = make_row_scale((float)sc);
+#pragma unroll
+        for (int f = 4 * c; f < 4 * c + 4; ++f)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                code[f][2 * j] = quantize_code<E3M2Format>(v[f][j] & 0xffffu, scale);
+                code[f][2 * j + 1] = quantize_code<E3M2Format>(v[f][j] >> 16, scale);
+            }
+    }
+    E3M2Format::store_tile(code, packed + tile * E3M2Format::kTileBytes, lane);
+    if (q == 0) {
+        const int64_t groups = K / kGroupColumns;
+        *reinterpret_cast<uint32_t *>(scales + (row_tile * kTileRows + r) * groups + 2 * kt) = scale_bits[0] | (scale_bits[1] << 16);
+    }
+}
+
 template <class Src>
 __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__ packed,
                                                      const half_t *__restrict__ scales, int M, int K,
@@ -252,7 +305,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
     stream.issue(t, 0);
     wait_loads<0>();
     Src::pin_tile(t);
-    const float scale = (float)scales[row_tile * kTileRows + r];
+    const float scale = Src::kHasScale ? (float)scales[row_tile * kTileRows + r] : 1.0f;  // else already applied
     half_t *out = W_out + (row_tile * kTileRows + r) * K + kt * kTileK + q * 8;
     half8_t frag[8];
     Src::template fragments<0>(t, frag[0], frag[1]);

@@ -20,7 +20,7 @@ def lib():
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "fp6.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(fp6_\w+|fp5_\w+|fp4_\w+|fp16_\w+)\s*\(", text)
+    names = re.findall(r"\b(fp6g?_\w+|fp5_\w+|fp4_\w+|fp16_\w+)\s*\(", text)
     return sorted(set(names))
 
 
@@ -30,7 +30,8 @@ def test_exports_every_declared_symbol(lib):
                      "fp6_linear_workspace_bytes", "fp6_workspace_init", "fp6_status_str", "fp6_layout_version",
                      "fp16_linear_workspace_bytes", "fp6_tuning_set_split_k", "fp6_tuning_set_tile",
                      "fp5_quantize_pack", "fp5_unpack", "fp5_linear", "fp5_packed_bytes", "fp5_linear_workspace_bytes",
-                     "fp4_quantize_pack", "fp4_unpack", "fp4_linear", "fp4_packed_bytes", "fp4_linear_workspace_bytes"):
+                     "fp4_quantize_pack", "fp4_unpack", "fp4_linear", "fp4_packed_bytes", "fp4_linear_workspace_bytes",
+                     "fp6g_quantize_pack", "fp6g_unpack", "fp6g_linear"):
         assert expected in names
     for n in names:
         assert hasattr(lib, n), "library does not export %s" % n

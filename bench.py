@@ -341,6 +341,7 @@ def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_
     out["down_projection_22016x8192"] = _compare_sweep(pkg, torch, workloads, Mt, Kt, pk_t, sc_t, W16t, Ns)
     out["w5a16_e2m2"] = narrow_sweep(pkg, "fp5", torch, workloads, M, K, W16, Ns)
     out["w4a16_e2m1"] = narrow_sweep(pkg, "fp4", torch, workloads, M, K, W16, Ns)
+    out["w6a16_group128"] = narrow_sweep(pkg, "fp6g", torch, workloads, M, K, W16, Ns)
     del W16, W16t, pk_t, sc_t
     torch.cuda.empty_cache()
     out["decoder_set_70b"] = decoder_set_measurements(pkg, torch, np, workloads, dev)
@@ -348,20 +349,29 @@ def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_
 
 
 def narrow_sweep(pkg, prefix, torch, workloads, M, K, W16, Ns):
-    """A narrower weight format (prefix "fp5": e2m2, 5MK/8 bytes; "fp4": e2m1, MK/2 bytes) on the same layer:
+    """Another weight format (prefix "fp5": e2m2, 5MK/8 bytes; "fp4": e2m1, MK/2 bytes; "fp6g": e3m2 with a scale
+    per row and 128 columns) on the same layer:
     its linear call at every N, rotating over 8 packed copies, plus its quantize_pack and unpack once."""
     dev = W16[0].device
-    packed_bytes = getattr(pkg, prefix + "_packed_bytes")
-    quantize_pack = getattr(pkg, prefix + "_quantize_pack")
-    unpack = getattr(pkg, prefix + "_unpack")
-    linear = getattr(pkg, prefix + "_linear")
-    workspace_bytes = getattr(pkg, prefix + "_linear_workspace_bytes")
+    if prefix == "fp6g":      # e3m2 codes, one scale per row and 128 columns (extra 2MK/128 bytes of scales)
+        packed_bytes, workspace_bytes = pkg.fp6_packed_bytes, pkg.fp6_linear_workspace_bytes
+        quantize_pack = lambda W, pk, sc: pkg.fp6g_quantize_pack(W, 128, pk, sc)
+        unpack = lambda pk, sc, M, K, out: pkg.fp6g_unpack(pk, sc, M, K, 128, out=out)
+        linear = lambda pk, sc, X, M, K, out, workspace: pkg.fp6g_linear(pk, sc, X, M, K, 128, out=out, workspace=workspace)
+        n_scales = M * (K // 128)
+    else:
+        packed_bytes = getattr(pkg, prefix + "_packed_bytes")
+        quantize_pack = getattr(pkg, prefix + "_quantize_pack")
+        unpack = getattr(pkg, prefix + "_unpack")
+        linear = getattr(pkg, prefix + "_linear")
+        workspace_bytes = getattr(pkg, prefix + "_linear_workspace_bytes")
+        n_scales = M
     P = packed_bytes(M, K)
     packed, scales, pack_ms = [], [], []
     for b in range(N_BUFFERS):
         W = W16[b] if b < len(W16) else workloads.make_weights(M, K, seed=300 + b, device=dev)
         pk = torch.empty(P, dtype=torch.uint8, device=dev)
-        sc = torch.empty(M, dtype=torch.float16, device=dev)
+        sc = torch.empty(n_scales, dtype=torch.float16, device=dev)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         quantize_pack(W, pk, sc)
@@ -383,7 +393,7 @@ def narrow_sweep(pkg, prefix, torch, workloads, M, K, W16, Ns):
         ws = torch.zeros(max(workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
         us = _time_graph(torch, lambda i: linear(packed[i % len(packed)], scales[i % len(packed)], X, M, K, out=Y, workspace=ws),
                          len(packed), 10 if n <= 32 else 3)
-        alg = P + 2 * M + 2 * K * n + 2 * M * n
+        alg = P + 2 * n_scales + 2 * K * n + 2 * M * n
         tfl = 2.0 * M * n * K / us * 1e-6
         per_n[str(n)] = {"us": round(us, 2), "weight_GBps": round(P / us * 1e-3, 1), "tflops": round(tfl, 2),
                          "hbm_frac": round(alg / us * 1e-3 / HBM_PEAK_GBPS, 4), "mfma_frac": round(tfl / MFMA_F16_PEAK_TFLOPS, 4)}

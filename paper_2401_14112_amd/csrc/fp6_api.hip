@@ -293,9 +293,15 @@ fp6_status quantize_pack_impl(const void *W_f16, int64_t M, int64_t K, void *pac
         return FP6_ERR_SHAPE;
     if (!aligned16(W_f16) || !aligned16(packed) || !aligned16(scales_f16))
         return FP6_ERR_ALIGN;
-    hipLaunchKernelGGL(quantize_pack_kernel<Fmt>, dim3((unsigned)(M / kTileRows)), dim3(kPackWaves * 64), 0,
+    hipLaunchKernelGGL(row_scale_kernel<Fmt>, dim3((unsigned)((M + kScaleWavesPerBlock - 1) / kScaleWavesPerBlock)),
+                       dim3(kScaleWavesPerBlock * 64), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const half_t *>(W_f16), (int)M, (int)K, static_cast<half_t *>(scales_f16));
+    if (hipGetLastError() != hipSuccess)
+        return FP6_ERR_HIP;
+    const int64_t tiles = (M / kTileRows) * (K / kTileK);
+    hipLaunchKernelGGL(quantize_tiles_kernel<Fmt>, dim3((unsigned)((tiles + 3) / 4)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), static_cast<const half_t *>(W_f16), (int)M, (int)K,
-                       static_cast<uint8_t *>(packed), static_cast<half_t *>(scales_f16));
+                       static_cast<uint8_t *>(packed), static_cast<const half_t *>(scales_f16));
     return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
 }
 

@@ -1,9 +1,9 @@
 // fp6_quantize_pack and fp6_unpack kernels for gfx950.
 //
-// quantize_pack: one block per 16-row tile.  Pass 1 finds the row maxima and the
-// fp16 scales; pass 2 re-reads the rows, rounds every weight to its e3m2 code and
-// writes whole tiles of the packed stream with one 16-byte store per lane per plane
-// (the ahead-of-time re-layout of the paper's Section 5.2, in this library's order).
+// quantize_pack: a first launch finds the row maxima and the fp16 scales, a second
+// one reads W tile by tile, rounds every weight to its code and writes whole tiles of
+// the packed stream with 16-byte stores per lane and plane (the ahead-of-time re-layout
+// of the paper's Section 5.2, in this library's order).
 //
 // unpack: one wave per tile; the same register-level decode as the GEMM, followed by
 // the row scale and a single rounding to fp16.
@@ -177,61 +177,81 @@ struct E2M1Format {
     }
 };
 
-constexpr int kPackWaves = 16;  // waves per block of quantize_pack_kernel
+// ---- per-row scales: two launches ------------------------------------------------------------------
+// row_scale_kernel: one wave per row finds max |W| and writes scale = fp16(max / Fmt::kMax) (a plain read of
+// W at streaming rate).  quantize_tiles_kernel: one wave per 16 x 256 tile reads the tile once, rounds every
+// weight with its row's scale and writes the packed tile.  The scales array is the only thing that passes
+// between the two, so nothing is kept on chip across a row (a row of 22016 fp16 values is 44 KB and a row
+// tile 0.7 MB - more than a CU can hold); W is read twice from memory and that is the algorithmic minimum
+// for a per-row maximum unless rows fit on chip.
+constexpr int kScaleWavesPerBlock = 4;
 
 template <class Fmt>
-__global__ __launch_bounds__(kPackWaves * 64) void quantize_pack_kernel(const half_t *__restrict__ W, int M, int K,
-                                                                        uint8_t *__restrict__ packed,
-                                                                        half_t *__restrict__ scales)
+__global__ __launch_bounds__(kScaleWavesPerBlock * 64) void row_scale_kernel(const half_t *__restrict__ W, int M, int K,
+                                                                              half_t *__restrict__ scales)
 {
-    __shared__ float s_scale[kTileRows];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int row_tile = blockIdx.x;
-    const int KT = K / kTileK;
-
-    // ---- pass 1: one wave per row (16 waves, 16 rows), 1 KB per load instruction
-    for (int r = wave; r < kTileRows; r += kPackWaves) {
-        const u32x4 *row = reinterpret_cast<const u32x4 *>(W + ((int64_t)row_tile * kTileRows + r) * K);
-        ushort2_t mx = {0, 0};
-        for (int i = lane; i < K / 8; i += 64) {
-            const u32x4 v = row[i];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = blockIdx.x * kScaleWavesPerBlock + wave;
+    if (m >= M)
+        return;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(W + (int64_t)m * K);
+    const int n16 = K / 8;  // 16-byte pieces of the row (K % 256 == 0, so n16 % 32 == 0)
+    ushort2_t mx = {0, 0};
+    int i = lane;
+    for (; i + 448 < n16; i += 512) {  // eight independent loads in flight
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            v[u] = __builtin_nontemporal_load(row + i + 64 * u);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                mx = __builtin_elementwise_max(mx, bit_cast<ushort2_t>(v[j] & 0x7fff7fffu));
-        }
-        uint32_t amax = mx[0] > mx[1] ? mx[0] : mx[1];  // finite fp16 magnitudes order like integers
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t other = __shfl_xor(amax, off, 64);
-            amax = other > amax ? other : amax;
-        }
-        if (lane == 0) {
-            const float a = (float)bit_cast<half_t>((uint16_t)amax);
-            const half_t sc = (half_t)(a / Fmt::kMax);  // fp32 quotient, then one rounding to fp16
-            scales[row_tile * kTileRows + r] = sc;
-            s_scale[r] = (float)sc;
-        }
+                mx = __builtin_elementwise_max(mx, bit_cast<ushort2_t>(v[u][j] & 0x7fff7fffu));
     }
-    __syncthreads();
+    for (; i < n16; i += 64) {
+        const u32x4 v = row[i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            mx = __builtin_elementwise_max(mx, bit_cast<ushort2_t>(v[j] & 0x7fff7fffu));
+    }
+    uint32_t amax = mx[0] > mx[1] ? mx[0] : mx[1];  // finite fp16 magnitudes order like integers
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t other = __shfl_xor(amax, off, 64);
+        amax = other > amax ? other : amax;
+    }
+    if (lane == 0)
+        scales[m] = (half_t)((float)bit_cast<half_t>((uint16_t)amax) / Fmt::kMax);  // fp32 quotient, one rounding
+}
 
-    // ---- pass 2: one wave per k-tile; lane (r, q) builds its 48 bytes of the tile
-    const int r = lane & 15, q = lane >> 4;
-    const RowScale scale = make_row_scale(s_scale[r]);
-    const half_t *row = W + ((int64_t)row_tile * kTileRows + r) * K + q * 8;
-    for (int kt = wave; kt < KT; kt += kPackWaves) {
-        uint32_t code[8][8];
+template <class Fmt>
+__global__ __launch_bounds__(256) void quantize_tiles_kernel(const half_t *__restrict__ W, int M, int K,
+                                                             uint8_t *__restrict__ packed,
+                                                             const half_t *__restrict__ scales)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int KT = K / kTileK;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+    if (tile >= (int64_t)(M / kTileRows) * KT)
+        return;
+    const int64_t row_tile = tile / KT, kt = tile % KT;
+    const int r = lane & 15, q = lane >> 4;  // lane (r, q) builds its bytes of the tile
+    const half_t *row = W + (row_tile * kTileRows + r) * K + kt * kTileK + q * 8;
+    u32x4 v[8];
 #pragma unroll
-        for (int f = 0; f < 8; ++f) {
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(row + (int64_t)kt * kTileK + f * 32);
+    for (int f = 0; f < 8; ++f)
+        v[f] = *reinterpret_cast<const u32x4 *>(row + f * 32);
+    const RowScale scale = make_row_scale((float)scales[row_tile * kTileRows + r]);
+    uint32_t code[8][8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                code[f][2 * j] = quantize_code<Fmt>(v[j] & 0xffffu, scale);
-                code[f][2 * j + 1] = quantize_code<Fmt>(v[j] >> 16, scale);
-            }
+    for (int f = 0; f < 8; ++f)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            code[f][2 * j] = quantize_code<Fmt>(v[f][j] & 0xffffu, scale);
+            code[f][2 * j + 1] = quantize_code<Fmt>(v[f][j] >> 16, scale);
         }
-        Fmt::store_tile(code, packed + ((int64_t)row_tile * KT + kt) * Fmt::kTileBytes, lane);
-    }
+    Fmt::store_tile(code, packed + tile * Fmt::kTileBytes, lane);
 }
 
 // Group-wise scales (one per row and per 128 columns): a group lies inside one tile and inside one of a

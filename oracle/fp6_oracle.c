@@ -319,6 +319,62 @@ int fp6o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X
     return 0;
 }
 
+/* The linear layer followed by the element-wise steps that a decoder block
+ * attaches to it (Section 7.3 runs whole LLaMA / OPT decoders: their projections
+ * carry an optional bias, the feed-forward block multiplies silu(gate) by up, and
+ * the last projection of each half of a block is added to the residual stream).
+ * All in double, no intermediate rounding, in this order:
+ *     z[n][m] = scale[m] * sum_k decode(code[m][k]) * X[n][k]      (fp6o_linear)
+ *     z[n][m] += bias[m]                                            if bias
+ *     gated:  y[n][i] = z[n][2i] / (1 + exp(-z[n][2i])) * z[n][2i+1]   (M/2 outputs)
+ *     else:   y[n][m] = z[n][m]
+ *     y[n][o] += residual[n][o]                                     if residual
+ * bias is fp16 [M]; residual is fp16 [N][Mout], Mout = M/2 when gated, else M.
+ * rows (NULL: all) lists OUTPUT rows o; Y is double [N][nrows]. */
+int fp6o_linear_fused(const uint8_t *packed, const uint16_t *scales, const uint16_t *X, int64_t M,
+                      int64_t N, int64_t K, const uint16_t *bias, const uint16_t *residual, int gated,
+                      const int64_t *rows, int64_t nrows, double *Y)
+{
+    const int64_t Mout = gated ? M / 2 : M;
+    if (gated && M % 2)
+        return 3;
+    if (!rows)
+        nrows = Mout;
+    const int64_t per = gated ? 2 : 1; /* weight rows behind one output row */
+    int64_t *wrows = (int64_t *)malloc((size_t)(nrows * per) * sizeof(int64_t));
+    double *Z = (double *)malloc((size_t)(N * nrows * per) * sizeof(double));
+    if (!wrows || !Z) {
+        free(wrows);
+        free(Z);
+        return 2;
+    }
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t o = rows ? rows[i] : i;
+        for (int64_t j = 0; j < per; ++j)
+            wrows[i * per + j] = o * per + j;
+    }
+    int rc = fp6o_linear(packed, scales, X, M, N, K, wrows, nrows * per, Z);
+    if (rc == 0) {
+        for (int64_t n = 0; n < N; ++n)
+            for (int64_t i = 0; i < nrows; ++i) {
+                int64_t o = rows ? rows[i] : i;
+                double z[2] = {0.0, 0.0};
+                for (int64_t j = 0; j < per; ++j) {
+                    z[j] = Z[n * nrows * per + i * per + j];
+                    if (bias)
+                        z[j] += fp6o_half_to_double(bias[o * per + j]);
+                }
+                double y = gated ? z[0] / (1.0 + exp(-z[0])) * z[1] : z[0];
+                if (residual)
+                    y += fp6o_half_to_double(residual[n * Mout + o]);
+                Y[n * nrows + i] = y;
+            }
+    }
+    free(wrows);
+    free(Z);
+    return rc;
+}
+
 /* Plain fp16-weight linear layer in double, for the W16A16 comparison kernel:
  * Y[n][m] = sum_k W[m][k] * X[n][k]. */
 void fp6o_linear_f16(const uint16_t *W, const uint16_t *X, int64_t M, int64_t N, int64_t K,

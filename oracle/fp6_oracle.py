@@ -69,6 +69,8 @@ def _load():
     L.fp6o_linear_codes.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, vp]
     L.fp6o_linear.restype = ci
     L.fp6o_linear.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, vp]
+    L.fp6o_linear_fused.restype = ci
+    L.fp6o_linear_fused.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, ci, vp, i64, vp]
     L.fp6o_linear_f16.restype = None
     L.fp6o_linear_f16.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
     L.fp6o_threads.restype = ci
@@ -226,6 +228,40 @@ def linear(packed: np.ndarray, scales: np.ndarray, X: np.ndarray, M: int, K: int
     Y = np.empty((N, nrows), dtype=np.float64)
     if _load().fp6o_linear(_p(packed), _p(sc), _p(Xb), M, N, K, rp, nrows, _p(Y)):
         raise MemoryError
+    return Y
+
+
+def linear_fused(packed: np.ndarray, scales: np.ndarray, X: np.ndarray, M: int, K: int, bias=None,
+                 residual=None, gated: bool = False, rows=None) -> np.ndarray:
+    """The linear layer plus bias / silu(gate)*up / residual (see fp6o_linear_fused); float64 [N][nrows].
+
+    rows lists OUTPUT rows (of M/2 when gated); bias fp16 [M]; residual fp16 [N][Mout]."""
+    _check_shape(M, K)
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.size == packed_bytes(M, K)
+    Xb = _u16(X)
+    N, K2 = Xb.shape
+    assert K2 == K
+    sc = _u16(scales)
+    assert sc.size == M
+    Mout = M // 2 if gated else M
+    null = ctypes.c_void_p(0)
+    bp = rp_ = null
+    if bias is not None:
+        bb = _u16(bias)
+        assert bb.shape == (M,)
+        bp = _p(bb)
+    if residual is not None:
+        rb = _u16(residual)
+        assert rb.shape == (N, Mout)
+        rp_ = _p(rb)
+    r, nrows, rp = _rows_arg(rows, Mout)
+    Y = np.empty((N, nrows), dtype=np.float64)
+    rc = _load().fp6o_linear_fused(_p(packed), _p(sc), _p(Xb), M, N, K, bp, rp_, int(bool(gated)), rp, nrows, _p(Y))
+    if rc == 2:
+        raise MemoryError
+    if rc:
+        raise ValueError("gated needs an even M")
     return Y
 
 

@@ -345,6 +345,7 @@ def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_
     del W16, W16t, pk_t, sc_t
     torch.cuda.empty_cache()
     out["decoder_set_70b"] = decoder_set_measurements(pkg, torch, np, workloads, dev)
+    out["fused_feed_forward_70b"] = fused_block_measurements(pkg, torch, workloads, dev)
     return out
 
 
@@ -460,6 +461,53 @@ def decoder_set_measurements(pkg, torch, np, workloads, dev, blocks=20):
                           "weight_GBps": round(total_packed / (us * gemms) * 1e-3, 1),
                           "hbm_frac": round(alg / (us * gemms) * 1e-3 / HBM_PEAK_GBPS, 4)}
     out["weight_stream_80_gemms_one_graph"] = stream
+    return out
+
+
+def fused_block_measurements(pkg, torch, workloads, dev, copies=4):
+    """The feed-forward block of a 70B-class decoder (hidden 8192, inner 28672) as two launches of
+    fp6_linear_fused - gate and up interleaved row by row with silu(gate) * up in the kernel, then the down
+    projection adding into the residual stream in place - against the same block from fp6_linear plus
+    separate element-wise kernels (torch's), from graphs that rotate over `copies` sets of weights."""
+    F, H = 28672, 8192
+    gu, dn = [], []
+    for c in range(copies):
+        W = workloads.make_weights(2 * F, H, seed=2000 + c, device=dev)
+        gu.append(pkg.fp6_quantize_pack(W))
+        del W
+        W = workloads.make_weights(H, F, seed=2100 + c, device=dev)
+        dn.append(pkg.fp6_quantize_pack(W))
+        del W
+    out = {"packed_bytes_per_block": pkg.fp6_packed_bytes(2 * F, H) + pkg.fp6_packed_bytes(H, F)}
+    for n in (1, 16, 32):
+        X = workloads.make_activations(n, H, seed=n, device=dev)
+        G = torch.empty((n, 2 * F), dtype=torch.float16, device=dev)
+        A = torch.empty((n, F), dtype=torch.float16, device=dev)
+        T = torch.empty((n, F), dtype=torch.float16, device=dev)
+        D = torch.empty((n, H), dtype=torch.float16, device=dev)
+        R = torch.zeros((n, H), dtype=torch.float16, device=dev)
+        ws1 = torch.zeros(max(pkg.fp6_linear_workspace_bytes(2 * F, n, H), 16), dtype=torch.uint8, device=dev)
+        ws2 = torch.zeros(max(pkg.fp6_linear_workspace_bytes(H, n, F), 16), dtype=torch.uint8, device=dev)
+
+        def fused(i):
+            pkg.fp6_linear_fused(gu[i][0], gu[i][1], X, 2 * F, H, gated=True, out=A, workspace=ws1)
+            pkg.fp6_linear_fused(dn[i][0], dn[i][1], A, H, F, residual=R, out=R, workspace=ws2)
+
+        def separate(i):
+            # the same arithmetic from the plain layer: the row order of the weights does not matter for the time
+            pkg.fp6_linear(gu[i][0], gu[i][1], X, 2 * F, H, out=G, workspace=ws1)
+            torch.sigmoid(G[:, 0::2], out=T)
+            T.mul_(G[:, 0::2]).mul_(G[:, 1::2])
+            pkg.fp6_linear(dn[i][0], dn[i][1], T, H, F, out=D, workspace=ws2)
+            R.add_(D)
+
+        us_f = _time_graph(torch, fused, copies, reps=5)
+        R.zero_()
+        us_s = _time_graph(torch, separate, copies, reps=5)
+        alg = algorithmic_bytes(2 * F, n, H) - n * F * 2 + algorithmic_bytes(H, n, F) + n * H * 2
+        out[str(n)] = {"fused_us_per_block": round(us_f, 2), "separate_us_per_block": round(us_s, 2),
+                       "speedup": round(us_s / us_f, 3),
+                       "fused_hbm_frac": round(alg / us_f * 1e-3 / HBM_PEAK_GBPS, 4)}
     return out
 
 

@@ -114,6 +114,32 @@ fp6_status fp6_linear(const void *packed, const void *scales_f16, const void *X_
                       int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * fp6_linear with the element-wise steps that a decoder block attaches to its
+ * projections done in the kernel's last step, on the fp32 sums, before the one
+ * rounding to fp16 (Section 7.3 runs whole LLaMA / OPT decoders; this removes the
+ * separate kernels, and their trip through memory, between the projections):
+ *     z[n][m] = scale[m] * sum_k e3m2_value(code[m][k]) * X[n][k]
+ *     z[n][m] += bias[m]                                   if bias_f16 != NULL
+ *     gated != 0:  y[n][i] = silu(z[n][2i]) * z[n][2i+1]   (i < M/2; silu(t) = t / (1 + exp(-t)))
+ *     gated == 0:  y[n][m] = z[n][m]
+ *     y += residual[n][.]                                  if residual_f16 != NULL
+ *     Y = fp16_rne(y)
+ * For the gated form the caller interleaves the two projections row by row before
+ * fp6_quantize_pack: weight row 2i is row i of the gate projection, row 2i+1 is row i
+ * of the up projection (M counts both, so Y has M/2 rows).
+ *   bias_f16      in   device, fp16 [M] (one per weight row), or NULL
+ *   residual_f16  in   device, fp16 [N][Mout], Mout = gated ? M/2 : M, or NULL;
+ *                 may be Y_f16 itself (each element is read before it is written)
+ *   Y_f16         out  device, fp16 [N][Mout]
+ *   everything else as for fp6_linear, including the workspace size
+ *   (fp6_linear_workspace_bytes(M, N, K)) and the status codes; bias and residual
+ *   must be 16-byte aligned.
+ */
+fp6_status fp6_linear_fused(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                            int64_t N, int64_t K, const void *bias_f16, const void *residual_f16, int gated,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The library's own W16A16 linear layer, Y[n][m] = fp16_rne(sum_k W[m][k] X[n][k]),
  * built on the same kernel skeleton; it is the in-library baseline that the paper's
  * comparison against an fp16 GEMM (Section 7.1) is re-run against.

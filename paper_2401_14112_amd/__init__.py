@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     fp6g_unpack,
     fp6_layout_version,
     fp6_linear,
+    fp6_linear_fused,
     fp6_linear_workspace_bytes,
     fp6_packed_bytes,
     fp6_quantize_pack,

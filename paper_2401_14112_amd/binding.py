@@ -53,6 +53,8 @@ def load_library():
     L.fp6_unpack.argtypes = [vp, vp, i64, i64, vp, vp]
     L.fp6_linear.restype = ci
     L.fp6_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
+    L.fp6_linear_fused.restype = ci
+    L.fp6_linear_fused.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, ci, vp, sz, vp]
     L.fp16_linear.restype = ci
     L.fp16_linear.argtypes = [vp, vp, vp, i64, i64, i64, vp, sz, vp]
     L.fp5_packed_bytes.restype = sz
@@ -224,6 +226,49 @@ def fp6_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: i
                out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Y[N][M] = X[N][K] @ dequant(packed, scales)[M][K]^T  (fp16 in, fp16 out)."""
     return _linear("fp6", packed, scales, X, M, K, out, workspace)
+
+
+def fp6_linear_fused(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
+                     bias: Optional[torch.Tensor] = None, residual: Optional[torch.Tensor] = None,
+                     gated: bool = False, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """fp6_linear followed, inside the kernel, by + bias[M], silu(row 2i) * row 2i+1 (gated) and + residual.
+
+    Returns Y[N][Mout], Mout = M/2 when gated else M; residual has Y's shape and may be `out` itself."""
+    L = load_library()
+    _dev(packed, torch.uint8, "packed")
+    _dev(scales, torch.float16, "scales")
+    _dev(X, torch.float16, "X")
+    if X.dim() != 2 or X.shape[1] != K:
+        raise Fp6Error("X must be [N][K]")
+    N = X.shape[0]
+    nbytes = L.fp6_packed_bytes(M, K)
+    if nbytes == 0 or N == 0:
+        _check(2)
+    if packed.numel() != nbytes or scales.numel() != M:
+        raise Fp6Error("packed/scales do not match M, K")
+    Mout = M // 2 if gated else M
+    if bias is not None:
+        _dev(bias, torch.float16, "bias")
+        if bias.numel() != M:
+            raise Fp6Error("bias must hold M values")
+    if residual is not None:
+        _dev(residual, torch.float16, "residual")
+        if residual.numel() != N * Mout:
+            raise Fp6Error("residual has the wrong size")
+    if out is None:
+        out = torch.empty((N, Mout), dtype=torch.float16, device=X.device)
+    _dev(out, torch.float16, "out")
+    if out.numel() != N * Mout:
+        raise Fp6Error("out has the wrong size")
+    if workspace is None:
+        workspace = _new_workspace(L.fp6_linear_workspace_bytes(M, N, K), X.device)
+    ws_ptr, ws_len = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
+    _check(L.fp6_linear_fused(packed.data_ptr(), scales.data_ptr(), X.data_ptr(), out.data_ptr(), M, N, K,
+                              bias.data_ptr() if bias is not None else None,
+                              residual.data_ptr() if residual is not None else None, int(bool(gated)),
+                              ws_ptr, ws_len, _stream()))
+    return out
 
 
 def fp5_packed_bytes(M: int, K: int) -> int:

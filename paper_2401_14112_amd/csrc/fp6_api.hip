@@ -183,7 +183,8 @@ TiledPlan plan_tiled(int64_t M, int64_t N, int64_t K, bool tall_tile_ok)
 
 template <class Src, int RT, int NT, int WM, int WN>
 fp6_status launch_tiled_cfg(const TiledPlan &p, const void *weights, const void *scales, const void *X, void *Y,
-                            int64_t M, int64_t N, int64_t K, float4_t *partials, int *counters, hipStream_t stream)
+                            int64_t M, int64_t N, int64_t K, float4_t *partials, int *counters, const Epilogue &epi,
+                            hipStream_t stream)
 {
     auto kernel = linear_tiled_kernel<Src, RT, NT, WM, WN>;
     static bool lds_ok = false;  // per instantiation: allow more than 64 KB of dynamic LDS
@@ -198,13 +199,13 @@ fp6_status launch_tiled_cfg(const TiledPlan &p, const void *weights, const void 
     const dim3 grid((unsigned)(padded_row_blocks * p.n_blocks * p.split)), block(WM * WN * 64);
     hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, stream, weights, static_cast<const half_t *>(scales),
                        static_cast<const half_t *>(X), static_cast<half_t *>(Y), (int)M, (int)N, (int)K, p.split,
-                       p.n_blocks, partials, counters);
+                       p.n_blocks, partials, counters, epi);
     return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
 }
 
 template <class Src>
 fp6_status launch_tiled(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
-                        int64_t K, void *workspace, size_t workspace_bytes, hipStream_t stream)
+                        int64_t K, void *workspace, size_t workspace_bytes, const Epilogue &epi, hipStream_t stream)
 {
     const TiledPlan p = plan_tiled(M, N, K, Src::kTallTile);
     if ((uint64_t)N * (uint64_t)K * 2u >= (1ull << 31))
@@ -221,7 +222,8 @@ fp6_status launch_tiled(const void *weights, const void *scales, const void *X, 
     const TileShape &t = p.tile;
 #define FP6_TILED_CASE(RT_, NT_, WM_, WN_)                                                                        \
     if (t.rt == RT_ && t.nt == NT_ && t.wm == WM_ && t.wn == WN_)                                                 \
-        return launch_tiled_cfg<Src, RT_, NT_, WM_, WN_>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
+        return launch_tiled_cfg<Src, RT_, NT_, WM_, WN_>(p, weights, scales, X, Y, M, N, K, partials, counters, epi, \
+                                                         stream);
     FP6_TILED_CASE(2, 4, 4, 2)
     FP6_TILED_CASE(2, 4, 4, 1)
     if constexpr (Src::kTallTile) {
@@ -234,7 +236,8 @@ fp6_status launch_tiled(const void *weights, const void *scales, const void *X, 
 
 template <class Src, int C>
 fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const void *scales, const void *X, void *Y,
-                             int64_t M, int64_t N, int64_t K, float4_t *partials, int *counters, hipStream_t stream)
+                             int64_t M, int64_t N, int64_t K, float4_t *partials, int *counters, const Epilogue &epi,
+                             hipStream_t stream)
 {
     constexpr StreamCfg c = Src::kPackedConfigs ? kStreamCfg[C] : kStreamCfgFp16[C];
     auto kernel = linear_stream_kernel<Src, c.nt, c.waves, c.depth, c.stage, c.spread>;
@@ -250,12 +253,16 @@ fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const voi
     const dim3 grid((unsigned)(p.row_blocks * p.split)), block(c.waves * 64);
     // tokens are processed 16*nt at a time; each pass re-streams the weights
     const int64_t step = 16 * c.nt;
+    const int64_t Mout = epi.gated ? M / 2 : M;
     for (int64_t n0 = 0; n0 < N; n0 += step) {
         const int64_t n = (N - n0 < step) ? (N - n0) : step;
         const half_t *Xp = static_cast<const half_t *>(X) + n0 * K;
-        half_t *Yp = static_cast<half_t *>(Y) + n0 * M;
+        half_t *Yp = static_cast<half_t *>(Y) + n0 * Mout;
+        Epilogue e = epi;
+        if (e.residual)
+            e.residual += n0 * Mout;
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, weights, static_cast<const half_t *>(scales), Xp, Yp,
-                           (int)M, (int)n, (int)K, p.split, partials, counters);
+                           (int)M, (int)n, (int)K, p.split, partials, counters, e);
         if (hipGetLastError() != hipSuccess)
             return FP6_ERR_HIP;
     }
@@ -264,7 +271,7 @@ fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const voi
 
 template <class Src>
 fp6_status launch_stream(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
-                         int64_t K, void *workspace, size_t workspace_bytes, hipStream_t stream)
+                         int64_t K, void *workspace, size_t workspace_bytes, const Epilogue &epi, hipStream_t stream)
 {
     const StreamPlan p = plan_stream(M, N, K, Src::kPackedConfigs);
     if (p.total_bytes() > 0) {
@@ -277,10 +284,10 @@ fp6_status launch_stream(const void *weights, const void *scales, const void *X,
     float4_t *partials =
         p.total_bytes() ? reinterpret_cast<float4_t *>(static_cast<uint8_t *>(workspace) + p.counter_bytes) : nullptr;
     switch (p.cfg) {
-    case 0: return launch_stream_cfg<Src, 0>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
-    case 1: return launch_stream_cfg<Src, 1>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
-    case 2: return launch_stream_cfg<Src, 2>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
-    default: return launch_stream_cfg<Src, 3>(p, weights, scales, X, Y, M, N, K, partials, counters, stream);
+    case 0: return launch_stream_cfg<Src, 0>(p, weights, scales, X, Y, M, N, K, partials, counters, epi, stream);
+    case 1: return launch_stream_cfg<Src, 1>(p, weights, scales, X, Y, M, N, K, partials, counters, epi, stream);
+    case 2: return launch_stream_cfg<Src, 2>(p, weights, scales, X, Y, M, N, K, partials, counters, epi, stream);
+    default: return launch_stream_cfg<Src, 3>(p, weights, scales, X, Y, M, N, K, partials, counters, epi, stream);
     }
 }
 
@@ -323,18 +330,20 @@ fp6_status unpack_impl(const void *packed, const void *scales_f16, int64_t M, in
 
 template <class Src>
 fp6_status packed_linear_impl(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
-                              int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream)
+                              int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream,
+                              const Epilogue &epi = Epilogue{nullptr, nullptr, 0})
 {
     if (!packed || !scales_f16 || !X_f16 || !Y_f16)
         return FP6_ERR_NULL;
     if (!shape_ok(M, K) || N <= 0 || N >= (1ll << 31))
         return FP6_ERR_SHAPE;
-    if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(X_f16) || !aligned16(Y_f16))
+    if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(X_f16) || !aligned16(Y_f16) || !aligned16(epi.bias)
+        || !aligned16(epi.residual))
         return FP6_ERR_ALIGN;
     if (N > kStreamMaxN)
-        return launch_tiled<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
+        return launch_tiled<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes, epi,
                                  static_cast<hipStream_t>(stream));
-    return launch_stream<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
+    return launch_stream<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes, epi,
                               static_cast<hipStream_t>(stream));
 }
 
@@ -412,6 +421,15 @@ fp6_status fp6_linear(const void *packed, const void *scales_f16, const void *X_
 {
     return packed_linear_impl<PackedFp6Source>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
                                                stream);
+}
+
+fp6_status fp6_linear_fused(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                            int64_t N, int64_t K, const void *bias_f16, const void *residual_f16, int gated,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    const Epilogue epi{static_cast<const half_t *>(bias_f16), static_cast<const half_t *>(residual_f16), gated ? 1 : 0};
+    return packed_linear_impl<PackedFp6Source>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
+                                               stream, epi);
 }
 
 fp6_status fp6g_quantize_pack(const void *W_f16, int64_t M, int64_t K, int64_t group, void *packed, void *scales_f16,
@@ -500,9 +518,9 @@ fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_
         return FP6_ERR_ALIGN;
     if (N > kStreamMaxN)
         return launch_tiled<PlainFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
-                                             static_cast<hipStream_t>(stream));
+                                             Epilogue{nullptr, nullptr, 0}, static_cast<hipStream_t>(stream));
     return launch_stream<PlainFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
-                                          static_cast<hipStream_t>(stream));
+                                          Epilogue{nullptr, nullptr, 0}, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

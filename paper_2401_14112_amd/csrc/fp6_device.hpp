@@ -487,4 +487,65 @@ struct PlainFp16Source {
     }
 };
 
+// ---- last step of the linear kernels ----------------------------------------------------------
+// What happens between a finished fp32 sum and the stored fp16: the per-row scale (sources that
+// have one), then the element-wise steps that a decoder block attaches to its projections
+// (Section 7.3 of the paper runs whole decoders): an optional bias per weight row, optionally
+// silu(gate) * up over row pairs, an optional residual, one rounding to fp16 at the very end.
+struct Epilogue {
+    const half_t *bias;      // fp16 [M] or nullptr
+    const half_t *residual;  // fp16 laid out like the output, or nullptr; may be the output itself
+    int gated;               // nonzero: weight rows 2i (gate), 2i+1 (up) give output row i of M/2
+};
+
+// Rows m0 .. m0+3 (m0 % 4 == 0) of token column `col`: the four sums one lane holds after the MFMAs.
+// Y and the residual are [tokens][M] (or [tokens][M/2] when gated).
+template <bool kHasScale>
+__device__ __forceinline__ void finish_rows(const Epilogue &e, const half_t *__restrict__ scales, const float4_t &sum,
+                                            int col, int m0, int M, half_t *Y)
+{
+    float v[4] = {sum[0], sum[1], sum[2], sum[3]};
+    if (kHasScale) {
+        const half4_t s4 = *reinterpret_cast<const half4_t *>(scales + m0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            v[i] *= (float)s4[i];
+    }
+    if (e.bias) {
+        const half4_t b4 = *reinterpret_cast<const half4_t *>(e.bias + m0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            v[i] += (float)b4[i];
+    }
+    if (!e.gated) {
+        const int64_t at = (int64_t)col * M + m0;
+        if (e.residual) {
+            const half4_t r4 = *reinterpret_cast<const half4_t *>(e.residual + at);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                v[i] += (float)r4[i];
+        }
+        half4_t y;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            y[i] = (half_t)v[i];
+        *reinterpret_cast<half4_t *>(Y + at) = y;
+    } else {
+        const int64_t at = (int64_t)col * (M >> 1) + (m0 >> 1);
+        float o[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            o[i] = v[2 * i] / (1.0f + __expf(-v[2 * i])) * v[2 * i + 1];
+        if (e.residual) {
+            const half2_t r2 = *reinterpret_cast<const half2_t *>(e.residual + at);
+            o[0] += (float)r2[0];
+            o[1] += (float)r2[1];
+        }
+        half2_t y;
+        y[0] = (half_t)o[0];
+        y[1] = (half_t)o[1];
+        *reinterpret_cast<half2_t *>(Y + at) = y;
+    }
+}
+
 }  // namespace fp6

@@ -51,8 +51,8 @@ __device__ __forceinline__ void static_for(F &&f)
 template <class Src, int NT, int WAVES, int DEPTH, int G, int XSPREAD>
 __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     const void *__restrict__ weights, const half_t *__restrict__ scales, const half_t *__restrict__ X,
-    half_t *__restrict__ Y, int M, int N, int K, int S, float4_t *__restrict__ partials,
-    int *__restrict__ counters)
+    half_t *Y, int M, int N, int K, int S, float4_t *__restrict__ partials,
+    int *__restrict__ counters, Epilogue epi)
 {
     constexpr int COPIES = G * NT * 8;  // copy instructions (1 KB each: one token tile x one run) per stage
     static_assert(COPIES % WAVES == 0, "the copies of a stage must split evenly over the waves");
@@ -196,23 +196,11 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     const int n_in_tile = lane & 15;
     const int m0 = row_tile * kTileRows + 4 * (lane >> 4);
     auto finish = [&](const float4_t (&sum)[NT]) {
-        float sc[4] = {1.f, 1.f, 1.f, 1.f};
-        if (Src::kHasScale) {
-            const half4_t s4 = *reinterpret_cast<const half4_t *>(scales + m0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                sc[i] = (float)s4[i];
-        }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int col = nt * 16 + n_in_tile;
-            if (col < N) {
-                half4_t y;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    y[i] = (half_t)(sum[nt][i] * sc[i]);
-                *reinterpret_cast<half4_t *>(Y + (int64_t)col * M + m0) = y;
-            }
+            if (col < N)
+                finish_rows<Src::kHasScale>(epi, scales, sum[nt], col, m0, M, Y);
         }
     };
 

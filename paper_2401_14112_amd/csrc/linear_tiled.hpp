@@ -26,8 +26,8 @@ namespace fp6 {
 template <class Src, int RT, int NT, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     const void *__restrict__ weights, const half_t *__restrict__ scales, const half_t *__restrict__ X,
-    half_t *__restrict__ Y, int M, int N, int K, int S, int n_blocks, float4_t *__restrict__ partials,
-    int *__restrict__ counters)
+    half_t *Y, int M, int N, int K, int S, int n_blocks, float4_t *__restrict__ partials,
+    int *__restrict__ counters, Epilogue epi)
 {
     constexpr int WAVES = WM * WN;
     constexpr int BNT = WN * NT;             // 16-token tiles of the block
@@ -211,23 +211,11 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     const int n_tiles_total = n_blocks * BNT;
     auto finish = [&](const float4_t (&sum)[NT], int r) {
         const int m0 = (row_tile0 + r) * kTileRows + 4 * (lane >> 4);
-        float sc[4] = {1.f, 1.f, 1.f, 1.f};
-        if (Src::kHasScale) {
-            const half4_t s4 = *reinterpret_cast<const half4_t *>(scales + m0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                sc[i] = (float)s4[i];
-        }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int col = col0 + nt * 16 + n_in_tile;
-            if (col < N) {
-                half4_t y;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    y[i] = (half_t)(sum[nt][i] * sc[i]);
-                *reinterpret_cast<half4_t *>(Y + (int64_t)col * M + m0) = y;
-            }
+            if (col < N)
+                finish_rows<Src::kHasScale>(epi, scales, sum[nt], col, m0, M, Y);
         }
     };
 

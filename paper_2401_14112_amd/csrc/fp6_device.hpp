@@ -81,6 +81,7 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t num_bytes
     return r;
 }
 
+constexpr int kPartialBatch = 4;  // split-K: partial tiles of this many k slices are fetched per trip to memory
 constexpr int kOutOfRange = (int)0x80000000u;  // a lane offset no buffer here reaches: reads as zeros
 
 // The pipelined kernels issue their loads from inline assembly and wait for them with explicit

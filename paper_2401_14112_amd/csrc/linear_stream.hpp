@@ -233,23 +233,35 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     arrived = __builtin_amdgcn_readfirstlane(arrived);
     if (arrived != S - 1)
         return;
+    // The partial tiles of kPartialBatch slices are requested together (one trip to memory per batch, not
+    // per slice) and then added in slice order.  Every lane loads (lanes of token columns >= N read
+    // words that nobody stored; their sums are never written).
     float4_t sum[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
         sum[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
-    for (int s_ = 0; s_ < S; ++s_) {
+    for (int s0 = 0; s0 < S; s0 += kPartialBatch) {
+        float4_t part[kPartialBatch][NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            if (nt * 16 + n_in_tile < N) {
-                if (s_ == split) {
-                    sum[nt] += acc[nt];
-                } else {
-                    const float *src = slot(s_, nt);
+        for (int u = 0; u < kPartialBatch; ++u) {
+            const int s_ = s0 + u < S ? s0 + u : S - 1;  // clamped: always an existing slot
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        sum[nt][i] += __hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
+            for (int nt = 0; nt < NT; ++nt) {
+                const float *src = slot(s_, nt);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    part[u][nt][i] = __hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+        }
+#pragma unroll
+        for (int u = 0; u < kPartialBatch; ++u) {
+            const int s_ = s0 + u;
+            if (s_ < S) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    sum[nt] += s_ == split ? acc[nt] : part[u][nt];
+            }
+        }
     }
     finish(sum);
     if (lane == 0)

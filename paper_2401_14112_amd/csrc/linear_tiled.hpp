@@ -263,14 +263,28 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
             sum[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < S; ++s) {
+        // PB slices per trip to memory, added in slice order (see linear_stream.hpp); fewer with wide
+        // wave tiles, whose partial tiles take more registers
+        constexpr int PB = NT >= 8 ? kPartialBatch / 2 : kPartialBatch;
+        for (int s0 = 0; s0 < S; s0 += PB) {
+            float4_t part[PB][NT];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                if (col0 + nt * 16 + n_in_tile < N) {
+            for (int u = 0; u < PB; ++u) {
+                const int s = s0 + u < S ? s0 + u : S - 1;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
                     const float *src = partial_ptr(s, r, nt);
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        sum[nt][i] += __hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        part[u][nt][i] = __hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < PB; ++u)
+                if (s0 + u < S) {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        sum[nt] += part[u][nt];
                 }
         }
         finish(sum, r);

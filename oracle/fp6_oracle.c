@@ -956,6 +956,228 @@ int fp4o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X
     return 0;
 }
 
+/* ====================================================================== *
+ * The 3-bit variant (W3A16; the paper lists 3-bit among the widths its scheme
+ * supports, Section 1).  FP3 is read as e2m0, code = s e1 e0: Eq. 1 with bias
+ * 2^(2-1)-1 = 1 and no mantissa bits, the E = 0 binade read as subnormals
+ * 0.M * 2^(1-bias) = 0, no inf/NaN: values 0 | 1 | 2 | 4.  (The other 3-bit
+ * split, e1m1 with bias 0, gives the uniform grid 0 1 2 3, i.e. a sign-magnitude
+ * integer; e2m0 is the one with a floating-point character.)  Quantizer: the
+ * same recipe with 4 in place of 28.
+ * ====================================================================== */
+
+#define FP3O_TILE_BYTES 1536 /* 16 * 256 * 3 / 8 */
+
+double fp3o_decode(int code)
+{
+    int S = (code >> 2) & 1;
+    int E = code & 3;
+    double mag = E == 0 ? 0.0 : ldexp(1.0, E - 1); /* 0.M * 2^(1-bias) with no M; 1.M * 2^(E-bias) */
+    return S ? -mag : mag;
+}
+
+/* fp16 nearest to amax/4 (ties to even), decided with exact arithmetic. */
+uint16_t fp3o_scale_for_amax(uint16_t amax_bits)
+{
+    double a = fp6o_half_to_double((uint16_t)(amax_bits & 0x7fffu));
+    uint16_t guess = fp6o_double_to_half(a / 4.0);
+    int lo = guess > 0 ? guess - 1 : 0;
+    int hi = guess + 1;
+    int best = -1;
+    double best_err = 0.0;
+    for (int h = lo; h <= hi; ++h) {
+        double err = fabs(4.0 * fp6o_half_to_double((uint16_t)h) - a); /* exact */
+        if (best < 0 || err < best_err || (err == best_err && (h & 1) == 0 && (best & 1) == 1)) {
+            best = h;
+            best_err = err;
+        }
+    }
+    return (uint16_t)best;
+}
+
+int fp3o_quantize_one(uint16_t w_bits, uint16_t scale_bits)
+{
+    int sign = (w_bits >> 15) & 1;
+    double a = fp6o_half_to_double((uint16_t)(w_bits & 0x7fffu));
+    double s = fp6o_half_to_double((uint16_t)(scale_bits & 0x7fffu));
+    if (s == 0.0)
+        return sign << 2;
+    int best = 0;
+    double best_err = fabs(a - fp3o_decode(0) * s);
+    for (int g = 1; g < 4; ++g) {
+        double err = fabs(a - fp3o_decode(g) * s);
+        if (err < best_err || (err == best_err && (g & 1) == 0)) {
+            best = g;
+            best_err = err;
+        }
+    }
+    return (sign << 2) | best;
+}
+
+int fp3o_quantize(const uint16_t *W, int64_t M, int64_t K, uint8_t *codes, uint16_t *scales)
+{
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        uint16_t amax = 0;
+        for (int64_t k = 0; k < K; ++k) {
+            uint16_t mag = (uint16_t)(W[m * K + k] & 0x7fffu);
+            if (mag >= 0x7c00u)
+                bad |= 1;
+            if (mag > amax)
+                amax = mag;
+        }
+        uint16_t sc = fp3o_scale_for_amax(amax);
+        scales[m] = sc;
+        for (int64_t k = 0; k < K; ++k)
+            codes[m * K + k] = (uint8_t)fp3o_quantize_one(W[m * K + k], sc);
+    }
+    return bad;
+}
+
+int64_t fp3o_packed_bytes(int64_t M, int64_t K) { return M * K / 8 * 3; }
+
+/*
+ * Bit address of bit b (0..2 = e0, e1, s) of the code of weight (m, k) in the packed
+ * 3-bit stream.  Tiles of 16 rows x 256 columns, row-tile major, 1536 bytes each: a plane
+ * of 1024 bytes (64 slots of 16 bytes) followed by a plane of 512 bytes (64 slots of 8
+ * bytes), slot = 16*q + r as in the other layouts.  The slot owns six 32-bit words, words
+ * 0..3 in the first plane, 4..5 in the second; words 3g .. 3g+2 serve the runs 4g .. 4g+3
+ * (g = 0, 1).  The reader wants, per run, a word of eight 4-bit fields "s e1 e0 0" (the
+ * 4-bit code of the same value), field j = column 32*run + 8*q + j.  Runs 4g+i, i < 3, sit
+ * in word 3g+i in exactly that form, which leaves bit 0 of every field free; the three bits
+ * of run 4g+3 are spread over those free bits: its bit b+1 of field j is bit 4j of word
+ * 3g+b.  (The ahead-of-time bit-level re-layout of Section 5.2 with a 3+1 split: the
+ * reader needs one AND per in-place run and three AND/shift/OR for the spread one.)
+ */
+uint64_t fp3o_pos(int64_t K, int64_t m, int64_t k, int b)
+{
+    int64_t row_tile = m / FP6O_TILE_ROWS;
+    int r = (int)(m % FP6O_TILE_ROWS);
+    int64_t k_tile = k / FP6O_TILE_K;
+    int kk = (int)(k % FP6O_TILE_K);
+    int run = kk / 32;
+    int q = (kk % 32) / 8;
+    int j = kk % 8;
+    int slot = 16 * q + r;
+    int g = run / 4, i = run % 4;
+    int word = i < 3 ? 3 * g + i : 3 * g + b;
+    int bit = i < 3 ? 4 * j + b + 1 : 4 * j;
+    uint64_t tile = (uint64_t)(row_tile * (K / FP6O_TILE_K) + k_tile);
+    uint64_t byte_addr = tile * FP3O_TILE_BYTES
+                         + (word < 4 ? (uint64_t)slot * 16u + (uint64_t)word * 4u
+                                     : 1024u + (uint64_t)slot * 8u + (uint64_t)(word - 4) * 4u);
+    return byte_addr * 8u + (uint64_t)bit;
+}
+
+void fp3o_pack(const uint8_t *codes, int64_t M, int64_t K, uint8_t *packed)
+{
+    memset(packed, 0, (size_t)fp3o_packed_bytes(M, K));
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k)
+            for (int b = 0; b < 3; ++b)
+                if ((codes[m * K + k] >> b) & 1) {
+                    uint64_t p = fp3o_pos(K, m, k, b);
+                    packed[p >> 3] |= (uint8_t)(1u << (p & 7));
+                }
+}
+
+void fp3o_unpack_codes(const uint8_t *packed, int64_t M, int64_t K, uint8_t *codes)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            int c = 0;
+            for (int b = 0; b < 3; ++b) {
+                uint64_t p = fp3o_pos(K, m, k, b);
+                c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
+            }
+            codes[m * K + k] = (uint8_t)c;
+        }
+}
+
+int fp3o_quantize_pack(const uint16_t *W, int64_t M, int64_t K, uint8_t *packed, uint16_t *scales)
+{
+    uint8_t *codes = (uint8_t *)malloc((size_t)(M * K));
+    if (!codes)
+        return 2;
+    int bad = fp3o_quantize(W, M, K, codes, scales);
+    fp3o_pack(codes, M, K, packed);
+    free(codes);
+    return bad;
+}
+
+int fp3o_unpack(const uint8_t *packed, const uint16_t *scales, int64_t M, int64_t K, uint16_t *W)
+{
+    uint8_t *codes = (uint8_t *)malloc((size_t)(M * K));
+    if (!codes)
+        return 2;
+    fp3o_unpack_codes(packed, M, K, codes);
+    for (int64_t m = 0; m < M; ++m) {
+        double s = fp6o_half_to_double(scales[m]);
+        for (int64_t k = 0; k < K; ++k)
+            W[m * K + k] = fp6o_double_to_half(fp3o_decode(codes[m * K + k]) * s);
+    }
+    free(codes);
+    return 0;
+}
+
+void fp3o_linear_codes(const uint8_t *codes, const uint16_t *scales, const uint16_t *X, int64_t M,
+                       int64_t N, int64_t K, const int64_t *rows, int64_t nrows, double *Y)
+{
+    if (!rows)
+        nrows = M;
+    double *Xd = (double *)malloc((size_t)(N * K) * sizeof(double));
+    for (int64_t i = 0; i < N * K; ++i)
+        Xd[i] = fp6o_half_to_double(X[i]);
+    double table[8];
+    for (int c = 0; c < 8; ++c)
+        table[c] = fp3o_decode(c);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t m = rows ? rows[i] : i;
+        double s = fp6o_half_to_double(scales[m]);
+        for (int64_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += table[codes[m * K + k]] * Xd[n * K + k];
+            Y[n * nrows + i] = s * acc;
+        }
+    }
+    free(Xd);
+}
+
+int fp3o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X, int64_t M,
+                int64_t N, int64_t K, const int64_t *rows, int64_t nrows, double *Y)
+{
+    if (!rows)
+        nrows = M;
+    uint8_t *codes = (uint8_t *)malloc((size_t)(nrows * K));
+    uint16_t *sc = (uint16_t *)malloc((size_t)nrows * sizeof(uint16_t));
+    if (!codes || !sc) {
+        free(codes);
+        free(sc);
+        return 2;
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t m = rows ? rows[i] : i;
+        sc[i] = scales[m];
+        for (int64_t k = 0; k < K; ++k) {
+            int c = 0;
+            for (int b = 0; b < 3; ++b) {
+                uint64_t p = fp3o_pos(K, m, k, b);
+                c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
+            }
+            codes[i * K + k] = (uint8_t)c;
+        }
+    }
+    fp3o_linear_codes(codes, sc, X, nrows, N, K, NULL, nrows, Y);
+    free(codes);
+    free(sc);
+    return 0;
+}
+
 #ifdef _OPENMP
 #include <omp.h>
 int fp6o_threads(void) { return omp_get_max_threads(); }

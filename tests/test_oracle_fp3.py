@@ -1,0 +1,213 @@
+"""Pins for the 3-bit (e2m0) part of the oracle (CPU only).
+
+Same kinds of pins as for e3m2: hand-evaluated values of the paper's Eq. 1 (tests/golden/), the bit-copy
+cast of Section 5.3, Eq. 3 as an independent decode route, hand-derived ties, the quantizer's three exact
+routes, the layout as a bijection and as a register-level reconstruction written from its description, and
+the linear layer against brute force, closed forms and numpy's fp64 matmul.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import workloads
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.fixture(scope="module")
+def o5():
+    from oracle import fp3_oracle
+    return fp3_oracle
+
+
+def _read(name):
+    rows = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            rows.append([float(t) for t in line.split()])
+    return rows
+
+
+def test_decode_matches_hand_table(o5):
+    vals = [v for row in _read("e2m0_values.txt") for v in row]
+    assert len(vals) == 4
+    for c in range(4):
+        assert o5.decode(c) == vals[c]
+        assert o5.decode(c + 4) == -vals[c]
+    assert np.signbit(o5.decode(4)) and o5.decode(4) == 0.0
+    t = o5.decode_table()
+    assert t[:4].sum() == 7.0 and t[:4].max() == 4.0
+    assert np.all(np.diff(t[:4]) > 0)
+
+
+def test_decode_equals_bitcopy_cast(o5):
+    """Section 5.3, Eq. 3 for e2m0: sign to bit 15, EE to bits 11..10 of an fp16 (E16 := Ex), times 2^(15-1)."""
+    for c in range(8):
+        bits = np.array([((c & 0x4) << 13) | ((c & 0x3) << 10)], dtype=np.uint16)
+        v = float(bits.view(np.float16)[0]) * 16384.0
+        assert v == o5.decode(c), c
+        assert np.signbit(v) == np.signbit(o5.decode(c))
+
+
+def test_values_are_a_subset_of_the_4_bit_grid(o5):
+    """e2m0 code s e1 e0 has the value of the e2m1 code s e1 e0 0 (what the GPU's unpack relies on)."""
+    from oracle import fp4_oracle
+    for c in range(8):
+        assert o5.decode(c) == fp4_oracle.decode(c << 1)
+        assert np.signbit(o5.decode(c)) == np.signbit(fp4_oracle.decode(c << 1))
+
+
+def test_hand_ties(o5):
+    one = int(np.array([1.0], dtype=np.float16).view(np.uint16)[0])
+    for value, grid, g in _read("quantize_ties_e2m0.txt"):
+        w = np.array([value], dtype=np.float16)
+        assert float(w[0]) == value or abs(float(w[0]) - value) < 1e-3     # inputs are (near) fp16 values
+        code = o5.quantize_one(int(w.view(np.uint16)[0]), one)
+        assert code == int(g), (value, code)
+        assert o5.decode(code) == grid
+        assert o5.quantize_one(int((-w).view(np.uint16)[0]), one) == int(g) + 4
+
+
+def test_scale_is_exactly_rounded_and_quantizer_routes_agree(o5):
+    rng = np.random.default_rng(5)
+    amax = rng.integers(1, 0x7C00, size=4000).astype(np.uint16)
+    for a in amax[:2000]:
+        a_val = float(np.array([a], dtype=np.uint16).view(np.float16)[0])
+        want = np.float16(np.float64(a_val) / 4.0)        # fp64 quotient then one rounding: no double-rounding case
+        assert o5.scale_for_amax(int(a)) == int(np.array([want]).view(np.uint16)[0])
+    # three exact routes to the code: oracle (argmin of exact differences), fp32 divide + round to grid, midpoints
+    table = o5.decode_table()[:4]
+    mids = (table[1:] + table[:-1]) / 2
+    W = workloads.make_weights(16, 256, seed=3).numpy()
+    codes, scales = o5.quantize(W)
+    for m in range(16):
+        s = np.float64(scales[m])
+        ratio = np.abs(W[m].astype(np.float64)) / s
+        g = np.searchsorted(mids, ratio, side="left")      # ratio == mid goes to the lower index ...
+        tie = np.isin(ratio, mids)
+        g = np.where(tie & (g % 2 == 1), g + 1, g)         # ... unless the upper code is the even one
+        g = np.minimum(g, 3)
+        want = g + 4 * np.signbit(W[m]).astype(np.int64)
+        assert np.array_equal(codes[m], want)
+
+
+def test_every_code_round_trips(o5):
+    for s in (2.0 ** -6, 0.01171875):
+        row = np.array([o5.decode(c) * s for c in range(8)] * 32, dtype=np.float64)
+        W = np.tile(row.astype(np.float16), (16, 1))
+        assert np.all(W.astype(np.float64) == row)         # exact in fp16
+        codes, scales = o5.quantize(W)
+        assert np.all(scales.astype(np.float64) == s)
+        assert np.array_equal(codes[0], np.tile(np.arange(8, dtype=np.uint8), 32))
+        packed = o5.pack(codes)
+        assert np.array_equal(o5.unpack_codes(packed, 16, 256), codes)
+        Wd = o5.unpack(packed, scales, 16, 256)
+        assert np.array_equal(Wd.view(np.uint16), W.view(np.uint16))      # -0 keeps its sign
+
+
+def test_pos_is_a_bijection(o5):
+    for M, K in ((16, 256), (32, 512)):
+        seen = np.zeros(3 * M * K, dtype=np.uint8)
+        for m in range(M):
+            for k in range(K):
+                for b in range(3):
+                    p = o5.pos(K, m, k, b)
+                    assert 0 <= p < 3 * M * K
+                    seen[p] += 1
+                    assert p // (1536 * 8) == (m // 16) * (K // 256) + k // 256
+        assert np.all(seen == 1)
+        assert o5.packed_bytes(M, K) == 3 * M * K // 8
+
+
+def _swar_unpack_tile(tile_bytes):
+    """One tile (1536 bytes) -> codes [16][256], read the way a lane does: its six words are four from the
+    16-byte plane and two from the 8-byte plane; words 3g..3g+2 give runs 4g..4g+2 as 4-bit fields
+    "s e1 e0 ." after masking bit 0 of every field, and run 4g+3 is stitched from the masked-out bits.
+    Written from the layout's description, without pos()."""
+    plane0 = tile_bytes[:1024].view(np.uint32).reshape(64, 4)
+    plane1 = tile_bytes[1024:].view(np.uint32).reshape(64, 2)
+    codes = np.zeros((16, 256), dtype=np.uint8)
+    for slot in range(64):
+        r, q = slot % 16, slot // 16
+        words = [int(w) for w in plane0[slot]] + [int(w) for w in plane1[slot]]
+        for g in range(2):
+            A = words[3 * g:3 * g + 3]
+            T = [a & 0xEEEEEEEE for a in A]
+            T.append(((A[0] & 0x11111111) << 1) | ((A[1] & 0x11111111) << 2) | ((A[2] & 0x11111111) << 3))
+            for i in range(4):
+                for j in range(8):
+                    field = (T[i] >> (4 * j)) & 0xF
+                    assert field & 1 == 0
+                    codes[r, (4 * g + i) * 32 + q * 8 + j] = field >> 1
+    return codes
+
+
+def test_register_level_reconstruction(o5):
+    M, K = 32, 512
+    codes = (workloads.make_codes(M, K, 9).numpy() & 7).astype(np.uint8)
+    packed = o5.pack(codes)
+    tiles = packed.reshape(M // 16, K // 256, 1536)
+    for rt in range(M // 16):
+        for kt in range(K // 256):
+            got = _swar_unpack_tile(tiles[rt, kt])
+            assert np.array_equal(got, codes[rt * 16:(rt + 1) * 16, kt * 256:(kt + 1) * 256])
+    assert np.array_equal(o5.unpack_codes(packed, M, K), codes)
+
+
+def test_unpack_is_layout_independent(o5):
+    name, M, K = workloads.TINY
+    W = workloads.make_weights(M, K, seed=0).numpy()
+    codes, scales = o5.quantize(W)
+    packed, scales2 = o5.quantize_pack(W)
+    assert np.array_equal(scales.view(np.uint16), scales2.view(np.uint16))
+    want = (o5.decode_table()[codes] * scales.astype(np.float64)[:, None]).astype(np.float16)
+    got = o5.unpack(packed, scales2, M, K)
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+    # every row reaches a +-4 code; the error is at most half a step of the top binade (1 * scale), plus the
+    # rounding of the scale (the row maximum may sit 4 * 2^-11 * scale above the grid) and of the fp16 result
+    assert np.all((codes & 3).max(axis=1) == 3)
+    err = np.abs(got.astype(np.float64) - W.astype(np.float64))
+    assert np.all(err <= (1.0 + 4 * 2.0 ** -10) * scales.astype(np.float64)[:, None])
+
+
+def test_linear_against_brute_force_and_numpy(o5):
+    M, K, N = 32, 512, 5
+    W = workloads.make_weights(M, K, seed=4).numpy()
+    X = workloads.make_activations(N, K, seed=4).numpy()
+    packed, scales = o5.quantize_pack(W)
+    codes = o5.unpack_codes(packed, M, K)
+    Y = o5.linear(packed, scales, X, M, K)
+    table = o5.decode_table()
+    Wd = table[codes] * scales.astype(np.float64)[:, None]
+    brute = np.zeros((N, M))
+    for n in range(N):
+        for m in range(0, M, 7):
+            acc = 0.0
+            for k in range(K):
+                acc += table[codes[m, k]] * float(X[n, k])
+            brute[n, m] = float(scales[m]) * acc
+    assert np.allclose(Y[:, ::7], brute[:, ::7], rtol=1e-13, atol=0)
+    assert np.allclose(Y, X.astype(np.float64) @ Wd.T, rtol=1e-11, atol=1e-12)
+    rows = np.array([3, 17, 31])
+    assert np.array_equal(o5.linear(packed, scales, X, M, K, rows=rows), Y[:, rows])
+
+
+def test_linear_closed_forms(o5):
+    M, K, N = 16, 256, 3
+    X = workloads.make_activations(N, K, seed=1).numpy()
+    # all codes = 0b001 (1.0), scale 1: column sums of X
+    codes = np.full((M, K), 0b001, dtype=np.uint8)
+    ones = np.ones(M, dtype=np.float16)
+    Y = o5.linear(o5.pack(codes), ones, X, M, K)
+    assert np.allclose(Y, X.astype(np.float64).sum(axis=1)[:, None], rtol=1e-13)
+    # one non-zero 0.75 = 4 * 0.1875 per row at column pi(m): scale 0.1875, code 3, Y = 0.75 * X[pi(m)]
+    W = np.zeros((M, K), dtype=np.float16)
+    pi = (np.arange(M) * 37 + 5) % K
+    W[np.arange(M), pi] = 0.75
+    packed, scales = o5.quantize_pack(W)
+    assert np.all(scales.astype(np.float64) == 0.1875)
+    Y = o5.linear(packed, scales, X, M, K)
+    assert np.array_equal(Y, 0.75 * X.astype(np.float64)[:, pi])

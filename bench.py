@@ -341,6 +341,7 @@ def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_
     out["down_projection_22016x8192"] = _compare_sweep(pkg, torch, workloads, Mt, Kt, pk_t, sc_t, W16t, Ns)
     out["w5a16_e2m2"] = narrow_sweep(pkg, "fp5", torch, workloads, M, K, W16, Ns)
     out["w4a16_e2m1"] = narrow_sweep(pkg, "fp4", torch, workloads, M, K, W16, Ns)
+    out["w3a16_e2m0"] = narrow_sweep(pkg, "fp3", torch, workloads, M, K, W16, Ns)
     out["w6a16_group128"] = narrow_sweep(pkg, "fp6g", torch, workloads, M, K, W16, Ns)
     del W16, W16t, pk_t, sc_t
     torch.cuda.empty_cache()
@@ -350,7 +351,7 @@ def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_
 
 
 def narrow_sweep(pkg, prefix, torch, workloads, M, K, W16, Ns):
-    """Another weight format (prefix "fp5": e2m2, 5MK/8 bytes; "fp4": e2m1, MK/2 bytes; "fp6g": e3m2 with a scale
+    """Another weight format (prefix "fp5": e2m2, 5MK/8 bytes; "fp4": e2m1, MK/2 bytes; "fp3": e2m0, 3MK/8 bytes; "fp6g": e3m2 with a scale
     per row and 128 columns) on the same layer:
     its linear call at every N, rotating over 8 packed copies, plus its quantize_pack and unpack once."""
     dev = W16[0].device

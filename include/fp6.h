@@ -210,8 +210,26 @@ fp6_status fp4_linear(const void *packed, const void *scales_f16, const void *X_
                       int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * And for 3-bit weights (W3A16; Section 1 of the paper names 3-bit among the widths
+ * the scheme covers): FP3 is read as e2m0, code = s e1 e0, Eq. 1 with bias 1 and no
+ * mantissa bits, E = 0 holding only zero, no inf/NaN: magnitudes 0 1 2 4.  Quantizer:
+ * scale[m] = fp16_rne(max_k |W[m][k]| / 4), nearest magnitude, ties to the even code,
+ * saturating at 4.  fp3_packed_bytes(M, K) = 3*M*K/8 (tiles of 1536 bytes; the codes
+ * are pre-arranged bit by bit so that the kernel rebuilds four 4-bit words from three
+ * stored ones with a handful of AND/shift/OR).  Everything else as for the fp6_ calls.
+ */
+size_t fp3_packed_bytes(int64_t M, int64_t K);
+size_t fp3_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
+fp6_status fp3_quantize_pack(const void *W_f16, int64_t M, int64_t K, void *packed, void *scales_f16,
+                             void *stream);
+fp6_status fp3_unpack(const void *packed, const void *scales_f16, int64_t M, int64_t K, void *W_f16_out,
+                      void *stream);
+fp6_status fp3_linear(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                      int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Tuning hook for benchmarks: force the split-K factor used by fp6_linear, fp5_linear,
- * fp4_linear and fp16_linear (0 = choose automatically, the default).  Process-wide; affects the
+ * fp4_linear, fp3_linear and fp16_linear (0 = choose automatically, the default).  Process-wide; affects the
  * workspace size queries as well.  Values the shape cannot honour are clamped.
  */
 void fp6_tuning_set_split_k(int split_k);

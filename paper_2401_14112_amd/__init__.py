@@ -6,10 +6,15 @@ only - every step of the path runs in the library's HIP kernels.
 """
 from .binding import (  # noqa: F401
     fp4_linear,
+    fp3_linear,
     fp4_linear_workspace_bytes,
+    fp3_linear_workspace_bytes,
     fp4_packed_bytes,
+    fp3_packed_bytes,
     fp4_quantize_pack,
+    fp3_quantize_pack,
     fp4_unpack,
+    fp3_unpack,
     fp5_linear,
     fp5_linear_workspace_bytes,
     fp5_packed_bytes,

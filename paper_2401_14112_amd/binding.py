@@ -77,6 +77,16 @@ def load_library():
     L.fp4_unpack.argtypes = [vp, vp, i64, i64, vp, vp]
     L.fp4_linear.restype = ci
     L.fp4_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
+    L.fp3_packed_bytes.restype = sz
+    L.fp3_packed_bytes.argtypes = [i64, i64]
+    L.fp3_linear_workspace_bytes.restype = sz
+    L.fp3_linear_workspace_bytes.argtypes = [i64, i64, i64]
+    L.fp3_quantize_pack.restype = ci
+    L.fp3_quantize_pack.argtypes = [vp, i64, i64, vp, vp, vp]
+    L.fp3_unpack.restype = ci
+    L.fp3_unpack.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.fp3_linear.restype = ci
+    L.fp3_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
     L.fp6g_quantize_pack.restype = ci
     L.fp6g_quantize_pack.argtypes = [vp, i64, i64, i64, vp, vp, vp]
     L.fp6g_unpack.restype = ci
@@ -386,6 +396,30 @@ def fp4_unpack(packed: torch.Tensor, scales: torch.Tensor, M: int, K: int,
 def fp4_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
                out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     return _linear("fp4", packed, scales, X, M, K, out, workspace)
+
+
+def fp3_packed_bytes(M: int, K: int) -> int:
+    return int(load_library().fp3_packed_bytes(M, K))
+
+
+def fp3_linear_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load_library().fp3_linear_workspace_bytes(M, N, K))
+
+
+def fp3_quantize_pack(W: torch.Tensor, packed: Optional[torch.Tensor] = None,
+                      scales: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """fp16 [M][K] -> (packed uint8 [3MK/8], scales fp16 [M]), e2m0 codes."""
+    return _quantize_pack("fp3", W, packed, scales)
+
+
+def fp3_unpack(packed: torch.Tensor, scales: torch.Tensor, M: int, K: int,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    return _unpack("fp3", packed, scales, M, K, out)
+
+
+def fp3_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
+               out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    return _linear("fp3", packed, scales, X, M, K, out, workspace)
 
 
 def fp16_linear(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] = None,

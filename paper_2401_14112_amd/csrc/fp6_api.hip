@@ -507,6 +507,27 @@ fp6_status fp4_linear(const void *packed, const void *scales_f16, const void *X_
                                                stream);
 }
 
+size_t fp3_packed_bytes(int64_t M, int64_t K) { return shape_ok(M, K) ? (size_t)(M * K / 8 * 3) : 0; }
+
+size_t fp3_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) { return fp6_linear_workspace_bytes(M, N, K); }
+
+fp6_status fp3_quantize_pack(const void *W_f16, int64_t M, int64_t K, void *packed, void *scales_f16, void *stream)
+{
+    return quantize_pack_impl<E2M0Format>(W_f16, M, K, packed, scales_f16, stream);
+}
+
+fp6_status fp3_unpack(const void *packed, const void *scales_f16, int64_t M, int64_t K, void *W_f16_out, void *stream)
+{
+    return unpack_impl<PackedFp3Source>(packed, scales_f16, M, K, W_f16_out, stream);
+}
+
+fp6_status fp3_linear(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N,
+                      int64_t K, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return packed_linear_impl<PackedFp3Source>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
+                                               stream);
+}
+
 fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N, int64_t K,
                        void *workspace, size_t workspace_bytes, void *stream)
 {

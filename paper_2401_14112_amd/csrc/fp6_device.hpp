@@ -439,6 +439,64 @@ struct PackedFp4Source {
     }
 };
 
+// ---- 3-bit (e2m0) weights ------------------------------------------------------------------------
+// e2m0 (bias 1, no mantissa bits: 0 1 2 4) has no conversion instruction of its own, but code s e1 e0 has
+// the value of the e2m1 code s e1 e0 0, so a word of eight 4-bit fields "s e1 e0 0" goes through the FP4
+// conversion.  The layout (the paper's ahead-of-time bit-level pre-packing, Section 5.2, with a 3+1 split)
+// stores exactly such words: tile = 16 rows x 256 columns = 1536 bytes = a plane of 16 bytes per lane and
+// a plane of 8 bytes per lane; the lane's six words serve two groups of four runs, words 3g..3g+2 are runs
+// 4g..4g+2 in place with bit 0 of every field free, and those free bits carry run 4g+3: its bit b+1 of
+// field j is bit 4j of word 3g+b.  Unpack: one AND per in-place run, three AND/shift/OR for the fourth.
+struct PackedFp3Source {
+    typedef SimpleStream<PackedFp3Source> Stream;
+    static constexpr bool kPackedConfigs = true;  // which table of kernel configurations the host uses
+    struct Tile {
+        u32x4 p0;
+        u32x2 p1;
+    };
+    static constexpr bool kHasScale = true;
+    static constexpr bool kTallTile = true;
+    static constexpr int kLoads = 2;
+    static constexpr int kTileBytes3 = 1536;
+    static constexpr int kTileStride = kTileBytes3;
+    __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
+    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
+                                                        int64_t KT, int64_t /*K*/)
+    {
+        return make_rsrc(static_cast<const uint8_t *>(base) + (row_tile * KT + kt0) * kTileBytes3,
+                         (uint32_t)(kt1 - kt0) * kTileBytes3);
+    }
+    __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
+    __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
+    {
+        // the second plane holds 8 bytes per lane: its offset is the tile's base + 1024 + 8 * lane
+        const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+        t.p0 = issue_load_b128<0, true>(r, off);
+        t.p1 = issue_load_b64<1024>(r, off - 8 * lane);
+    }
+    __device__ static __forceinline__ void pin_tile(Tile &t)
+    {
+        pin(t.p0);
+        pin(t.p1);
+    }
+    // A fragments of runs 2G (even) and 2G+1 (odd): group g = G/2 uses words A0..A2 = words 3g..3g+2
+    template <int G>
+    __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
+    {
+        constexpr uint32_t kFields = 0xeeeeeeeeu, kFree = 0x11111111u;
+        const uint32_t a0 = G < 2 ? t.p0[0] : t.p0[3];
+        const uint32_t a1 = G < 2 ? t.p0[1] : t.p1[0];
+        const uint32_t a2 = G < 2 ? t.p0[2] : t.p1[1];
+        if ((G & 1) == 0) {
+            even_run = e2m1_word_to_fragment(a0 & kFields);
+            odd_run = e2m1_word_to_fragment(a1 & kFields);
+        } else {
+            even_run = e2m1_word_to_fragment(a2 & kFields);
+            odd_run = e2m1_word_to_fragment(((a0 & kFree) << 1) | ((a1 & kFree) << 2) | ((a2 & kFree) << 3));
+        }
+    }
+};
+
 struct PlainFp16Source {
     typedef SimpleStream<PlainFp16Source> Stream;
     static constexpr bool kPackedConfigs = false;  // which table of kernel configurations the host uses

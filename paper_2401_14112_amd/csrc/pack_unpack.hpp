@@ -177,6 +177,48 @@ struct E2M1Format {
     }
 };
 
+// e2m0: grid 0 | 1 | 2 | 4 (Eq. 1 with bias 1 and no mantissa bits; the E = 0 binade holds only 0).
+struct E2M0Format {
+    static constexpr float kMax = 4.0f;
+    static constexpr int kSignShift = 2;
+    static constexpr int kTileBytes = 1536;
+    __device__ static __forceinline__ uint32_t magnitude_code(float ratio)
+    {
+        uint32_t g;
+        if (ratio < 1.0f) {
+            g = (uint32_t)__builtin_rintf(ratio);  // 0 or 1, the midpoint 0.5 to the even code 0
+        } else {
+            uint32_t u = bit_cast<uint32_t>(ratio);
+            u += 0x003fffffu + ((u >> 23) & 1u);  // round the mantissa away entirely, half to the even exponent code
+            g = (u >> 23) - 126u;                 // exponent field - 127 + bias 1
+        }
+        return g < 3u ? g : 3u;
+    }
+    __device__ static __forceinline__ void store_tile(const uint32_t (&code)[8][8], uint8_t *tile, int lane)
+    {
+        uint32_t d[6];
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            uint32_t w[3] = {0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+#pragma unroll
+                for (int i = 0; i < 3; ++i)
+                    w[i] |= (code[4 * g + i][j] << 1) << (4 * j);  // in place: field "s e1 e0 ."
+                const uint32_t c = code[4 * g + 3][j];             // spread over the free bits
+#pragma unroll
+                for (int b = 0; b < 3; ++b)
+                    w[b] |= ((c >> b) & 1u) << (4 * j);
+            }
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+                d[3 * g + i] = w[i];
+        }
+        *(reinterpret_cast<u32x4 *>(tile) + lane) = (u32x4){d[0], d[1], d[2], d[3]};
+        *(reinterpret_cast<u32x2 *>(tile + 1024) + lane) = (u32x2){d[4], d[5]};
+    }
+};
+
 // ---- per-row scales: two launches ------------------------------------------------------------------
 // row_scale_kernel: one wave per row finds max |W| and writes scale = fp16(max / Fmt::kMax) (a plain read of
 // W at streaming rate).  quantize_tiles_kernel: one wave per 16 x 256 tile reads the tile once, rounds every

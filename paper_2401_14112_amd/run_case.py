@@ -1,4 +1,4 @@
-"""Runs one shape of fp6_linear (or fp6g_linear, fp5_linear, fp4_linear, fp16_linear) a few times on cuda:0 and prints the time per launch.
+"""Runs one shape of fp6_linear (or fp6g_linear, fp5_linear, fp4_linear, fp3_linear, fp16_linear) a few times on cuda:0 and prints the time per launch.
 
 Meant to be the program of a profiler run, e.g.
 
@@ -23,7 +23,7 @@ def main():
     ap.add_argument("--N", type=int, default=512)
     ap.add_argument("--reps", type=int, default=16)
     ap.add_argument("--buffers", type=int, default=8)
-    ap.add_argument("--which", choices=("fp6", "fp6g", "fp5", "fp4", "fp16"), default="fp6")
+    ap.add_argument("--which", choices=("fp6", "fp6g", "fp5", "fp4", "fp3", "fp16"), default="fp6")
     args = ap.parse_args()
 
     import torch

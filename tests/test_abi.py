@@ -20,7 +20,7 @@ def lib():
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "fp6.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(fp6g?_\w+|fp5_\w+|fp4_\w+|fp16_\w+)\s*\(", text)
+    names = re.findall(r"\b(fp6g?_\w+|fp5_\w+|fp4_\w+|fp3_\w+|fp16_\w+)\s*\(", text)
     return sorted(set(names))
 
 

@@ -1,0 +1,198 @@
+"""GPU parity tests of the 3-bit (e2m0) calls, through the C-ABI binding, against the CPU oracle.
+
+pack / unpack bit for bit; the GEMM within max_m |Y_gpu - Y_ref| <= 5e-3 * max_m |Y_ref| per output column.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL = 5e-3
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2401_14112_amd as p
+
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    p.load_library()
+    return p
+
+
+@pytest.fixture(scope="module")
+def o5():  # the 3-bit oracle (the fixture keeps the name used by the 5-bit tests)
+    from oracle import fp3_oracle
+    return fp3_oracle
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _check_linear(Y_gpu, Y_ref, what):
+    err = np.abs(Y_gpu.astype(np.float64) - Y_ref)
+    col_err = err.max(axis=1)
+    col_ref = np.abs(Y_ref).max(axis=1)
+    assert not (col_err > TOL * col_ref).any(), "%s: worst ratio %.3g" % (what, (col_err / np.maximum(col_ref, 1e-300)).max())
+    return (col_err / np.maximum(col_ref, 1e-300)).max()
+
+
+def _special_matrix(o5):
+    """Every code under several scales, hand ties, signed zeros, zero rows, subnormal scales, huge values."""
+    table = o5.decode_table()
+    M, K = 32, 512
+    W = np.zeros((M, K), dtype=np.float16)
+    for m, s in enumerate([2.0 ** -6, 0.01171875, 1.0, 3.0]):
+        W[m, :8] = (table * s).astype(np.float16)
+        W[m, 100:108] = (table[::-1] * s).astype(np.float16)
+    ties = [3, 1.5, 0.5, 3.1, 2.9, 3.5, 1.6, 1.4, 0.51, 0.49]
+    W[4, 0] = 4.0
+    W[4, 1:1 + len(ties)] = ties
+    W[5, 0] = -4.0
+    W[5, 1:1 + len(ties)] = [-t for t in ties]
+    W[6, 3] = -0.0
+    W[7, :] = np.float16(2.0 ** -24)                 # amax / 4 rounds to a zero scale
+    W[7, 5] = -np.float16(2.0 ** -24)
+    W[8, 0] = np.float16(4 * 2.0 ** -24)             # subnormal scale 2^-24
+    W[8, 1] = np.float16(2 * 2.0 ** -24)
+    W[8, 2] = -np.float16(1 * 2.0 ** -24)
+    W[9, 0] = np.float16(5 * 2.0 ** -24)             # scale rounds down (1.25 -> 1) so the row maximum saturates
+    W[9, 1] = np.float16(3 * 2.0 ** -24)
+    W[10, :] = np.float16(65504.0)
+    W[11, 7] = np.float16(-65504.0)
+    W[11, 8] = np.float16(6.1e-5)
+    rng = np.random.default_rng(5)
+    W[12:] = rng.standard_normal((M - 12, K)).astype(np.float16) * np.float16(0.02)
+    return W
+
+
+@pytest.mark.parametrize("M,K,seed", [(256, 512, 0), (16, 256, 1), (80, 1280, 2), (48, 2304, 3)])
+def test_quantize_pack_bit_exact(pkg, o5, M, K, seed):
+    _say("fp3 quantize_pack M=%d K=%d seed=%d" % (M, K, seed))
+    W = workloads.make_weights(M, K, seed)
+    packed, scales = pkg.fp3_quantize_pack(W.cuda())
+    torch.cuda.synchronize()
+    ref_packed, ref_scales = o5.quantize_pack(W.numpy())
+    assert packed.numel() == 3 * M * K // 8
+    assert np.array_equal(_np(scales).view(np.uint16), ref_scales.view(np.uint16))
+    assert np.array_equal(_np(packed), ref_packed)
+
+
+def test_quantize_pack_special_values(pkg, o5):
+    _say("fp3 quantize_pack special values")
+    W = _special_matrix(o5)
+    M, K = W.shape
+    packed, scales = pkg.fp3_quantize_pack(torch.from_numpy(W).cuda())
+    torch.cuda.synchronize()
+    ref_packed, ref_scales = o5.quantize_pack(W)
+    assert np.array_equal(_np(scales).view(np.uint16), ref_scales.view(np.uint16))
+    got_codes = o5.unpack_codes(_np(packed), M, K)
+    assert np.array_equal(got_codes, o5.unpack_codes(ref_packed, M, K))
+    assert np.array_equal(_np(packed), ref_packed)
+    assert np.array_equal(got_codes[0, :8], np.arange(8, dtype=np.uint8))
+    back = pkg.fp3_unpack(packed, scales, M, K)
+    torch.cuda.synchronize()
+    assert np.array_equal(_np(back).view(np.uint16), o5.unpack(ref_packed, ref_scales, M, K).view(np.uint16))
+
+
+def test_unpack_every_code_and_scales(pkg, o5):
+    """All 8 codes at every position of a lane's group under assorted scales: bit-exact, signed zeros kept."""
+    _say("fp3 unpack every code")
+    M, K = 16, 256
+    codes = np.zeros((M, K), dtype=np.uint8)
+    for m in range(M):
+        codes[m] = (np.arange(K) * (2 * m + 1) + m) % 8
+    scale_bits = np.array([0x3C00, 0x0000, 0x0001, 0x0002, 0x03FF, 0x0400, 0x1E00, 0x2001, 0x77FF, 0x68AB,
+                           0x0155, 0x2E66, 0x3555, 0x1001, 0x5BFF, 0x7BFF], dtype=np.uint16)
+    packed = o5.pack(codes)
+    scales = scale_bits.view(np.float16)
+    got = pkg.fp3_unpack(torch.from_numpy(packed).cuda(), torch.from_numpy(scales.copy()).cuda(), M, K)
+    torch.cuda.synchronize()
+    want = o5.unpack(packed, scales, M, K)
+    assert np.array_equal(_np(got).view(np.uint16), want.view(np.uint16))
+    assert np.isinf(want.astype(np.float32)).any()      # 4 * 65504 overflows: inf on both sides
+
+
+def _linear_case(pkg, o5, M, K, N, seed, split=0):
+    W = workloads.make_weights(M, K, seed).numpy()
+    X = workloads.make_activations(N, K, seed)
+    packed, scales = o5.quantize_pack(W)
+    pkg.fp6_tuning_set_split_k(split)
+    try:
+        Y = pkg.fp3_linear(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), X.cuda(), M, K)
+        torch.cuda.synchronize()
+    finally:
+        pkg.fp6_tuning_set_split_k(0)
+    return _np(Y), o5.linear(packed, scales, X.numpy(), M, K)
+
+
+@pytest.mark.parametrize("N", [1, 3, 8, 16, 17, 32, 33, 64, 70, 130, 257])
+def test_linear_token_counts(pkg, o5, N):
+    M, K = 80, 1280
+    _say("fp3 linear M=%d K=%d N=%d" % (M, K, N))
+    Y, Y_ref = _linear_case(pkg, o5, M, K, N, seed=N)
+    worst = _check_linear(Y, Y_ref, "N=%d" % N)
+    assert worst < 2e-3
+
+
+@pytest.mark.parametrize("split", [1, 2, 3, 5])
+@pytest.mark.parametrize("N", [5, 48, 100])
+def test_linear_split_k(pkg, o5, split, N):
+    M, K = 144, 2816
+    _say("fp3 linear split-K S=%d N=%d" % (split, N))
+    Y, Y_ref = _linear_case(pkg, o5, M, K, N, seed=split, split=split)
+    _check_linear(Y, Y_ref, "split=%d" % split)
+
+
+def test_linear_exact_cases_and_determinism(pkg, o5):
+    _say("fp3 linear exact cases")
+    M, K, N = 64, 1024, 9
+    X = workloads.make_activations(N, K, seed=1)
+    # one non-zero 0.75 = 4 * 0.1875 per row: the result is 0.75 * X[pi(m)], exact after one fp16 rounding
+    W = np.zeros((M, K), dtype=np.float16)
+    pi = (np.arange(M) * 37 + 5) % K
+    W[np.arange(M), pi] = 0.75
+    packed, scales = pkg.fp3_quantize_pack(torch.from_numpy(W).cuda())
+    Y = pkg.fp3_linear(packed, scales, X.cuda(), M, K)
+    torch.cuda.synchronize()
+    want = (0.75 * X.numpy().astype(np.float64)[:, pi]).astype(np.float16)
+    assert np.array_equal(_np(Y).view(np.uint16), want.view(np.uint16))
+    # reruns give identical bits
+    Wr = workloads.make_weights(M, K, 3).cuda()
+    packed, scales = pkg.fp3_quantize_pack(Wr)
+    outs = [pkg.fp3_linear(packed, scales, X.cuda(), M, K) for _ in range(4)]
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16))
+
+
+def test_full_size_layer_sampled(pkg, o5):
+    """The benchmark layer at its real size: packed stream and scales bit for bit on sampled row tiles, Y on their rows."""
+    name, M, K = workloads.FFN_65B
+    _say("fp3 full-size %s M=%d K=%d" % (name, M, K))
+    W = workloads.make_weights(M, K, seed=0, device="cuda")
+    packed, scales = pkg.fp3_quantize_pack(W)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    tiles = np.array(sorted(set([0, M // 16 - 1]) | set(int(t) for t in rng.choice(M // 16, size=14, replace=False))))
+    rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
+    ref_packed, ref_scales = o5.quantize_pack(_np(W[torch.from_numpy(rows).cuda()]))
+    tile_bytes = (K // 256) * 1536
+    got_packed = np.concatenate([_np(packed[t * tile_bytes:(t + 1) * tile_bytes]) for t in tiles])
+    assert np.array_equal(_np(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
+    assert np.array_equal(got_packed, ref_packed)
+    del W
+    for N in (1, 16, 32, 512):
+        _say("  fp3 linear N=%d" % N)
+        X = workloads.make_activations(N, K, seed=N, device="cuda")
+        Y = pkg.fp3_linear(packed, scales, X, M, K)
+        torch.cuda.synchronize()
+        Y_ref = o5.linear(ref_packed, ref_scales, _np(X), len(rows), K)
+        _check_linear(_np(Y)[:, rows], Y_ref, "%s N=%d" % (name, N))

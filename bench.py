@@ -200,13 +200,14 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "fp6_e3m2 weights x f16 activations, f32 accumulate",
+        "dtype": "f16",   # the matrix instructions take fp16 operands (weights de-quantized from e3m2) and add in fp32
         "data": "synthetic",
         "config": {
             "workload": "llama65b_ffn W[8192x22016] W6A16 linear, one step = decode sweep N in "
                         "{1,2,4,8,16,32}, launch j reads packed copy j%8 (1.08 GB rotation), HIP-graph replay",
             "M": M, "K": K, "N_sweep": sweep, "weight_buffers": N_BUFFERS,
             "layout_version": pkg.fp6_layout_version(),
+            "arithmetic": "e3m2 weights de-quantized to f16 in registers x f16 activations, f32 accumulate, one f16 rounding",
         },
         "tflops": round(step_flops / (ms_per_step * 1e-3) * 1e-12, 2),
         "roofline": {

@@ -153,12 +153,10 @@ TiledPlan plan_tiled(int64_t M, int64_t N, int64_t K, bool tall_tile_ok)
     const int rows = forced / 1024, tokens = forced % 1024;
     if (forced > 0)
         p.tile = rows == 256 ? (tokens == 128 ? kTile256x128 : kTile256x64) : (tokens == 128 ? kTile128x128 : kTile128x64);
-    else if (N <= 64)
-        p.tile = kTile128x64;
-    else if (N <= 128)
-        p.tile = kTile128x128;
+    else if (N <= 128 && (M + 255) / 256 < 64)
+        p.tile = kTile128x64;  // few row blocks: small blocks and little split-K (measured on 8192-row layers)
     else
-        p.tile = kTile256x128;
+        p.tile = kTile256x128;  // the shape that moves the fewest bytes per MFMA
     if (p.tile.rows() == 256 && !tall_tile_ok)  // this weight source does not fit four row tiles per wave in registers
         p.tile = p.tile.tokens() == 128 ? kTile128x128 : kTile128x64;
     p.row_blocks = (int)((M + p.tile.rows() - 1) / p.tile.rows());

@@ -27,6 +27,7 @@
 // re-assembled values with 27 VALU instructions per 16 weights; the conversion
 // instruction made the kernels 4-7 % faster at every N and needs no layout tricks.)
 #pragma once
+#include <utility>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -545,6 +546,20 @@ struct PlainFp16Source {
         odd_run = bit_cast<half8_t>(t.v[2 * G + 1]);
     }
 };
+
+constexpr int stream_gcd(int a, int b) { return b == 0 ? a : stream_gcd(b, a % b); }
+
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a compile-time constant
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 // ---- last step of the linear kernels ----------------------------------------------------------
 // What happens between a finished fp32 sum and the stored fp16: the per-row scale (sources that

@@ -18,13 +18,9 @@
 // result does not depend on arrival order), scales, rounds and stores Y.  The counter
 // is reset by that wave, so a zeroed workspace stays reusable.
 #pragma once
-#include <utility>
-
 #include "fp6_device.hpp"
 
 namespace fp6 {
-
-constexpr int stream_gcd(int a, int b) { return b == 0 ? a : stream_gcd(b, a % b); }
 
 // Activation copies requested in the DEPTH-1 iterations before the iteration at stage position g, when
 // each of the first XSPREAD iterations of a stage requests XPART of them.
@@ -34,18 +30,6 @@ constexpr int stream_copies_between(int g, int G, int DEPTH, int XSPREAD, int XP
     for (int d = 1; d < DEPTH; ++d)
         c += ((g - d + DEPTH * G) % G) < XSPREAD ? XPART : 0;
     return c;
-}
-
-template <class F, int... I>
-__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a compile-time constant
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
 template <class Src, int NT, int WAVES, int DEPTH, int G, int XSPREAD>

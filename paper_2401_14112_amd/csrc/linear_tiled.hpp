@@ -6,16 +6,11 @@
 // (16*NT*WN) tokens.  Per 256-column k-tile a wave fetches its RT packed weight tiles straight into
 // registers, de-quantizes four runs of 32 columns with one conversion and feeds every run to NT MFMAs (the
 // conversion is amortised over 4*NT matrix instructions); every activation fragment read from LDS feeds RT
-// MFMAs.  The activation tile (all tokens of the block x 256 columns) is shared by the block: it is
-// copied global -> LDS without passing through registers, already in B-fragment order (the 64 lanes
-// of one copy instruction fetch the 64 pieces that the 64 lanes of one MFMA will read), and is
-// double-buffered.
-//
-// Pipeline (one k-tile of look-ahead, enough because a k-tile is RT*NT*8 MFMAs of work per wave and
-// two waves share a SIMD): at the top of iteration t the wave waits for everything it requested for
-// tile t, one barrier makes the whole activation tile visible (and guarantees that the other LDS
-// buffer is no longer being read), then the requests for tile t+1 are issued - activation copies
-// into the other LDS buffer, weights into the other register buffer - and tile t is computed.
+// MFMAs.  The activations (all tokens of the block) are shared by the block: they are copied
+// global -> LDS without passing through registers, already in B-fragment order (the 64 lanes of one
+// copy instruction fetch the 64 pieces that the 64 lanes of one MFMA will read), half a k-tile (128
+// columns) at a time into a ring of four buffers, requested three half tiles ahead and made visible one
+// half tile ahead; weights are double-buffered in registers, one k-tile ahead.
 //
 // Split-K and the epilogue are those of the streaming kernel (linear_stream.hpp).
 #pragma once
@@ -31,13 +26,17 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
 {
     constexpr int WAVES = WM * WN;
     constexpr int BNT = WN * NT;             // 16-token tiles of the block
-    constexpr int XCHUNKS = BNT * 512;       // 16-byte pieces of one activation tile
-    constexpr int XBYTES = XCHUNKS * 16;
-    constexpr int COPIES = BNT * 8;          // copy instructions per activation tile (one per token tile and run)
-    static_assert(COPIES % WAVES == 0, "activation copies must split evenly over the waves");
-    constexpr int XPER = COPIES / WAVES;
+    // Activations are staged half a k-tile (128 columns = runs 0..3 or 4..7) at a time in a ring of XS
+    // buffers; weights are double-buffered in registers (whole k-tiles).
+    constexpr int XS = 4;
+    constexpr int XHPIECES = BNT * 256;      // 16-byte pieces of one half tile of activations
+    constexpr int XHBYTES = XHPIECES * 16;
+    constexpr int HCOPIES = BNT * 4;         // copy instructions per half tile (one per token tile and run)
+    static_assert(HCOPIES % WAVES == 0, "activation copies must split evenly over the waves");
+    constexpr int XPERH = HCOPIES / WAVES;
+    constexpr int WLOADS = RT * Src::kLoads; // weight loads of one wave per k-tile
 
-    extern __shared__ u32x4 xs_dyn[];  // [2][XCHUNKS]
+    extern __shared__ u32x4 xs_dyn[];  // [XS][XHPIECES]
     __shared__ int s_is_last;
 
     const int tid = threadIdx.x;
@@ -76,27 +75,27 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     }
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
-    // Activation copies: copy j = wave + WAVES*i of a tile serves token tile nt = j/8 and run f = j%8;
-    // lane p of the copy fetches X[block_col0 + 16*nt + n][k0 + k_offset(f, q) ..+8] for the (n, q) that
-    // piece p of the 1 KB holds (see x_source_of_piece), and its 16 bytes land at piece 64*j + p.
+    // Activation copies: copy j = wave + WAVES*i of half tile h serves token tile nt = j/4 and run
+    // f = j%4 + 4*(h%2) of k-tile h/2; lane p of the copy fetches
+    // X[block_col0 + 16*nt + n][k0 + k_offset(f, q) ..+8] for the (n, q) that piece p of the 1 KB holds (see
+    // x_source_of_piece), and its 16 bytes land at piece 64*j + p of the ring buffer.  Half tiles past the
+    // end of the slice and token columns >= N get an offset outside the buffer: zeros land in LDS.
     int xq, xn;
     x_source_of_piece(lane, xn, xq);
     const int b_piece = x_piece_of_lane(lane);
     // LDS byte address of the activation buffers (the low 32 bits of a shared-memory pointer)
     const uint32_t xs_lds = (uint32_t)reinterpret_cast<uintptr_t>(xs_dyn);
-    // copies [i0, i1) of the XPER copies this wave contributes to the activation tile of k-tile t
-    auto x_issue = [&](int t, int buf, int i0, int i1) {
+    auto x_issue = [&](int h, int buf) {
+        const int t = h >> 1;
 #pragma unroll
-        for (int i = 0; i < XPER; ++i) {
-            if (i < i0 || i >= i1)
-                continue;
+        for (int i = 0; i < XPERH; ++i) {
             const int j = wave + WAVES * i;
-            const int nt = j >> 3, f = j & 7;
+            const int nt = j >> 2, f = (j & 3) + 4 * (h & 1);
             const int col = block_col0 + nt * 16 + xn;
             const int off = (t < n_valid && col < N)
                                 ? (col * K + (kt0 + t) * kTileK + Src::k_offset(f, xq)) * 2
                                 : kOutOfRange;
-            const uint32_t lds_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(xs_lds + buf * XBYTES + j * 1024));
+            const uint32_t lds_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(xs_lds + buf * XHBYTES + j * 1024));
             issue_load_to_lds_b128<0>(x_rsrc, off, lds_base);
         }
     };
@@ -108,103 +107,112 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
         for (int nt = 0; nt < NT; ++nt)
             acc[r][nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
-    // One k-tile = 8 runs x NT token tiles = 8*NT steps of RT MFMAs.  B fragments travel through a small
-    // ring of registers: the LDS read of step s+LOOK is issued when step s is consumed.  The A fragments of
-    // runs 2g+2, 2g+3 are produced (conversion + register moves, VALU work) while the MFMAs of runs 2g, 2g+1
-    // execute.  The sched_group_barrier sequence fixes the instruction order inside each group of two runs
-    // to "1 LDS read, RT MFMAs, a few VALU" per step: a wave cannot issue anything else while one of its
-    // MFMAs is being issued, so the VALU work is laid out in small pieces that the other waves of the SIMD
-    // can cover with their own MFMAs, instead of bursts in which the matrix pipe idles.
+    // One half tile = 4 runs x NT token tiles = 4*NT steps of RT MFMAs, in two groups of two runs.  B
+    // fragments travel through a small ring of registers: the LDS read of step s+LOOK is issued when step s
+    // is consumed, and the ring runs on across half tiles (the next half tile is already visible, see
+    // below), so the matrix pipe does not drain at a boundary.  The A fragments of the next group are
+    // produced (conversion + register moves, VALU work) while the MFMAs of the current group execute.  The
+    // sched_group_barrier sequence fixes the instruction order inside a group to "1 LDS read, RT MFMAs, a few
+    // VALU" per step: a wave cannot issue anything else while one of its MFMAs is being issued, so the VALU
+    // work is laid out in small pieces that the other waves of the SIMD can cover with their own MFMAs.
     constexpr int LOOK = 4;
-    constexpr int STEPS = 8 * NT;
+    constexpr int STEPS = 4 * NT;
 #ifndef FP6_TILED_VALU
 #define FP6_TILED_VALU 2  // VALU instructions the scheduler may place after the MFMAs of a step
 #endif
-#ifndef FP6_TILED_PARTS
-#define FP6_TILED_PARTS 4
-#endif
     constexpr int VALU_PER_STEP = FP6_TILED_VALU;
+    half8_t a[2][2][RT];  // [group parity][even/odd run][row tile]
+    half8_t bq[LOOK];
     auto ldb = [&](const u32x4 *xbuf, int st) {
-        return bit_cast<half8_t>(xbuf[((wn * NT + (st % NT)) * 8 + st / NT) * 64 + b_piece]);
+        return bit_cast<half8_t>(xbuf[((wn * NT + (st % NT)) * 4 + st / NT) * 64 + b_piece]);
     };
-    // `issue_part(g)`, g = 0..3, is called between the four groups: the requests for the next k-tile are
-    // spread over the computation instead of being issued in one burst while the matrix pipe idles.
-    auto compute = [&](const typename Src::Tile (&t)[RT], const u32x4 *xbuf, auto &&issue_part) {
-        half8_t a[2][2][RT];  // [group parity][even/odd run][row tile]
-        half8_t bq[LOOK];
-#pragma unroll
-        for (int i = 0; i < LOOK; ++i)
-            bq[i] = ldb(xbuf, i);
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-            Src::template fragments<0>(t[r], a[0][0][r], a[0][1][r]);
+    // HP: which half of the k-tile t; xbuf: its activations; xnext: those of the following half tile
+    auto compute_half = [&](auto hp_c, const typename Src::Tile (&t)[RT], const u32x4 *xbuf, const u32x4 *xnext) {
+        constexpr int HP = decltype(hp_c)::value;
         __builtin_amdgcn_sched_barrier(0);
-#define FP6_TILED_GROUP(G, NEXT)                                                                  \
-    if (G < 3) {                                                                                  \
+#define FP6_TILED_GROUP(GH)                                                                       \
+    if (HP == 0 || GH == 0) {                                                                     \
         _Pragma("unroll") for (int r = 0; r < RT; ++r)                                            \
-            Src::template fragments<NEXT>(t[r], a[(G + 1) & 1][0][r], a[(G + 1) & 1][1][r]);      \
+            Src::template fragments<2 * HP + GH + 1 <= 3 ? 2 * HP + GH + 1 : 3>(t[r], a[GH ^ 1][0][r], a[GH ^ 1][1][r]); \
     }                                                                                             \
     _Pragma("unroll") for (int i = 0; i < 2 * NT; ++i) {                                          \
-        const int st = 2 * G * NT + i;                                                            \
+        const int st = 2 * GH * NT + i;                                                           \
         const half8_t b = bq[st % LOOK];                                                          \
-        if (st + LOOK < STEPS)                                                                    \
-            bq[st % LOOK] = ldb(xbuf, st + LOOK);                                                 \
+        bq[st % LOOK] = st + LOOK < STEPS ? ldb(xbuf, st + LOOK) : ldb(xnext, st + LOOK - STEPS); \
         _Pragma("unroll") for (int r = 0; r < RT; ++r)                                            \
-            acc[r][st % NT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[G & 1][i / NT][r], b, acc[r][st % NT], 0, 0, 0); \
+            acc[r][st % NT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[GH][i / NT][r], b, acc[r][st % NT], 0, 0, 0); \
     }                                                                                             \
     _Pragma("unroll") for (int i = 0; i < 2 * NT; ++i) {                                          \
-        if (2 * G * NT + i + LOOK < STEPS)                                                        \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                        \
         __builtin_amdgcn_sched_group_barrier(0x008, RT, 0);                                       \
         __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_STEP, 0);                            \
     }                                                                                             \
-    __builtin_amdgcn_sched_barrier(0);                                                            \
-    issue_part(G);                                                                                \
     __builtin_amdgcn_sched_barrier(0);
-        FP6_TILED_GROUP(0, 1)
-        FP6_TILED_GROUP(1, 2)
-        FP6_TILED_GROUP(2, 3)
-        FP6_TILED_GROUP(3, 3)
+        FP6_TILED_GROUP(0)
+        FP6_TILED_GROUP(1)
 #undef FP6_TILED_GROUP
     };
 
+    // ---- software pipeline.  Half step h (k-tile t = h/2) computes half tile h.  At its top the wave waits
+    // for the activations of half tile h+1 (its own copies of them, requested at half step h-2) and, when h
+    // is even, for the weights of k-tile t (requested at half step h-2, before those copies); one barrier
+    // then makes half tile h+1 visible to the whole block - half tile h became visible one step earlier,
+    // which is what lets the B-fragment ring run across the boundary - and guarantees that half tile h-1 is
+    // no longer being read, so its buffer takes the copies of half tile h+3, requested next, after the
+    // weights of k-tile t+1 when h is even.  Loads complete in order, so "at most n outstanding" with n = the
+    // loads requested after the ones needed (the copies of half step h-1, plus its weight loads when h is
+    // odd) means they have arrived.
     typename Src::Tile w[2][RT];
-    auto w_issue = [&](typename Src::Tile (&dst)[RT], int t, int r0, int r1) {
+    auto w_issue = [&](typename Src::Tile (&dst)[RT], int t) {
 #pragma unroll
         for (int r = 0; r < RT; ++r)
-            if (r >= r0 && r < r1)
-                w_stream[r].issue(dst[r], t);
+            w_stream[r].issue(dst[r], t);
     };
-    auto arrive = [&](typename Src::Tile (&dst)[RT]) {
-        wait_loads<0>();
+    auto pin_tiles = [&](typename Src::Tile (&dst)[RT]) {
 #pragma unroll
         for (int r = 0; r < RT; ++r)
             Src::pin_tile(dst[r]);
     };
-    // part g of the requests for k-tile t: a quarter of this wave's activation copies and (RT/4 or 1) weight tiles
-    auto issue_part = [&](typename Src::Tile (&dst)[RT], int t, int buf, int g) {
-        constexpr int PARTS = FP6_TILED_PARTS;  // the activation copies are spread over the first PARTS groups
-        if (g < PARTS)
-            x_issue(t, buf, g * XPER / PARTS, (g + 1) * XPER / PARTS);
-        if (RT >= 4)
-            w_issue(dst, t, g * RT / 4, (g + 1) * RT / 4);
-        else if (g < RT)
-            w_issue(dst, t, g, g + 1);
-    };
-
-    x_issue(0, 0, 0, XPER);
-    w_issue(w[0], 0, 0, RT);
-    // two tiles per trip so that the register / LDS buffer index is static; tiles past the slice are zeros
-    for (int t = 0; t < n_valid; t += 2) {
-        arrive(w[0]);
-        __syncthreads();
-        compute(w[0], xs_dyn, [&](int g) { issue_part(w[1], t + 1, 1, g); });
-
-        arrive(w[1]);
-        __syncthreads();
-        compute(w[1], xs_dyn + XCHUNKS, [&](int g) { issue_part(w[0], t + 2, 0, g); });
+    w_issue(w[0], 0);
+#pragma unroll
+    for (int i = 0; i < XS - 1; ++i)
+        x_issue(i, i);
+    // half tile 0 has to be visible before the ring is primed
+    wait_loads<XPERH>();
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < LOOK; ++i)
+        bq[i] = ldb(xs_dyn, i);
+    const int n_half = 2 * n_valid;
+    for (int h0 = 0; h0 < n_half; h0 += XS) {
+        static_for<XS>([&](auto uc) {
+            constexpr int u = decltype(uc)::value;
+            constexpr int hp = u & 1, xb = u % XS, ws = (u / 2) % 2;
+            constexpr int n_after = hp == 1 ? XPERH + WLOADS : XPERH;
+            const int h = h0 + u;
+            if (h < n_half) {  // the same for every wave of the block
+                wait_loads<n_after>();
+                if (hp == 0)
+                    pin_tiles(w[ws]);
+                __syncthreads();
+                if (hp == 0)
+                    w_issue(w[ws ^ 1], (h >> 1) + 1);
+                x_issue(h + XS - 1, (xb + XS - 1) % XS);
+                if (hp == 0) {
+#pragma unroll
+                    for (int r = 0; r < RT; ++r)
+                        Src::template fragments<0>(w[ws][r], a[0][0][r], a[0][1][r]);
+                }
+                compute_half(std::integral_constant<int, hp>{}, w[ws], xs_dyn + xb * XHPIECES,
+                             xs_dyn + ((xb + 1) % XS) * XHPIECES);
+            }
+        });
     }
-    arrive(w[0]);  // the last look-ahead requests (out of range: zeros) must land before the block ends
+    // the look-ahead requests (out of range: zeros) must land before the registers are reused and before
+    // the block gives up its LDS
+    wait_loads<0>();
+    pin_tiles(w[0]);
+    pin_tiles(w[1]);
 
     // ---- epilogue.  Lane L holds, per (row tile, token tile), rows 4*(L/16)+i of token column L%16.
     const int n_in_tile = lane & 15;

@@ -18,7 +18,9 @@
  *     channels, K input features); activations B = [K][N] and outputs C = [M][N]
  *     are column-major, i.e. X is stored [N][K] (K contiguous) and Y is stored
  *     [N][M] (M contiguous) - the natural layout of a linear layer over N tokens.
- *   - Supported shapes: M a multiple of 16, K a multiple of 256, N >= 1.
+ *   - Supported shapes: M a multiple of 16, K a multiple of 256, 1 <= N < 2^31
+ *     (M, K < 2^31; token counts whose activations exceed 2 GiB are processed as
+ *     several launches on the same stream).
  *   - Errors are detected on the host before anything is launched and reported
  *     as a status code; nothing is enqueued when a call fails.
  *   - W must be finite (the method has no inf/NaN code); this is not checked.

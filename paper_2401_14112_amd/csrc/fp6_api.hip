@@ -201,19 +201,37 @@ fp6_status launch_tiled_cfg(const TiledPlan &p, const void *weights, const void 
     return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
 }
 
+// The tiled kernel addresses the activations with 32-bit byte offsets, so one launch takes at most this many
+// tokens (a multiple of the widest block); longer inputs are processed in chunks on the same stream.
+int64_t tiled_chunk_tokens(int64_t K)
+{
+    const int64_t fit = ((1ll << 31) - 1) / (2 * K);
+    return fit >= 128 ? fit / 128 * 128 : fit;  // K < 2^24 leaves at least one full block
+}
+
+// Workspace of the tiled path: the largest over the chunks a call is cut into (the last, shorter chunk may
+// use more k slices than the full ones).
+size_t tiled_workspace_bytes(int64_t M, int64_t N, int64_t K, bool tall_tile_ok)
+{
+    const int64_t chunk = tiled_chunk_tokens(K);
+    if (chunk <= 0)
+        return 0;
+    if (N <= chunk)
+        return plan_tiled(M, N, K, tall_tile_ok).total_bytes();
+    size_t bytes = plan_tiled(M, chunk, K, tall_tile_ok).total_bytes();
+    const int64_t last = N % chunk;
+    if (last > 0) {
+        const size_t b = plan_tiled(M, last, K, tall_tile_ok).total_bytes();
+        bytes = b > bytes ? b : bytes;
+    }
+    return bytes;
+}
+
 template <class Src>
-fp6_status launch_tiled(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
-                        int64_t K, void *workspace, size_t workspace_bytes, const Epilogue &epi, hipStream_t stream)
+fp6_status launch_tiled_chunk(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
+                              int64_t K, void *workspace, const Epilogue &epi, hipStream_t stream)
 {
     const TiledPlan p = plan_tiled(M, N, K, Src::kTallTile);
-    if ((uint64_t)N * (uint64_t)K * 2u >= (1ull << 31))
-        return FP6_ERR_SHAPE;  // activations are addressed with 32-bit buffer offsets
-    if (p.total_bytes() > 0) {
-        if (!workspace || workspace_bytes < p.total_bytes())
-            return FP6_ERR_WORKSPACE;
-        if (!aligned16(workspace))
-            return FP6_ERR_ALIGN;
-    }
     int *counters = static_cast<int *>(workspace);
     float4_t *partials =
         p.total_bytes() ? reinterpret_cast<float4_t *>(static_cast<uint8_t *>(workspace) + p.counter_bytes) : nullptr;
@@ -230,6 +248,36 @@ fp6_status launch_tiled(const void *weights, const void *scales, const void *X, 
     }
 #undef FP6_TILED_CASE
     return FP6_ERR_SHAPE;  // not reached: plan_tiled only picks the shapes above
+}
+
+template <class Src>
+fp6_status launch_tiled(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
+                        int64_t K, void *workspace, size_t workspace_bytes, const Epilogue &epi, hipStream_t stream)
+{
+    const int64_t chunk = tiled_chunk_tokens(K);
+    if (chunk <= 0)
+        return FP6_ERR_SHAPE;  // one token's activations exceed a 32-bit byte offset
+    const size_t need = tiled_workspace_bytes(M, N, K, Src::kTallTile);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need)
+            return FP6_ERR_WORKSPACE;
+        if (!aligned16(workspace))
+            return FP6_ERR_ALIGN;
+    }
+    const int64_t Mout = epi.gated ? M / 2 : M;
+    for (int64_t n0 = 0; n0 < N; n0 += chunk) {
+        // a short last chunk still goes through this kernel (it handles any token count)
+        const int64_t n = N - n0 < chunk ? N - n0 : chunk;
+        Epilogue e = epi;
+        if (e.residual)
+            e.residual += n0 * Mout;
+        const fp6_status st = launch_tiled_chunk<Src>(weights, scales, static_cast<const half_t *>(X) + n0 * K,
+                                                      static_cast<half_t *>(Y) + n0 * Mout, M, n, K, workspace, e,
+                                                      stream);
+        if (st != FP6_OK)
+            return st;
+    }
+    return FP6_OK;
 }
 
 template <class Src, int C>
@@ -371,7 +419,7 @@ size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
     if (!shape_ok(M, K) || N <= 0)
         return 0;
     return N <= kStreamMaxN ? plan_stream(M, N, K, true).total_bytes()
-                            : plan_tiled(M, N, K, PackedFp6Source::kTallTile).total_bytes();
+                            : tiled_workspace_bytes(M, N, K, PackedFp6Source::kTallTile);
 }
 
 size_t fp16_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
@@ -379,7 +427,7 @@ size_t fp16_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
     if (!shape_ok(M, K) || N <= 0)
         return 0;
     return N <= kStreamMaxN ? plan_stream(M, N, K, false).total_bytes()
-                            : plan_tiled(M, N, K, PlainFp16Source::kTallTile).total_bytes();
+                            : tiled_workspace_bytes(M, N, K, PlainFp16Source::kTallTile);
 }
 
 void fp6_tuning_set_split_k(int split_k) { g_forced_split.store(split_k < 0 ? 0 : split_k); }

@@ -441,3 +441,27 @@ def test_decoder_weight_stream_graph(pkg, oracle, N):
         torch.cuda.synchronize()
         for l, e in zip(layers, eager):
             assert torch.equal(l[6].view(torch.int16), e.view(torch.int16)), "replay %d, %s" % (replay, l[0])
+
+
+def test_linear_more_tokens_than_one_launch_can_address(pkg, oracle):
+    """Activations larger than 2 GiB (the kernels address them with 32-bit byte offsets): the call is cut into
+    launches of at most floor((2^31 - 1) / 2K) tokens rounded down to 128.  Sampled tokens around the cut,
+    at both ends and in the short last piece against the oracle; every output written."""
+    M, K = 32, 256
+    chunk = ((2 ** 31 - 1) // (2 * K)) // 128 * 128
+    N = chunk + 300
+    _say("linear M=%d K=%d N=%d (two launches: %d + 300 tokens)" % (M, K, N, chunk))
+    W = workloads.make_weights(M, K, seed=9)
+    packed, scales = oracle.quantize_pack(W.numpy())
+    X = workloads.make_activations(N, K, seed=77, device="cuda")
+    assert X.numel() * 2 > 2 ** 31
+    Y = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    pkg.fp6_linear(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), X, M, K, out=Y)
+    torch.cuda.synchronize()
+    assert not torch.isnan(Y).any()
+    rng = np.random.default_rng(4)
+    tokens = np.unique(np.concatenate([np.arange(0, 40), np.arange(chunk - 130, chunk + 130), np.arange(N - 40, N),
+                                       rng.integers(0, N, size=64)]))
+    idx = torch.from_numpy(tokens).cuda()
+    Y_ref = oracle.linear(packed, scales, _np16(X[idx]), M, K)
+    _check_linear(_np16(Y[idx]), Y_ref, "long input")

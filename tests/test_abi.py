@@ -56,6 +56,10 @@ def test_size_queries(lib):
     assert lib.fp4_packed_bytes(16, 256) == 2048 and lib.fp4_packed_bytes(16, 128) == 0
     assert lib.fp6_packed_bytes(15, 256) == 0 and lib.fp6_packed_bytes(16, 128) == 0
     assert lib.fp6_packed_bytes(0, 256) == 0 and lib.fp6_packed_bytes(-16, 256) == 0
+    assert lib.fp3_packed_bytes(16, 256) == 1536 and lib.fp3_packed_bytes(8192, 22016) == 67633152
+    # a token count whose activations exceed 2 GiB is cut into several launches: the query still answers
+    assert lib.fp6_linear_workspace_bytes(32, 4194476, 256) % 16 == 0
+    assert lib.fp6_linear_workspace_bytes(8192, 200000, 22016) <= 256 * 1024 * 1024
     for (M, N, K) in [(8192, 1, 22016), (8192, 32, 22016), (256, 8, 512), (22016, 16, 8192)]:
         b = lib.fp6_linear_workspace_bytes(M, N, K)
         assert b % 16 == 0
@@ -78,6 +82,12 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.fp6_linear(p, p, p, p, 16, 0, 256, null, 0, null) == SHAPE
     assert lib.fp6_linear(p, p, p, p, 16, 1, 255, null, 0, null) == SHAPE
     assert lib.fp6_linear(p, p, odd, p, 16, 1, 256, null, 0, null) == ALIGN
+    assert lib.fp6_linear_fused(p, p, p, null, 16, 1, 256, null, null, 0, null, 0, null) == NULL
+    assert lib.fp6_linear_fused(p, p, p, p, 16, 1, 256, odd, null, 0, null, 0, null) == ALIGN
+    assert lib.fp6_linear_fused(p, p, p, p, 16, 1, 256, null, odd, 1, null, 0, null) == ALIGN
+    assert lib.fp6_linear_fused(p, p, p, p, 16, 0, 256, null, null, 1, null, 0, null) == SHAPE
+    assert lib.fp3_linear(p, p, p, p, 16, 1, 128, null, 0, null) == SHAPE
+    assert lib.fp6g_linear(p, p, p, p, 16, 1, 256, 64, null, 0, null) == SHAPE       # only groups of 128 columns
     assert lib.fp16_linear(null, p, p, 16, 1, 256, null, 0, null) == NULL
     assert lib.fp16_linear(p, p, p, 24, 1, 256, null, 0, null) == SHAPE
     # a shape that needs split-K partial sums refuses to run without a workspace

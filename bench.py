@@ -348,6 +348,7 @@ def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_
     torch.cuda.empty_cache()
     out["decoder_set_70b"] = decoder_set_measurements(pkg, torch, np, workloads, dev)
     out["fused_feed_forward_70b"] = fused_block_measurements(pkg, torch, workloads, dev)
+    out["model_blocks_vs_fp16"] = model_block_measurements(pkg, torch, workloads, dev)
     return out
 
 
@@ -510,6 +511,50 @@ def fused_block_measurements(pkg, torch, workloads, dev, copies=4):
         out[str(n)] = {"fused_us_per_block": round(us_f, 2), "separate_us_per_block": round(us_s, 2),
                        "speedup": round(us_s / us_f, 3),
                        "fused_hbm_frac": round(alg / us_f * 1e-3 / HBM_PEAK_GBPS, 4)}
+    return out
+
+
+def model_block_measurements(pkg, torch, workloads, dev):
+    """The experiment of the paper's Section 7.1 re-run inside this library: the four linear layers of one
+    decoder block of LLaMA-7b/13b/33b/65b and OPT-30b/66b/175b (synthetic weights of those shapes) at batch 8, 16
+    and 32, fp6_linear against the library's own fp16_linear and (context) the vendor fp16 GEMM.  Every layer is
+    timed from a graph that rotates over enough copies of its weights to exceed the 256 MB last-level cache;
+    reported per model: microseconds per block (sum over the four layers) and the speed-up over fp16."""
+    out = {}
+    for name, hidden, inner, gated in workloads.MODEL_DIMS:
+        per_n = {str(n): {"fp6_us": 0.0, "fp16_us": 0.0, "vendor_fp16_us": 0.0} for n in (8, 16, 32)}
+        for lname, M, K in workloads.model_layers(hidden, inner, gated):
+            P = pkg.fp6_packed_bytes(M, K)
+            copies = max(2, min(64, -(-600 * 1024 * 1024 // P)))
+            copies16 = max(2, min(copies, -(-600 * 1024 * 1024 // (2 * M * K))))
+            packed, W16 = [], []
+            for c in range(copies):
+                W = workloads.make_weights(M, K, seed=3000 + c, device=dev)
+                packed.append(pkg.fp6_quantize_pack(W))
+                if c < copies16:
+                    W16.append(W)
+                del W
+            for n in (8, 16, 32):
+                X = workloads.make_activations(n, K, seed=n, device=dev)
+                Y = torch.empty((n, M), dtype=torch.float16, device=dev)
+                ws6 = torch.zeros(max(pkg.fp6_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
+                ws16 = torch.zeros(max(pkg.fp16_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
+                r = per_n[str(n)]
+                r["fp6_us"] += _time_graph(torch, lambda i: pkg.fp6_linear(packed[i][0], packed[i][1], X, M, K, out=Y, workspace=ws6), copies, reps=5)
+                r["fp16_us"] += _time_graph(torch, lambda i: pkg.fp16_linear(W16[i], X, out=Y, workspace=ws16), copies16, reps=5)
+                try:
+                    r["vendor_fp16_us"] += _time_graph(torch, lambda i: torch.matmul(X, W16[i].t(), out=Y), copies16, reps=5)
+                except Exception:      # context only
+                    r["vendor_fp16_us"] = float("nan")
+            del packed, W16
+        block_bytes = sum(pkg.fp6_packed_bytes(M, K) for _, M, K in workloads.model_layers(hidden, inner, gated))
+        for n, r in per_n.items():
+            r["speedup_vs_own_fp16"] = round(r["fp16_us"] / r["fp6_us"], 3)
+            r["speedup_vs_vendor_fp16"] = round(r["vendor_fp16_us"] / r["fp6_us"], 3)
+            r["weight_GBps"] = round(block_bytes / r["fp6_us"] * 1e-3, 1)
+            for k in ("fp6_us", "fp16_us", "vendor_fp16_us"):
+                r[k] = round(r[k], 2)
+        out[name] = {"packed_bytes_per_block": block_bytes, "batch": per_n}
     return out
 
 

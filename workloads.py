@@ -21,6 +21,27 @@ SET_70B = [
     ("70b_gate_up", 28672, 8192),
     ("70b_down", 8192, 28672),
 ]
+# Decoder-block linear layers of the model families whose shapes the paper's kernel benchmark sweeps
+# (Section 7.1: LLaMA-7b/13b/33b/65b, OPT-30b/66b/175b at batch 8, 16, 32): (hidden, feed-forward inner,
+# gated).  Per block: QKV [3h][h], attention output [h][h], feed-forward in [f][h] (twice for the gated
+# LLaMA form, stacked as [2f][h]) and out [h][f].  Architecture constants only; weights are synthetic.
+MODEL_DIMS = [
+    ("llama-7b", 4096, 11008, True),
+    ("llama-13b", 5120, 13824, True),
+    ("llama-33b", 6656, 17920, True),
+    ("llama-65b", 8192, 22016, True),
+    ("opt-30b", 7168, 28672, False),
+    ("opt-66b", 9216, 36864, False),
+    ("opt-175b", 12288, 49152, False),
+]
+
+
+def model_layers(hidden: int, inner: int, gated: bool):
+    """(name, M, K) of the four linear layers of one decoder block."""
+    return [("qkv", 3 * hidden, hidden), ("attn_out", hidden, hidden),
+            ("ffn_in", (2 if gated else 1) * inner, hidden), ("ffn_out", hidden, inner)]
+
+
 DECODE_N = [1, 2, 4, 8, 16, 32]
 PREFILL_N = [64, 128, 256, 512]
 

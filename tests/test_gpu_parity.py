@@ -465,3 +465,43 @@ def test_linear_more_tokens_than_one_launch_can_address(pkg, oracle):
     idx = torch.from_numpy(tokens).cuda()
     Y_ref = oracle.linear(packed, scales, _np16(X[idx]), M, K)
     _check_linear(_np16(Y[idx]), Y_ref, "long input")
+
+
+def test_linear_two_streams_with_their_own_workspaces(pkg, oracle):
+    """Calls that overlap on the GPU (two streams) with a workspace each give the bits of the same calls made
+    one after the other; split-K is forced so that both use partial tiles and arrival counters."""
+    M, K = 512, 4096
+    _say("linear on two streams M=%d K=%d" % (M, K))
+    Wa = workloads.make_weights(M, K, 31).cuda()
+    Wb = workloads.make_weights(M, K, 32).cuda()
+    pa, sa = pkg.fp6_quantize_pack(Wa)
+    pb, sb = pkg.fp6_quantize_pack(Wb)
+    pkg.fp6_tuning_set_split_k(4)
+    try:
+        cases = []
+        for N in (4, 48, 200):
+            Xa = workloads.make_activations(N, K, N).cuda()
+            Xb = workloads.make_activations(N, K, N + 1).cuda()
+            nbytes = max(pkg.fp6_linear_workspace_bytes(M, N, K), 16)
+            wsa = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+            wsb = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+            ref_a = pkg.fp6_linear(pa, sa, Xa, M, K, workspace=wsa).clone()
+            ref_b = pkg.fp6_linear(pb, sb, Xb, M, K, workspace=wsb).clone()
+            torch.cuda.synchronize()
+            s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+            outs_a, outs_b = [], []
+            for _ in range(6):
+                with torch.cuda.stream(s1):
+                    outs_a.append(pkg.fp6_linear(pa, sa, Xa, M, K, workspace=wsa).clone())
+                with torch.cuda.stream(s2):
+                    outs_b.append(pkg.fp6_linear(pb, sb, Xb, M, K, workspace=wsb).clone())
+            torch.cuda.synchronize()
+            for o in outs_a:
+                assert torch.equal(o.view(torch.int16), ref_a.view(torch.int16))
+            for o in outs_b:
+                assert torch.equal(o.view(torch.int16), ref_b.view(torch.int16))
+            cases.append((N, Xa, ref_a))
+    finally:
+        pkg.fp6_tuning_set_split_k(0)
+    N, Xa, ref_a = cases[1]
+    _check_linear(_np16(ref_a), oracle.linear(_np16(pa), _np16(sa), _np16(Xa), M, K), "two streams")

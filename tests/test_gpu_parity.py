@@ -336,7 +336,8 @@ def _sampled_row_tiles(M, count, seed):
 def test_full_size_layer_sampled(pkg, oracle, shape):
     """The benchmark layer at its real size, in the launch configuration bench.py times: the packed
     stream and scales are compared bit for bit on sampled 16-row tiles (tiles are contiguous in the
-    stream), and Y on the rows of those tiles for N = 1, 8, 32."""
+    stream), and Y on the rows of those tiles for N = 1 ... 512 (every kernel
+    and block shape the plan picks for this layer)."""
     name, M, K = shape
     _say("full-size %s M=%d K=%d" % (name, M, K))
     W = workloads.make_weights(M, K, seed=0, device="cuda")
@@ -351,7 +352,7 @@ def test_full_size_layer_sampled(pkg, oracle, shape):
     assert np.array_equal(_np16(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
     assert np.array_equal(got_packed, ref_packed)
     del W
-    for N in (1, 8, 32, 64, 512):
+    for N in (1, 8, 16, 32, 64, 128, 256, 512):
         _say("  linear N=%d" % N)
         X = workloads.make_activations(N, K, seed=N, device="cuda")
         Y = pkg.fp6_linear(packed, scales, X, M, K)

@@ -133,6 +133,22 @@ constexpr TileShape kTile128x128{2, 4, 4, 2};
 constexpr TileShape kTile256x64{4, 4, 4, 1};
 constexpr TileShape kTile128x64{2, 4, 4, 1};
 
+// A kernel that uses more than 64 KB of dynamic LDS has to be told so once per device.  `done` holds one
+// bit per device ordinal (mod 64); safe to call from several host threads.
+bool allow_dynamic_lds(const void *kernel, size_t bytes, std::atomic<uint64_t> &done)
+{
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess)
+        return false;
+    const uint64_t bit = 1ull << (device & 63);
+    if (done.load(std::memory_order_acquire) & bit)
+        return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+        return false;
+    done.fetch_or(bit, std::memory_order_release);
+    return true;
+}
+
 std::atomic<int> g_forced_tile{0};  // 0 = automatic, else rows * 1024 + tokens (tuning hook)
 
 struct TiledPlan {
@@ -185,13 +201,9 @@ fp6_status launch_tiled_cfg(const TiledPlan &p, const void *weights, const void 
                             hipStream_t stream)
 {
     auto kernel = linear_tiled_kernel<Src, RT, NT, WM, WN>;
-    static bool lds_ok = false;  // per instantiation: allow more than 64 KB of dynamic LDS
-    if (!lds_ok) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)p.lds_bytes) != hipSuccess)
-            return FP6_ERR_HIP;
-        lds_ok = true;
-    }
+    static std::atomic<uint64_t> lds_done{0};  // per instantiation
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(kernel), p.lds_bytes, lds_done))
+        return FP6_ERR_HIP;
     // row blocks are dealt to the 8 XCDs round-robin: the grid is padded to a multiple of 8 row blocks
     const int padded_row_blocks = (p.row_blocks + 7) / 8 * 8;
     const dim3 grid((unsigned)(padded_row_blocks * p.n_blocks * p.split)), block(WM * WN * 64);
@@ -289,13 +301,9 @@ fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const voi
     auto kernel = linear_stream_kernel<Src, c.nt, c.waves, c.depth, c.stage, c.spread>;
     constexpr size_t lds = (size_t)2 * c.stage * c.nt * 512 * 16;  // two stages of activations
     static_assert(lds <= 160 * 1024, "activation stages exceed the LDS of a CU");
-    static bool lds_ok = false;
-    if (!lds_ok) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return FP6_ERR_HIP;
-        lds_ok = true;
-    }
+    static std::atomic<uint64_t> lds_done{0};  // per instantiation
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(kernel), lds, lds_done))
+        return FP6_ERR_HIP;
     const dim3 grid((unsigned)(p.row_blocks * p.split)), block(c.waves * 64);
     // tokens are processed 16*nt at a time; each pass re-streams the weights
     const int64_t step = 16 * c.nt;

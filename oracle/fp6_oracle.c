@@ -331,48 +331,15 @@ int fp6o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X
  *     y[n][o] += residual[n][o]                                     if residual
  * bias is fp16 [M]; residual is fp16 [N][Mout], Mout = M/2 when gated, else M.
  * rows (NULL: all) lists OUTPUT rows o; Y is double [N][nrows]. */
+int fpxo_linear_fused(int bits, int64_t group, const uint8_t *packed, const uint16_t *scales, const uint16_t *X,
+                      int64_t M, int64_t N, int64_t K, const uint16_t *bias, const uint16_t *residual, int gated,
+                      const int64_t *rows, int64_t nrows, double *Y);
+
 int fp6o_linear_fused(const uint8_t *packed, const uint16_t *scales, const uint16_t *X, int64_t M,
                       int64_t N, int64_t K, const uint16_t *bias, const uint16_t *residual, int gated,
                       const int64_t *rows, int64_t nrows, double *Y)
 {
-    const int64_t Mout = gated ? M / 2 : M;
-    if (gated && M % 2)
-        return 3;
-    if (!rows)
-        nrows = Mout;
-    const int64_t per = gated ? 2 : 1; /* weight rows behind one output row */
-    int64_t *wrows = (int64_t *)malloc((size_t)(nrows * per) * sizeof(int64_t));
-    double *Z = (double *)malloc((size_t)(N * nrows * per) * sizeof(double));
-    if (!wrows || !Z) {
-        free(wrows);
-        free(Z);
-        return 2;
-    }
-    for (int64_t i = 0; i < nrows; ++i) {
-        int64_t o = rows ? rows[i] : i;
-        for (int64_t j = 0; j < per; ++j)
-            wrows[i * per + j] = o * per + j;
-    }
-    int rc = fp6o_linear(packed, scales, X, M, N, K, wrows, nrows * per, Z);
-    if (rc == 0) {
-        for (int64_t n = 0; n < N; ++n)
-            for (int64_t i = 0; i < nrows; ++i) {
-                int64_t o = rows ? rows[i] : i;
-                double z[2] = {0.0, 0.0};
-                for (int64_t j = 0; j < per; ++j) {
-                    z[j] = Z[n * nrows * per + i * per + j];
-                    if (bias)
-                        z[j] += fp6o_half_to_double(bias[o * per + j]);
-                }
-                double y = gated ? z[0] / (1.0 + exp(-z[0])) * z[1] : z[0];
-                if (residual)
-                    y += fp6o_half_to_double(residual[n * Mout + o]);
-                Y[n * nrows + i] = y;
-            }
-    }
-    free(wrows);
-    free(Z);
-    return rc;
+    return fpxo_linear_fused(6, 0, packed, scales, X, M, N, K, bias, residual, gated, rows, nrows, Y);
 }
 
 /* Plain fp16-weight linear layer in double, for the W16A16 comparison kernel:
@@ -1176,6 +1143,65 @@ int fp3o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X
     free(codes);
     free(sc);
     return 0;
+}
+
+/* The same steps after the linear layer of any of the formats of this file: bits = 6, 5, 4 or 3 selects
+ * fp6o_linear, fp5o_linear, fp4o_linear or fp3o_linear; bits = 6 with group > 0 selects the group-wise
+ * scales of fp6go_linear.  fp6o_linear_fused above is this function with bits = 6, group = 0. */
+int fpxo_linear_fused(int bits, int64_t group, const uint8_t *packed, const uint16_t *scales, const uint16_t *X,
+                      int64_t M, int64_t N, int64_t K, const uint16_t *bias, const uint16_t *residual, int gated,
+                      const int64_t *rows, int64_t nrows, double *Y)
+{
+    if (bits < 3 || bits > 6 || (group > 0 && bits != 6))
+        return 4;
+    const int64_t Mout = gated ? M / 2 : M;
+    if (gated && M % 2)
+        return 3;
+    if (!rows)
+        nrows = Mout;
+    const int64_t per = gated ? 2 : 1; /* weight rows behind one output row */
+    int64_t *wrows = (int64_t *)malloc((size_t)(nrows * per) * sizeof(int64_t));
+    double *Z = (double *)malloc((size_t)(N * nrows * per) * sizeof(double));
+    if (!wrows || !Z) {
+        free(wrows);
+        free(Z);
+        return 2;
+    }
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t o = rows ? rows[i] : i;
+        for (int64_t j = 0; j < per; ++j)
+            wrows[i * per + j] = o * per + j;
+    }
+    int rc;
+    if (bits == 6 && group > 0)
+        rc = fp6go_linear(packed, scales, X, M, N, K, group, wrows, nrows * per, Z);
+    else if (bits == 6)
+        rc = fp6o_linear(packed, scales, X, M, N, K, wrows, nrows * per, Z);
+    else if (bits == 5)
+        rc = fp5o_linear(packed, scales, X, M, N, K, wrows, nrows * per, Z);
+    else if (bits == 4)
+        rc = fp4o_linear(packed, scales, X, M, N, K, wrows, nrows * per, Z);
+    else
+        rc = fp3o_linear(packed, scales, X, M, N, K, wrows, nrows * per, Z);
+    if (rc == 0) {
+        for (int64_t n = 0; n < N; ++n)
+            for (int64_t i = 0; i < nrows; ++i) {
+                int64_t o = rows ? rows[i] : i;
+                double z[2] = {0.0, 0.0};
+                for (int64_t j = 0; j < per; ++j) {
+                    z[j] = Z[n * nrows * per + i * per + j];
+                    if (bias)
+                        z[j] += fp6o_half_to_double(bias[o * per + j]);
+                }
+                double y = gated ? z[0] / (1.0 + exp(-z[0])) * z[1] : z[0];
+                if (residual)
+                    y += fp6o_half_to_double(residual[n * Mout + o]);
+                Y[n * nrows + i] = y;
+            }
+    }
+    free(wrows);
+    free(Z);
+    return rc;
 }
 
 #ifdef _OPENMP

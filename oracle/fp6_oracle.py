@@ -71,6 +71,8 @@ def _load():
     L.fp6o_linear.argtypes = [vp, vp, vp, i64, i64, i64, vp, i64, vp]
     L.fp6o_linear_fused.restype = ci
     L.fp6o_linear_fused.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, ci, vp, i64, vp]
+    L.fpxo_linear_fused.restype = ci
+    L.fpxo_linear_fused.argtypes = [ci, i64, vp, vp, vp, i64, i64, i64, vp, vp, ci, vp, i64, vp]
     L.fp6o_linear_f16.restype = None
     L.fp6o_linear_f16.argtypes = [vp, vp, i64, i64, i64, vp, i64, vp]
     L.fp6o_threads.restype = ci
@@ -232,18 +234,19 @@ def linear(packed: np.ndarray, scales: np.ndarray, X: np.ndarray, M: int, K: int
 
 
 def linear_fused(packed: np.ndarray, scales: np.ndarray, X: np.ndarray, M: int, K: int, bias=None,
-                 residual=None, gated: bool = False, rows=None) -> np.ndarray:
+                 residual=None, gated: bool = False, rows=None, bits: int = 6, group: int = 0) -> np.ndarray:
     """The linear layer plus bias / silu(gate)*up / residual (see fp6o_linear_fused); float64 [N][nrows].
 
-    rows lists OUTPUT rows (of M/2 when gated); bias fp16 [M]; residual fp16 [N][Mout]."""
+    rows lists OUTPUT rows (of M/2 when gated); bias fp16 [M]; residual fp16 [N][Mout].  bits = 5, 4, 3
+    takes the packed stream of that width; bits = 6 with group > 0 takes scales [M][K/group]."""
     _check_shape(M, K)
     packed = np.ascontiguousarray(packed, dtype=np.uint8)
-    assert packed.size == packed_bytes(M, K)
+    assert packed.size == M * K * bits // 8
     Xb = _u16(X)
     N, K2 = Xb.shape
     assert K2 == K
     sc = _u16(scales)
-    assert sc.size == M
+    assert sc.size == (M * (K // group) if group else M)
     Mout = M // 2 if gated else M
     null = ctypes.c_void_p(0)
     bp = rp_ = null
@@ -257,11 +260,12 @@ def linear_fused(packed: np.ndarray, scales: np.ndarray, X: np.ndarray, M: int, 
         rp_ = _p(rb)
     r, nrows, rp = _rows_arg(rows, Mout)
     Y = np.empty((N, nrows), dtype=np.float64)
-    rc = _load().fp6o_linear_fused(_p(packed), _p(sc), _p(Xb), M, N, K, bp, rp_, int(bool(gated)), rp, nrows, _p(Y))
+    rc = _load().fpxo_linear_fused(int(bits), int(group), _p(packed), _p(sc), _p(Xb), M, N, K, bp, rp_,
+                                   int(bool(gated)), rp, nrows, _p(Y))
     if rc == 2:
         raise MemoryError
     if rc:
-        raise ValueError("gated needs an even M")
+        raise ValueError("gated needs an even M; bits must be 3..6; group only with 6 bits")
     return Y
 
 

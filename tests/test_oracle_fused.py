@@ -117,3 +117,37 @@ def test_gated_needs_even_rows_and_matching_shapes(oracle):
     X, packed, scales = _setup(oracle, M, K, N)
     with pytest.raises(AssertionError):
         oracle.linear_fused(packed, scales, X, M, K, residual=np.zeros((N, M), np.float16), gated=True)
+
+
+@pytest.mark.parametrize("bits", [5, 4, 3])
+def test_other_widths_share_the_steps(oracle, bits):
+    """The steps are one piece of code for every width (bits = 6 is the function pinned above); what changes
+    is the linear layer under them, each pinned in its own file: with no step the result is that layer, and
+    with all steps it is that layer's output pushed through the logistic function of scipy."""
+    import importlib
+    o = importlib.import_module("oracle.fp%d_oracle" % bits)
+    M, K, N = 32, 512, 3
+    W = workloads.make_weights(M, K, seed=bits).numpy()
+    X = workloads.make_activations(N, K, seed=bits).numpy()
+    packed, scales = o.quantize_pack(W)
+    Z = o.linear(packed, scales, X, M, K)
+    assert np.array_equal(oracle.linear_fused(packed, scales, X, M, K, bits=bits), Z)
+    bias = (workloads.make_activations(1, M, 40)[0] * 0.5).to(dtype=workloads.make_weights(1, 1).dtype).numpy()
+    R = workloads.make_activations(N, M // 2, 41).numpy()
+    got = oracle.linear_fused(packed, scales, X, M, K, bias=bias, residual=R, gated=True, bits=bits)
+    z = Z + bias.astype(np.float64)[None, :]
+    want = z[:, 0::2] * expit(z[:, 0::2]) * z[:, 1::2] + R.astype(np.float64)
+    assert np.abs(got - want).max() <= 1e-13 * np.abs(want).max()
+
+
+def test_group_scales_share_the_steps(oracle):
+    from oracle import fp6g_oracle
+    M, K, N = 32, 512, 3
+    W = workloads.make_weights(M, K, seed=12).numpy()
+    X = workloads.make_activations(N, K, seed=12).numpy()
+    packed, scales = fp6g_oracle.quantize_pack(W, 128)
+    Z = fp6g_oracle.linear(packed, scales, X, M, K, 128)
+    assert np.array_equal(oracle.linear_fused(packed, scales, X, M, K, group=128), Z)
+    R = workloads.make_activations(N, M, 42).numpy()
+    got = oracle.linear_fused(packed, scales, X, M, K, residual=R, group=128)
+    assert np.abs(got - (Z + R.astype(np.float64))).max() <= 1e-13 * np.abs(Z).max()

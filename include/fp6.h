@@ -230,6 +230,24 @@ fp6_status fp3_linear(const void *packed, const void *scales_f16, const void *X_
                       int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * fp6_linear_fused for the other weight formats: the same steps (bias, silu(gate) * up over
+ * interleaved row pairs, residual) after fp5_linear, fp4_linear, fp3_linear and fp6g_linear.
+ * Arguments as for fp6_linear_fused (fp6g: scales fp16 [M][K/group], group = 128).
+ */
+fp6_status fp5_linear_fused(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                            int64_t N, int64_t K, const void *bias_f16, const void *residual_f16, int gated,
+                            void *workspace, size_t workspace_bytes, void *stream);
+fp6_status fp4_linear_fused(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                            int64_t N, int64_t K, const void *bias_f16, const void *residual_f16, int gated,
+                            void *workspace, size_t workspace_bytes, void *stream);
+fp6_status fp3_linear_fused(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                            int64_t N, int64_t K, const void *bias_f16, const void *residual_f16, int gated,
+                            void *workspace, size_t workspace_bytes, void *stream);
+fp6_status fp6g_linear_fused(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                             int64_t N, int64_t K, int64_t group, const void *bias_f16, const void *residual_f16,
+                             int gated, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Tuning hook for benchmarks: force the split-K factor used by fp6_linear, fp5_linear,
  * fp4_linear, fp3_linear and fp16_linear (0 = choose automatically, the default).  Process-wide; affects the
  * workspace size queries as well.  Values the shape cannot honour are clamped.

@@ -55,6 +55,11 @@ def load_library():
     L.fp6_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
     L.fp6_linear_fused.restype = ci
     L.fp6_linear_fused.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, ci, vp, sz, vp]
+    for _name in ("fp5_linear_fused", "fp4_linear_fused", "fp3_linear_fused"):
+        getattr(L, _name).restype = ci
+        getattr(L, _name).argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, ci, vp, sz, vp]
+    L.fp6g_linear_fused.restype = ci
+    L.fp6g_linear_fused.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, ci, vp, sz, vp]
     L.fp16_linear.restype = ci
     L.fp16_linear.argtypes = [vp, vp, vp, i64, i64, i64, vp, sz, vp]
     L.fp5_packed_bytes.restype = sz
@@ -238,13 +243,7 @@ def fp6_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: i
     return _linear("fp6", packed, scales, X, M, K, out, workspace)
 
 
-def fp6_linear_fused(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
-                     bias: Optional[torch.Tensor] = None, residual: Optional[torch.Tensor] = None,
-                     gated: bool = False, out: Optional[torch.Tensor] = None,
-                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """fp6_linear followed, inside the kernel, by + bias[M], silu(row 2i) * row 2i+1 (gated) and + residual.
-
-    Returns Y[N][Mout], Mout = M/2 when gated else M; residual has Y's shape and may be `out` itself."""
+def _linear_fused(prefix, packed, scales, X, M, K, bias, residual, gated, out, workspace, group=0):
     L = load_library()
     _dev(packed, torch.uint8, "packed")
     _dev(scales, torch.float16, "scales")
@@ -252,10 +251,12 @@ def fp6_linear_fused(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor
     if X.dim() != 2 or X.shape[1] != K:
         raise Fp6Error("X must be [N][K]")
     N = X.shape[0]
-    nbytes = L.fp6_packed_bytes(M, K)
-    if nbytes == 0 or N == 0:
+    base = "fp6" if prefix == "fp6g" else prefix
+    nbytes = getattr(L, base + "_packed_bytes")(M, K)
+    if nbytes == 0 or N == 0 or (prefix == "fp6g" and (group <= 0 or K % group)):
         _check(2)
-    if packed.numel() != nbytes or scales.numel() != M:
+    n_scales = M * (K // group) if prefix == "fp6g" else M
+    if packed.numel() != nbytes or scales.numel() != n_scales:
         raise Fp6Error("packed/scales do not match M, K")
     Mout = M // 2 if gated else M
     if bias is not None:
@@ -272,13 +273,41 @@ def fp6_linear_fused(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor
     if out.numel() != N * Mout:
         raise Fp6Error("out has the wrong size")
     if workspace is None:
-        workspace = _new_workspace(L.fp6_linear_workspace_bytes(M, N, K), X.device)
+        workspace = _new_workspace(getattr(L, base + "_linear_workspace_bytes")(M, N, K), X.device)
     ws_ptr, ws_len = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
-    _check(L.fp6_linear_fused(packed.data_ptr(), scales.data_ptr(), X.data_ptr(), out.data_ptr(), M, N, K,
-                              bias.data_ptr() if bias is not None else None,
-                              residual.data_ptr() if residual is not None else None, int(bool(gated)),
-                              ws_ptr, ws_len, _stream()))
+    head = (packed.data_ptr(), scales.data_ptr(), X.data_ptr(), out.data_ptr(), M, N, K)
+    tail = (bias.data_ptr() if bias is not None else None, residual.data_ptr() if residual is not None else None,
+            int(bool(gated)), ws_ptr, ws_len, _stream())
+    fn = getattr(L, prefix + "_linear_fused")
+    _check(fn(*head, group, *tail) if prefix == "fp6g" else fn(*head, *tail))
     return out
+
+
+def fp6_linear_fused(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
+                     bias: Optional[torch.Tensor] = None, residual: Optional[torch.Tensor] = None,
+                     gated: bool = False, out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """fp6_linear followed, inside the kernel, by + bias[M], silu(row 2i) * row 2i+1 (gated) and + residual.
+
+    Returns Y[N][Mout], Mout = M/2 when gated else M; residual has Y's shape and may be `out` itself."""
+    return _linear_fused("fp6", packed, scales, X, M, K, bias, residual, gated, out, workspace)
+
+
+def fp5_linear_fused(packed, scales, X, M, K, bias=None, residual=None, gated=False, out=None, workspace=None):
+    return _linear_fused("fp5", packed, scales, X, M, K, bias, residual, gated, out, workspace)
+
+
+def fp4_linear_fused(packed, scales, X, M, K, bias=None, residual=None, gated=False, out=None, workspace=None):
+    return _linear_fused("fp4", packed, scales, X, M, K, bias, residual, gated, out, workspace)
+
+
+def fp3_linear_fused(packed, scales, X, M, K, bias=None, residual=None, gated=False, out=None, workspace=None):
+    return _linear_fused("fp3", packed, scales, X, M, K, bias, residual, gated, out, workspace)
+
+
+def fp6g_linear_fused(packed, scales, X, M, K, group=128, bias=None, residual=None, gated=False, out=None,
+                      workspace=None):
+    return _linear_fused("fp6g", packed, scales, X, M, K, bias, residual, gated, out, workspace, group=group)
 
 
 def fp5_packed_bytes(M: int, K: int) -> int:

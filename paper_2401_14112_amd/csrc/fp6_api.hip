@@ -582,6 +582,32 @@ fp6_status fp3_linear(const void *packed, const void *scales_f16, const void *X_
                                                stream);
 }
 
+#define FP6_FUSED_ENTRY(NAME, SRC)                                                                                     \
+    fp6_status NAME(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N, \
+                    int64_t K, const void *bias_f16, const void *residual_f16, int gated, void *workspace,             \
+                    size_t workspace_bytes, void *stream)                                                              \
+    {                                                                                                                  \
+        const Epilogue epi{static_cast<const half_t *>(bias_f16), static_cast<const half_t *>(residual_f16),         \
+                           gated ? 1 : 0};                                                                             \
+        return packed_linear_impl<SRC>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes, stream,  \
+                                       epi);                                                                           \
+    }
+FP6_FUSED_ENTRY(fp5_linear_fused, PackedFp5Source)
+FP6_FUSED_ENTRY(fp4_linear_fused, PackedFp4Source)
+FP6_FUSED_ENTRY(fp3_linear_fused, PackedFp3Source)
+#undef FP6_FUSED_ENTRY
+
+fp6_status fp6g_linear_fused(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                             int64_t N, int64_t K, int64_t group, const void *bias_f16, const void *residual_f16,
+                             int gated, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (group != kGroupColumns)
+        return FP6_ERR_SHAPE;
+    const Epilogue epi{static_cast<const half_t *>(bias_f16), static_cast<const half_t *>(residual_f16), gated ? 1 : 0};
+    return packed_linear_impl<PackedFp6GroupSource>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace,
+                                                    workspace_bytes, stream, epi);
+}
+
 fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N, int64_t K,
                        void *workspace, size_t workspace_bytes, void *stream)
 {

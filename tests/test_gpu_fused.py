@@ -227,3 +227,31 @@ def test_fused_full_size_decoder_projections(pkg, oracle, N):
     ref2 = oracle.linear_fused(ref_packed2, ref_scales2, _np(A), len(rows2), F, residual=R0[:, rows2])
     worst = _check(_np(R)[:, rows2], ref2, "down N=%d" % N)
     _say("  down + residual worst column ratio %.3g" % worst)
+
+
+@pytest.mark.parametrize("fmt", ["fp5", "fp4", "fp3", "fp6g"])
+@pytest.mark.parametrize("mode", ["all", "bias_residual"])
+@pytest.mark.parametrize("N", [5, 40, 100])
+def test_fused_other_formats(pkg, oracle, fmt, mode, N):
+    """The same steps after the 5-, 4-, 3-bit layers and the layer with group-wise scales."""
+    import importlib
+    M, K = 96, 1536
+    _say("fused %s %s N=%d" % (fmt, mode, N))
+    m = MODES[mode]
+    W, X, bias, R = _inputs(M, K, N, seed=N + len(fmt), mode=m)
+    kw = dict(bias=None if bias is None else bias.cuda(), residual=None if R is None else R.cuda(), gated=m["gated"])
+    okw = dict(bias=None if bias is None else bias.numpy(), residual=None if R is None else R.numpy(), gated=m["gated"])
+    if fmt == "fp6g":
+        from oracle import fp6g_oracle
+        packed, scales = fp6g_oracle.quantize_pack(W, 128)
+        Y_ref = oracle.linear_fused(packed, scales, X.numpy(), M, K, group=128, **okw)
+        Y = pkg.fp6g_linear_fused(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), X.cuda(), M, K, 128, **kw)
+    else:
+        bits = int(fmt[2])
+        o = importlib.import_module("oracle.%s_oracle" % fmt)
+        packed, scales = o.quantize_pack(W)
+        Y_ref = oracle.linear_fused(packed, scales, X.numpy(), M, K, bits=bits, **okw)
+        Y = getattr(pkg, fmt + "_linear_fused")(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), X.cuda(), M, K, **kw)
+    torch.cuda.synchronize()
+    assert Y.shape == Y_ref.shape
+    _check(_np(Y), Y_ref, "%s %s N=%d" % (fmt, mode, N))

@@ -106,6 +106,13 @@ def main():
             for i, n in enumerate(sweep):
                 launch(n, (s * len(sweep) + i) % N_BUFFERS)
         graphs.append(g)
+    # `period` consecutive steps (one pass over the rotation) as ONE graph: a graph launch has a fixed cost
+    # that a serving loop would also spread over as many launches as it can capture
+    rotation = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(rotation):
+        for s in range(period):
+            for i, n in enumerate(sweep):
+                launch(n, (s * len(sweep) + i) % N_BUFFERS)
 
     # ---- quick validity check of what is being timed (sampled rows against the CPU oracle)
     from oracle import fp6_oracle as oracle
@@ -134,12 +141,17 @@ def main():
     del cal_src, cal_dst
 
     # ---- timed region: W warm-up steps, then exactly K steps between synchronizations
-    for s in range(args.warmup):
-        graphs[s % period].replay()
+    def run_steps(count):
+        """Exactly `count` steps: whole rotations from the long graph, the remainder from single-step graphs."""
+        for _ in range(count // period):
+            rotation.replay()
+        for s in range(count % period):
+            graphs[s].replay()
+
+    run_steps(args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for s in range(args.steps):
-        graphs[s % period].replay()
+    run_steps(args.steps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -167,24 +179,25 @@ def main():
     # the same launches with the same buffer rotation, captured without the N = 32 launch, HIP events on the
     # launch stream around every replay; duration per launch = elapsed / launches in the replay
     small = [n for n in sweep if n <= 16]
-    dom_graphs = []
-    for s in range(period):
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
+    dom_graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(dom_graph):
+        for s in range(period):
             for i, n in enumerate(sweep):
                 if n <= 16:
                     launch(n, (s * len(sweep) + i) % N_BUFFERS)
-        dom_graphs.append(g)
-    for s in range(args.warmup):
-        dom_graphs[s % period].replay()
-    dev_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for s in range(max(1, args.warmup // period)):
+        dom_graph.replay()
+    # one pair of events brackets one replay of the whole rotation (an event record is a stream operation of
+    # its own and would otherwise add its gap to every five launches)
+    groups = max(1, args.steps // period)
+    dev_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(groups)]
     torch.cuda.synchronize()
-    for s in range(args.steps):
-        dev_ev[s][0].record()
-        dom_graphs[s % period].replay()
-        dev_ev[s][1].record()
+    for gi in range(groups):
+        dev_ev[gi][0].record()
+        dom_graph.replay()
+        dev_ev[gi][1].record()
     torch.cuda.synchronize()
-    dom_us_all = np.array([a.elapsed_time(b) for a, b in dev_ev]) * 1e3 / len(small)
+    dom_us_all = np.array([a.elapsed_time(b) for a, b in dev_ev]) * 1e3 / (len(small) * period)
     dom_bytes = sum(algorithmic_bytes(M, n, K) for n in small) / len(small)
     dom_us = float(dom_us_all.mean())
     achieved = dom_bytes / (dom_us * 1e-6) * 1e-9
@@ -204,7 +217,7 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": "llama65b_ffn W[8192x22016] W6A16 linear, one step = decode sweep N in "
-                        "{1,2,4,8,16,32}, launch j reads packed copy j%8 (1.08 GB rotation), HIP-graph replay",
+                        "{1,2,4,8,16,32}, launch j reads packed copy j mod 8 (1.08 GB rotation), replayed from a HIP graph of %d steps" % period,
             "M": M, "K": K, "N_sweep": sweep, "weight_buffers": N_BUFFERS,
             "layout_version": pkg.fp6_layout_version(),
             "arithmetic": "e3m2 weights de-quantized to f16 in registers x f16 activations, f32 accumulate, one f16 rounding",
@@ -221,8 +234,9 @@ def main():
             "algorithmic_bytes_per_launch": int(dom_bytes),
             "avg_launch_us": round(dom_us, 2),
             "min_launch_us": round(float(dom_us_all.min()), 2),
-            "timing": "HIP events on the launch stream around each graph replay of the step's five N <= 16 "
-                      "launches, elapsed / 5",
+            "timing": "HIP events on the launch stream around every replay of a graph holding the N <= 16 launches "
+                      "of %d consecutive steps (one pass over the rotation of weight copies), elapsed / %d"
+                      % (period, 5 * period),
         },
         "sweep": {
             str(n): {

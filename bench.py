@@ -275,22 +275,27 @@ def read_traffic_profile():
 
 
 def _time_graph(torch, fn, launches_per_graph, reps=20):
-    """Average microseconds per launch of fn(i) for i in range(launches_per_graph), from graph replays."""
+    """Average microseconds per launch of fn(i) for i in range(launches_per_graph), from graph replays.  The
+    graph holds as many passes over those launches as it takes to reach 24 launches, so that the fixed cost of
+    a graph launch is spread the same way for every kernel that is compared."""
     fn(0)
     torch.cuda.synchronize()
+    passes = max(1, -(-24 // launches_per_graph))
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
-        for i in range(launches_per_graph):
-            fn(i)
+        for _ in range(passes):
+            for i in range(launches_per_graph):
+                fn(i)
     g.replay()
     torch.cuda.synchronize()
+    reps = max(2, -(-reps // passes))
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
         g.replay()
     e1.record()
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / (reps * launches_per_graph)
+    return e0.elapsed_time(e1) * 1e3 / (reps * passes * launches_per_graph)
 
 
 def _compare_sweep(pkg, torch, workloads, M, K, packed, scales, W16, Ns):

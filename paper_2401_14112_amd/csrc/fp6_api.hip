@@ -191,7 +191,7 @@ TiledPlan plan_tiled(int64_t M, int64_t N, int64_t K, bool tall_tile_ok)
     const int bnt = p.tile.nt * p.tile.wn;
     p.counter_bytes = (((size_t)p.row_blocks * p.n_blocks * sizeof(int)) + 255) / 256 * 256;
     p.partial_bytes = (size_t)p.split * (size_t)row_tiles * (size_t)p.n_blocks * bnt * 64 * sizeof(float4_t);
-    p.lds_bytes = (size_t)2 * bnt * 512 * 16;
+    p.lds_bytes = (size_t)4 * bnt * 256 * 16;  // the kernel's ring of four half tiles of activations
     return p;
 }
 

@@ -506,3 +506,24 @@ def test_linear_two_streams_with_their_own_workspaces(pkg, oracle):
         pkg.fp6_tuning_set_split_k(0)
     N, Xa, ref_a = cases[1]
     _check_linear(_np16(ref_a), oracle.linear(_np16(pa), _np16(sa), _np16(Xa), M, K), "two streams")
+
+
+def test_decode_sweep_full_output(pkg, oracle):
+    """The benchmark layer's decode sweep checked on EVERY output (all 8192 rows), N = 1, 8 and 32: the library
+    quantizes and packs on the GPU (the sampled-tile test above compares that stream with the oracle's), the
+    oracle then computes the whole layer from those bytes in fp64."""
+    name, M, K = workloads.FFN_65B
+    _say("full output %s M=%d K=%d" % (name, M, K))
+    W = workloads.make_weights(M, K, seed=0, device="cuda")
+    packed, scales = pkg.fp6_quantize_pack(W)
+    del W
+    torch.cuda.synchronize()
+    packed_h, scales_h = _np16(packed), _np16(scales)
+    for N in (1, 8, 32):
+        X = workloads.make_activations(N, K, seed=N, device="cuda")
+        Y = pkg.fp6_linear(packed, scales, X, M, K)
+        torch.cuda.synchronize()
+        _say("  oracle on all rows, N=%d" % N)
+        Y_ref = oracle.linear(packed_h, scales_h, _np16(X), M, K)
+        worst = _check_linear(_np16(Y), Y_ref, "%s full N=%d" % (name, N))
+        _say("    worst column ratio %.3g" % worst)

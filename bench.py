@@ -252,6 +252,11 @@ def main():
 
     if not args.no_extras:
         result["offline"] = side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_ms)
+        ceil = result["offline"]["empirical_ceilings"]
+        result["roofline"]["measured_peak_GBps"] = ceil["read_stream_1GiB_GBps"]
+        result["roofline"]["frac_of_measured_peak"] = round(achieved / ceil["read_stream_1GiB_GBps"], 4)
+        result["roofline"]["frac_of_same_size_read_stream"] = round(
+            ceil["read_stream_one_launch_135MB_us"] / dom_us, 4)
     del W0
 
     if not args.no_cpu_baseline:
@@ -368,6 +373,7 @@ def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_
     out["decoder_set_70b"] = decoder_set_measurements(pkg, torch, np, workloads, dev)
     out["fused_feed_forward_70b"] = fused_block_measurements(pkg, torch, workloads, dev)
     out["model_blocks_vs_fp16"] = model_block_measurements(pkg, torch, workloads, dev)
+    out["empirical_ceilings"] = empirical_ceilings(pkg, torch, packed)
     return out
 
 
@@ -531,6 +537,29 @@ def fused_block_measurements(pkg, torch, workloads, dev, copies=4):
                        "speedup": round(us_s / us_f, 3),
                        "fused_hbm_frac": round(alg / us_f * 1e-3 / HBM_PEAK_GBPS, 4)}
     return out
+
+
+def empirical_ceilings(pkg, torch, packed):
+    """What this device delivers to the request patterns of the linear kernels, measured in the same run: a
+    read-only stream (the weight path's loads, nothing computed) over 1 GiB and over buffers of one launch's
+    size (the packed copies of the benchmark layer, rotating), and a loop of matrix instructions on register
+    operands.  The fractions in the sweep tables are against the vendor peaks; these are the measured ones."""
+    dev = packed[0].device
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).zero_()
+    rsink = torch.empty(1024, dtype=torch.int32, device=dev)
+    n_big = pkg.fp6_probe_read(big, rsink)
+    us_big = _time_graph(torch, lambda i: pkg.fp6_probe_read(big, rsink), 4, reps=8)
+    n_one = pkg.fp6_probe_read(packed[0], rsink)
+    us_one = _time_graph(torch, lambda i: pkg.fp6_probe_read(packed[i % len(packed)], rsink), len(packed), reps=10)
+    del big
+    sink = torch.empty(4 << 20, dtype=torch.uint8, device=dev)
+    iters = 5000
+    flop = pkg.fp6_probe_mfma(iters, sink)
+    us_mfma = _time_graph(torch, lambda i: pkg.fp6_probe_mfma(iters, sink), 2, reps=4)
+    return {"read_stream_1GiB_GBps": round(n_big / us_big * 1e-3, 1),
+            "read_stream_one_launch_135MB_us": round(us_one, 2),
+            "read_stream_one_launch_135MB_GBps": round(n_one / us_one * 1e-3, 1),
+            "mfma_f16_32x32x16_TFLOPs": round(flop / us_mfma * 1e-6, 1)}
 
 
 def model_block_measurements(pkg, torch, workloads, dev):

@@ -248,6 +248,24 @@ fp6_status fp6g_linear_fused(const void *packed, const void *scales_f16, const v
                              int gated, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Diagnostics for benchmarks: empirical ceilings of the device, measured with the request
+ * patterns of the linear kernels (the paper's Section 7.1 reads the same two utilisations
+ * off its profiler: DRAM bandwidth and Tensor-Core use).
+ *   fp6_probe_read: 1024 waves each stream a contiguous piece of `buffer` (device) once with
+ *     the non-temporal 128-bit loads of the weight path, sixteen in flight, and XOR the
+ *     32-bit words together; wave w covers bytes [w*c, (w+1)*c), c = fp6_probe_read_bytes(bytes)
+ *     / 1024 (whole 16 KB steps), and writes its XOR to sink[w] (device, 1024 x uint32).
+ *     bytes >= 16 MiB, else FP6_ERR_SHAPE.
+ *   fp6_probe_mfma: 4096 waves (four per SIMD) each issue iters x 4 independent
+ *     v_mfma_f32_32x32x16_f16 (32768 flop each) on register operands; `sink` (device,
+ *     fp6_probe_mfma_sink_bytes() bytes) receives one float per lane.
+ */
+fp6_status fp6_probe_read(const void *buffer, size_t bytes, void *sink, void *stream);
+size_t fp6_probe_read_bytes(size_t bytes);
+fp6_status fp6_probe_mfma(int64_t iters, void *sink, void *stream);
+size_t fp6_probe_mfma_sink_bytes(void);
+
+/*
  * Tuning hook for benchmarks: force the split-K factor used by fp6_linear, fp5_linear,
  * fp4_linear, fp3_linear and fp16_linear (0 = choose automatically, the default).  Process-wide; affects the
  * workspace size queries as well.  Values the shape cannot honour are clamped.

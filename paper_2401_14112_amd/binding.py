@@ -60,6 +60,14 @@ def load_library():
         getattr(L, _name).argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, ci, vp, sz, vp]
     L.fp6g_linear_fused.restype = ci
     L.fp6g_linear_fused.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, ci, vp, sz, vp]
+    L.fp6_probe_read.restype = ci
+    L.fp6_probe_read.argtypes = [vp, sz, vp, vp]
+    L.fp6_probe_read_bytes.restype = sz
+    L.fp6_probe_read_bytes.argtypes = [sz]
+    L.fp6_probe_mfma.restype = ci
+    L.fp6_probe_mfma.argtypes = [i64, vp, vp]
+    L.fp6_probe_mfma_sink_bytes.restype = sz
+    L.fp6_probe_mfma_sink_bytes.argtypes = []
     L.fp16_linear.restype = ci
     L.fp16_linear.argtypes = [vp, vp, vp, i64, i64, i64, vp, sz, vp]
     L.fp5_packed_bytes.restype = sz
@@ -471,3 +479,29 @@ def fp16_linear(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] = 
     ws_ptr, ws_len = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
     _check(L.fp16_linear(W.data_ptr(), X.data_ptr(), out.data_ptr(), M, N, K, ws_ptr, ws_len, _stream()))
     return out
+
+
+def fp6_probe_read(buffer: torch.Tensor, sink: Optional[torch.Tensor] = None) -> int:
+    """Stream `buffer` once with the weight path's loads (diagnostic); returns the bytes actually read.
+    sink (int32 [1024], device) receives the XOR of the 32-bit words of each wave's piece."""
+    L = load_library()
+    _dev(buffer, torch.uint8, "buffer")
+    if sink is None:
+        sink = torch.empty(1024, dtype=torch.int32, device=buffer.device)
+    _dev(sink, torch.int32, "sink")
+    if sink.numel() < 1024:
+        raise Fp6Error("sink too small")
+    _check(L.fp6_probe_read(buffer.data_ptr(), buffer.numel(), sink.data_ptr(), _stream()))
+    return int(L.fp6_probe_read_bytes(buffer.numel()))
+
+
+def fp6_probe_mfma(iters: int, sink: Optional[torch.Tensor] = None) -> float:
+    """Issue iters x 4 matrix instructions (32x32x16, fp16) per wave on 4096 waves (diagnostic); returns the flop count."""
+    L = load_library()
+    if sink is None:
+        sink = torch.empty(L.fp6_probe_mfma_sink_bytes(), dtype=torch.uint8, device="cuda")
+    _dev(sink, torch.uint8, "sink")
+    if sink.numel() < L.fp6_probe_mfma_sink_bytes():
+        raise Fp6Error("sink too small")
+    _check(L.fp6_probe_mfma(int(iters), sink.data_ptr(), _stream()))
+    return 4096.0 * iters * 4 * 32768.0

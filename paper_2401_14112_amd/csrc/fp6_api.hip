@@ -608,6 +608,37 @@ fp6_status fp6g_linear_fused(const void *packed, const void *scales_f16, const v
                                                     workspace_bytes, stream, epi);
 }
 
+fp6_status fp6_probe_read(const void *buffer, size_t bytes, void *sink, void *stream)
+{
+    if (!buffer || !sink)
+        return FP6_ERR_NULL;
+    if (!aligned16(buffer))
+        return FP6_ERR_ALIGN;
+    // 1024 waves (four per CU), each at least one double step of 16 KB and less than 2 GiB (32-bit lane offsets)
+    const unsigned blocks = kCus;
+    if (bytes < (size_t)blocks * 4 * 16384 || bytes / (blocks * 4) >= (1ull << 31))
+        return FP6_ERR_SHAPE;
+    hipLaunchKernelGGL(probe_read_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint8_t *>(buffer), bytes, static_cast<uint32_t *>(sink));
+    return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+}
+
+size_t fp6_probe_read_bytes(size_t bytes) { return bytes / (kCus * 4) / 16384 * 16384 * (kCus * 4); }
+
+size_t fp6_probe_mfma_sink_bytes(void) { return (size_t)kCus * 4 * 256 * sizeof(float); }
+
+fp6_status fp6_probe_mfma(int64_t iters, void *sink, void *stream)
+{
+    if (!sink)
+        return FP6_ERR_NULL;
+    if (iters <= 0 || iters >= (1ll << 31))
+        return FP6_ERR_SHAPE;
+    // four blocks of four waves per CU: four waves per SIMD
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(kCus * 4), dim3(256), 0, static_cast<hipStream_t>(stream), (int)iters,
+                       static_cast<float *>(sink));
+    return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
+}
+
 fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_t M, int64_t N, int64_t K,
                        void *workspace, size_t workspace_bytes, void *stream)
 {

@@ -93,6 +93,7 @@ constexpr int kOutOfRange = (int)0x80000000u;  // a lane offset no buffer here r
 template <int IMM, bool STREAMING>
 __device__ __forceinline__ u32x4 issue_load_b128(rsrc_t rsrc, int lane_off)
 {
+    static_assert(IMM >= 0 && IMM < 4096, "the immediate offset of a buffer load is a 12-bit field");
     u32x4 r;
     if (STREAMING)  // "nt": read-once data, do not keep it in the caches
         asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3 nt"
@@ -129,6 +130,7 @@ __device__ __forceinline__ void pin(uint32_t &v) { asm volatile("" : "+v"(v)); }
 template <int IMM>
 __device__ __forceinline__ u32x2 issue_load_b64(rsrc_t rsrc, int lane_off)
 {
+    static_assert(IMM >= 0 && IMM < 4096, "the immediate offset of a buffer load is a 12-bit field");
     u32x2 r;
     asm volatile("buffer_load_dwordx2 %0, %1, %2, 0 offen offset:%3 nt"
                  : "=v"(r) : "v"(lane_off), "s"(rsrc), "n"(IMM) : "memory");
@@ -141,6 +143,7 @@ __device__ __forceinline__ u32x2 issue_load_b64(rsrc_t rsrc, int lane_off)
 template <int IMM>
 __device__ __forceinline__ void issue_load_to_lds_b128(rsrc_t rsrc, int lane_off, uint32_t lds_base)
 {
+    static_assert(IMM >= 0 && IMM < 4096, "the immediate offset of a buffer load is a 12-bit field");
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen offset:%3 lds"
                  : : "s"(lds_base), "v"(lane_off), "s"(rsrc), "n"(IMM) : "memory");
 }

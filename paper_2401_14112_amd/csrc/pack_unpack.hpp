@@ -384,6 +384,84 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
     }
 }
 
+// ---- diagnostics: empirical ceilings of the device, with the request patterns of the linear kernels ------
+// probe_read_kernel: every wave streams a contiguous piece of the buffer with the non-temporal 128-bit loads
+// of the weight path, sixteen in flight (two sets of eight), and computes nothing.
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint8_t *__restrict__ buffer, size_t bytes,
+                                                         uint32_t *__restrict__ sink)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const size_t n_waves = (size_t)gridDim.x * 4;
+    const size_t chunk = bytes / n_waves / 16384 * 16384;  // whole double steps; the host sizes the grid for >= 1
+    const rsrc_t r = make_rsrc(buffer + wave * chunk, (uint32_t)chunk);
+    u32x4 a[8], b[8];
+    auto issue8 = [&](u32x4 (&v)[8], int off) {
+        v[0] = issue_load_b128<0, true>(r, off);
+        v[1] = issue_load_b128<1024, true>(r, off);
+        v[2] = issue_load_b128<2048, true>(r, off);
+        v[3] = issue_load_b128<3072, true>(r, off);
+        v[4] = issue_load_b128<0, true>(r, off + 4096);  // the immediate offset is a 12-bit field
+        v[5] = issue_load_b128<1024, true>(r, off + 4096);
+        v[6] = issue_load_b128<2048, true>(r, off + 4096);
+        v[7] = issue_load_b128<3072, true>(r, off + 4096);
+    };
+    u32x4 x = {0u, 0u, 0u, 0u};  // running XOR of everything loaded: the data is touched, and checkable
+    auto pin8 = [&](u32x4 (&v)[8]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            pin(v[i]);
+            x ^= v[i];
+        }
+        pin(x);  // the set is consumed here, before its registers are the target of the next loads
+    };
+    int off = lane * 16;
+    issue8(a, off);
+    for (size_t done = 0; done < chunk; done += 16384) {
+        issue8(b, off + 8192);
+        wait_loads<8>();
+        pin8(a);
+        issue8(a, off + 16384);  // past the end of the piece on the last trip: reads as zeros, no traffic
+        wait_loads<8>();
+        pin8(b);
+        off += 16384;
+    }
+    wait_loads<0>();
+    pin8(a);  // the look-ahead past the end of the piece: zeros
+    uint32_t w = x[0] ^ x[1] ^ x[2] ^ x[3];
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1)
+        w ^= (uint32_t)__shfl_xor((int)w, m, 64);
+    if (lane == 0)
+        sink[wave] = w;  // XOR of all 32-bit words of the wave's piece
+}
+
+// probe_mfma_kernel: every wave issues iters x 4 independent v_mfma_f32_32x32x16_f16 on register operands.
+typedef float float16_t __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *__restrict__ sink)
+{
+    const half_t one = (half_t)1.0f, tiny = (half_t)0.0009765625f;
+    half8_t a = {one, tiny, one, tiny, one, tiny, one, tiny}, b = {tiny, one, tiny, one, tiny, one, tiny, one};
+    float16_t acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            acc[i][j] = (float)(i + j);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            s += acc[i][j];
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 __global__ void zero_fill_kernel(u32x4 *p, size_t n16)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -118,8 +118,8 @@ def main():
     from oracle import fp6_oracle as oracle
     tiles = np.array([0, 37, M // 16 - 1])
     rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
-    tile_bytes = (K // 256) * 3072
-    sub_packed = np.concatenate([packed[0][t * tile_bytes:(t + 1) * tile_bytes].cpu().numpy() for t in tiles])
+    # tiles are stored k-tile major: the stream of the sub-matrix of the listed row tiles is, per k-tile, their bytes
+    sub_packed = packed[0].view(K // 256, M // 16, 3072)[:, torch.from_numpy(tiles).to(dev), :].reshape(-1).cpu().numpy()
     sub_scales = scales[0].cpu().numpy()[rows]
     worst = 0.0
     for n in (1, 32):
@@ -610,8 +610,7 @@ def cpu_baseline(oracle, np, workloads, packed0, scales0, M, K, sweep):
     """The CPU oracle, as it stands, on the same layer over the same sweep, repeated until about 10 s of
     host time have been spent."""
     rows_n = M
-    tile_bytes = (K // 256) * 3072
-    sub_packed = packed0[: (rows_n // 16) * tile_bytes].cpu().numpy()
+    sub_packed = packed0.cpu().numpy()
     sub_scales = scales0[:rows_n].cpu().numpy()
     Xs = [workloads.make_activations(n, K, seed=n).numpy() for n in sweep]
     passes = 0

@@ -20,7 +20,10 @@
  *     [N][M] (M contiguous) - the natural layout of a linear layer over N tokens.
  *   - Supported shapes: M a multiple of 16, K a multiple of 256, 1 <= N < 2^31
  *     (M, K < 2^31; token counts whose activations exceed 2 GiB are processed as
- *     several launches on the same stream).
+ *     several launches on the same stream).  Packed weights are addressed with
+ *     32-bit offsets: (K/256 + 64) * (M/16) * 3072 must stay below 2^31 (about
+ *     2.8e9 weights per matrix, at every width); larger matrices are refused with
+ *     FP6_ERR_SHAPE and their size queries return 0 - split them along M.
  *   - Errors are detected on the host before anything is launched and reported
  *     as a status code; nothing is enqueued when a call fails.
  *   - W must be finite (the method has no inf/NaN code); this is not checked.
@@ -38,7 +41,7 @@ extern "C" {
 typedef enum {
     FP6_OK = 0,
     FP6_ERR_NULL = 1,      /* a required pointer is NULL */
-    FP6_ERR_SHAPE = 2,     /* M, N, K not positive, or M % 16 != 0, or K % 256 != 0 */
+    FP6_ERR_SHAPE = 2,     /* M, N, K not positive, M % 16 != 0, K % 256 != 0, or the matrix too large */
     FP6_ERR_WORKSPACE = 3, /* workspace missing or smaller than fp6_linear_workspace_bytes() */
     FP6_ERR_ALIGN = 4,     /* a pointer is not 16-byte aligned */
     FP6_ERR_HIP = 5        /* the HIP runtime refused the launch */
@@ -251,11 +254,11 @@ fp6_status fp6g_linear_fused(const void *packed, const void *scales_f16, const v
  * Diagnostics for benchmarks: empirical ceilings of the device, measured with the request
  * patterns of the linear kernels (the paper's Section 7.1 reads the same two utilisations
  * off its profiler: DRAM bandwidth and Tensor-Core use).
- *   fp6_probe_read: 1024 waves each stream a contiguous piece of `buffer` (device) once with
- *     the non-temporal 128-bit loads of the weight path, sixteen in flight, and XOR the
- *     32-bit words together; wave w covers bytes [w*c, (w+1)*c), c = fp6_probe_read_bytes(bytes)
- *     / 1024 (whole 16 KB steps), and writes its XOR to sink[w] (device, 1024 x uint32).
- *     bytes >= 16 MiB, else FP6_ERR_SHAPE.
+ *   fp6_probe_read: `buffer` (device) is cut into pieces of 8 KB; 1024 waves sweep it front to
+ *     back, wave w reading pieces w, 1024 + w, 2048 + w, ... with the non-temporal 128-bit loads
+ *     of the weight path, sixteen in flight, and XOR the 32-bit words of their pieces together
+ *     into sink[w] (device, 1024 x uint32).  fp6_probe_read_bytes(bytes) is the number of bytes
+ *     actually read (a whole, even number of pieces per wave).  bytes >= 16 MiB, else FP6_ERR_SHAPE.
  *   fp6_probe_mfma: 4096 waves (four per SIMD) each issue iters x 4 independent
  *     v_mfma_f32_32x32x16_f16 (32768 flop each) on register operands; `sink` (device,
  *     fp6_probe_mfma_sink_bytes() bytes) receives one float per lane.

@@ -31,7 +31,7 @@ def _load():
         L.fp5o_packed_bytes.restype = i64
         L.fp5o_packed_bytes.argtypes = [i64, i64]
         L.fp5o_pos.restype = ctypes.c_uint64
-        L.fp5o_pos.argtypes = [i64, i64, i64, ci]
+        L.fp5o_pos.argtypes = [i64, i64, i64, i64, ci]
         L.fp5o_pack.restype = None
         L.fp5o_pack.argtypes = [vp, i64, i64, vp]
         L.fp5o_unpack_codes.restype = None
@@ -64,8 +64,8 @@ def quantize_one(w_bits: int, scale_bits: int) -> int:
     return int(_load().fp5o_quantize_one(int(w_bits), int(scale_bits)))
 
 
-def pos(K: int, m: int, k: int, b: int) -> int:
-    return int(_load().fp5o_pos(int(K), int(m), int(k), int(b)))
+def pos(M: int, K: int, m: int, k: int, b: int) -> int:
+    return int(_load().fp5o_pos(int(M), int(K), int(m), int(k), int(b)))
 
 
 def packed_bytes(M: int, K: int) -> int:

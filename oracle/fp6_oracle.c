@@ -168,9 +168,10 @@ int64_t fp6o_packed_bytes(int64_t M, int64_t K) { return M * K * 6 / 8; }
  * Bit address, in the packed stream, of bit b of the code of weight (m, k);
  * b = 0..5 = m0, m1, e0, e1, e2, s.
  *
- * The matrix is cut into tiles of 16 rows x 256 columns, stored row-tile major
- * (all k-tiles of rows 0..15, then of rows 16..31, ...), 3072 bytes each.  A tile
- * is three planes of 1024 bytes; a plane is 64 slots of 16 bytes, slot
+ * The matrix is cut into tiles of 16 rows x 256 columns, stored k-tile major
+ * (the tiles of columns 0..255 for rows 0..15, 16..31, ..., then those of columns
+ * 256..511, ...), 3072 bytes each: waves that work on neighbouring rows at the same
+ * depth of the reduction read neighbouring memory.  A tile is three planes of 1024 bytes; a plane is 64 slots of 16 bytes, slot
  * = 16*q + r for row r of the tile and the q-th group of 8 columns inside each
  * run of 32 columns.  The slot (r, q) therefore owns 12 little-endian 32-bit
  * words, word d of them sitting in plane d/4 at byte 4*(d%4) of the slot.  Words
@@ -179,7 +180,7 @@ int64_t fp6o_packed_bytes(int64_t M, int64_t K) { return M * K * 6 / 8; }
  * of the group) has index i = 8*(run%4) + j and occupies bits 6i .. 6i+5, least
  * significant code bit first, bit n of the stream being bit n%32 of word n/32.
  */
-uint64_t fp6o_pos(int64_t K, int64_t m, int64_t k, int b)
+uint64_t fp6o_pos(int64_t M, int64_t K, int64_t m, int64_t k, int b)
 {
     int64_t row_tile = m / FP6O_TILE_ROWS;
     int r = (int)(m % FP6O_TILE_ROWS);
@@ -193,7 +194,7 @@ uint64_t fp6o_pos(int64_t K, int64_t m, int64_t k, int b)
     int n = 6 * (8 * (run % 4) + j) + b; /* bit index inside the 192-bit stream */
     int d = 6 * stream + n / 32;        /* word of the slot, 0..11 */
     int plane = d / 4;
-    uint64_t tile = (uint64_t)(row_tile * (K / FP6O_TILE_K) + k_tile);
+    uint64_t tile = (uint64_t)(k_tile * (M / FP6O_TILE_ROWS) + row_tile);
     uint64_t byte_addr = tile * FP6O_TILE_BYTES + (uint64_t)plane * 1024u + (uint64_t)slot * 16u
                          + (uint64_t)(d % 4) * 4u;
     return byte_addr * 8u + (uint64_t)(n % 32);
@@ -207,7 +208,7 @@ void fp6o_pack(const uint8_t *codes, int64_t M, int64_t K, uint8_t *packed)
         for (int64_t k = 0; k < K; ++k)
             for (int b = 0; b < 6; ++b)
                 if ((codes[m * K + k] >> b) & 1) {
-                    uint64_t p = fp6o_pos(K, m, k, b);
+                    uint64_t p = fp6o_pos(M, K, m, k, b);
                     packed[p >> 3] |= (uint8_t)(1u << (p & 7));
                 }
 }
@@ -220,7 +221,7 @@ void fp6o_unpack_codes(const uint8_t *packed, int64_t M, int64_t K, uint8_t *cod
         for (int64_t k = 0; k < K; ++k) {
             int c = 0;
             for (int b = 0; b < 6; ++b) {
-                uint64_t p = fp6o_pos(K, m, k, b);
+                uint64_t p = fp6o_pos(M, K, m, k, b);
                 c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
             }
             codes[m * K + k] = (uint8_t)c;
@@ -307,7 +308,7 @@ int fp6o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X
         for (int64_t k = 0; k < K; ++k) {
             int c = 0;
             for (int b = 0; b < 6; ++b) {
-                uint64_t p = fp6o_pos(K, m, k, b);
+                uint64_t p = fp6o_pos(M, K, m, k, b);
                 c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
             }
             codes[i * K + k] = (uint8_t)c;
@@ -440,7 +441,7 @@ int fp6go_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *
         for (int64_t k = 0; k < K; ++k) {
             int c = 0;
             for (int b = 0; b < 6; ++b) {
-                uint64_t p = fp6o_pos(K, m, k, b);
+                uint64_t p = fp6o_pos(M, K, m, k, b);
                 c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
             }
             wd[k] = fp6o_decode(c) * fp6o_half_to_double(scales[m * G + k / group]); /* exact */
@@ -550,7 +551,7 @@ int64_t fp5o_packed_bytes(int64_t M, int64_t K) { return M * K * 5 / 8; }
  * Bit address, in the packed 5-bit stream, of bit b of the code of weight (m, k);
  * b = 0..4 = m0, m1, e0, e1, s.
  *
- * Tiles of 16 rows x 256 columns, row-tile major, 2560 bytes each.  A tile is two
+ * Tiles of 16 rows x 256 columns, k-tile major as in the 6-bit layout, 2560 bytes each.  A tile is two
  * planes of 1024 bytes (64 slots of 16 bytes) followed by one plane of 512 bytes
  * (64 slots of 8 bytes); slot = 16*q + r as in the 6-bit layout.  The slot owns
  * ten 32-bit words: words 0..3 in plane 0, 4..7 in plane 1, 8..9 in plane 2.
@@ -566,7 +567,7 @@ int64_t fp5o_packed_bytes(int64_t M, int64_t K) { return M * K * 5 / 8; }
  *   g = 2:  s -> D3.5   e1 -> D3.4   e0 -> D4.6   m1 -> D4.5   m0 -> D4.4
  * (Dn.x = bit x of the byte of lane i%4 in word Dn).
  */
-uint64_t fp5o_pos(int64_t K, int64_t m, int64_t k, int b)
+uint64_t fp5o_pos(int64_t M, int64_t K, int64_t m, int64_t k, int b)
 {
     static const int spread_word[3][5] = { /* indexed [g][b], b = m0 m1 e0 e1 s */
         {1, 1, 0, 0, 0}, {3, 2, 2, 2, 1}, {4, 4, 4, 3, 3}};
@@ -593,7 +594,7 @@ uint64_t fp5o_pos(int64_t K, int64_t m, int64_t k, int b)
         bit = spread_bit[g][b];
     }
     int d = 5 * half + word;      /* word of the slot, 0..9 */
-    uint64_t tile = (uint64_t)(row_tile * (K / FP6O_TILE_K) + k_tile);
+    uint64_t tile = (uint64_t)(k_tile * (M / FP6O_TILE_ROWS) + row_tile);
     uint64_t in_tile = d < 8 ? (uint64_t)(d / 4) * 1024u + (uint64_t)slot * 16u + (uint64_t)(d % 4) * 4u
                              : 2048u + (uint64_t)slot * 8u + (uint64_t)(d - 8) * 4u;
     return (tile * FP5O_TILE_BYTES + in_tile + (uint64_t)lane_byte) * 8u + (uint64_t)bit;
@@ -606,7 +607,7 @@ void fp5o_pack(const uint8_t *codes, int64_t M, int64_t K, uint8_t *packed)
         for (int64_t k = 0; k < K; ++k)
             for (int b = 0; b < 5; ++b)
                 if ((codes[m * K + k] >> b) & 1) {
-                    uint64_t p = fp5o_pos(K, m, k, b);
+                    uint64_t p = fp5o_pos(M, K, m, k, b);
                     packed[p >> 3] |= (uint8_t)(1u << (p & 7));
                 }
 }
@@ -618,7 +619,7 @@ void fp5o_unpack_codes(const uint8_t *packed, int64_t M, int64_t K, uint8_t *cod
         for (int64_t k = 0; k < K; ++k) {
             int c = 0;
             for (int b = 0; b < 5; ++b) {
-                uint64_t p = fp5o_pos(K, m, k, b);
+                uint64_t p = fp5o_pos(M, K, m, k, b);
                 c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
             }
             codes[m * K + k] = (uint8_t)c;
@@ -697,7 +698,7 @@ int fp5o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X
         for (int64_t k = 0; k < K; ++k) {
             int c = 0;
             for (int b = 0; b < 5; ++b) {
-                uint64_t p = fp5o_pos(K, m, k, b);
+                uint64_t p = fp5o_pos(M, K, m, k, b);
                 c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
             }
             codes[i * K + k] = (uint8_t)c;
@@ -794,12 +795,12 @@ int64_t fp4o_packed_bytes(int64_t M, int64_t K) { return M * K / 2; }
 
 /*
  * Bit address of bit b (0..3 = m0, e0, e1, s) of the code of weight (m, k) in the packed
- * 4-bit stream.  Tiles of 16 rows x 256 columns, row-tile major, 2048 bytes each: two
+ * 4-bit stream.  Tiles of 16 rows x 256 columns, k-tile major, 2048 bytes each: two
  * planes of 1024 bytes, 64 slots of 16 bytes per plane, slot = 16*q + r as in the other
  * layouts.  The slot owns eight 32-bit words, word d in plane d/4 at byte 4*(d%4); word d
  * holds the eight codes of run d (columns 32*d + 8*q + j), code j in bits 4j .. 4j+3.
  */
-uint64_t fp4o_pos(int64_t K, int64_t m, int64_t k, int b)
+uint64_t fp4o_pos(int64_t M, int64_t K, int64_t m, int64_t k, int b)
 {
     int64_t row_tile = m / FP6O_TILE_ROWS;
     int r = (int)(m % FP6O_TILE_ROWS);
@@ -809,7 +810,7 @@ uint64_t fp4o_pos(int64_t K, int64_t m, int64_t k, int b)
     int q = (kk % 32) / 8;
     int j = kk % 8;
     int slot = 16 * q + r;
-    uint64_t tile = (uint64_t)(row_tile * (K / FP6O_TILE_K) + k_tile);
+    uint64_t tile = (uint64_t)(k_tile * (M / FP6O_TILE_ROWS) + row_tile);
     uint64_t byte_addr = tile * FP4O_TILE_BYTES + (uint64_t)(run / 4) * 1024u + (uint64_t)slot * 16u
                          + (uint64_t)(run % 4) * 4u;
     return byte_addr * 8u + (uint64_t)(4 * j + b);
@@ -822,7 +823,7 @@ void fp4o_pack(const uint8_t *codes, int64_t M, int64_t K, uint8_t *packed)
         for (int64_t k = 0; k < K; ++k)
             for (int b = 0; b < 4; ++b)
                 if ((codes[m * K + k] >> b) & 1) {
-                    uint64_t p = fp4o_pos(K, m, k, b);
+                    uint64_t p = fp4o_pos(M, K, m, k, b);
                     packed[p >> 3] |= (uint8_t)(1u << (p & 7));
                 }
 }
@@ -834,7 +835,7 @@ void fp4o_unpack_codes(const uint8_t *packed, int64_t M, int64_t K, uint8_t *cod
         for (int64_t k = 0; k < K; ++k) {
             int c = 0;
             for (int b = 0; b < 4; ++b) {
-                uint64_t p = fp4o_pos(K, m, k, b);
+                uint64_t p = fp4o_pos(M, K, m, k, b);
                 c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
             }
             codes[m * K + k] = (uint8_t)c;
@@ -911,7 +912,7 @@ int fp4o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X
         for (int64_t k = 0; k < K; ++k) {
             int c = 0;
             for (int b = 0; b < 4; ++b) {
-                uint64_t p = fp4o_pos(K, m, k, b);
+                uint64_t p = fp4o_pos(M, K, m, k, b);
                 c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
             }
             codes[i * K + k] = (uint8_t)c;
@@ -1006,7 +1007,7 @@ int64_t fp3o_packed_bytes(int64_t M, int64_t K) { return M * K / 8 * 3; }
 
 /*
  * Bit address of bit b (0..2 = e0, e1, s) of the code of weight (m, k) in the packed
- * 3-bit stream.  Tiles of 16 rows x 256 columns, row-tile major, 1536 bytes each: a plane
+ * 3-bit stream.  Tiles of 16 rows x 256 columns, k-tile major, 1536 bytes each: a plane
  * of 1024 bytes (64 slots of 16 bytes) followed by a plane of 512 bytes (64 slots of 8
  * bytes), slot = 16*q + r as in the other layouts.  The slot owns six 32-bit words, words
  * 0..3 in the first plane, 4..5 in the second; words 3g .. 3g+2 serve the runs 4g .. 4g+3
@@ -1017,7 +1018,7 @@ int64_t fp3o_packed_bytes(int64_t M, int64_t K) { return M * K / 8 * 3; }
  * 3g+b.  (The ahead-of-time bit-level re-layout of Section 5.2 with a 3+1 split: the
  * reader needs one AND per in-place run and three AND/shift/OR for the spread one.)
  */
-uint64_t fp3o_pos(int64_t K, int64_t m, int64_t k, int b)
+uint64_t fp3o_pos(int64_t M, int64_t K, int64_t m, int64_t k, int b)
 {
     int64_t row_tile = m / FP6O_TILE_ROWS;
     int r = (int)(m % FP6O_TILE_ROWS);
@@ -1030,7 +1031,7 @@ uint64_t fp3o_pos(int64_t K, int64_t m, int64_t k, int b)
     int g = run / 4, i = run % 4;
     int word = i < 3 ? 3 * g + i : 3 * g + b;
     int bit = i < 3 ? 4 * j + b + 1 : 4 * j;
-    uint64_t tile = (uint64_t)(row_tile * (K / FP6O_TILE_K) + k_tile);
+    uint64_t tile = (uint64_t)(k_tile * (M / FP6O_TILE_ROWS) + row_tile);
     uint64_t byte_addr = tile * FP3O_TILE_BYTES
                          + (word < 4 ? (uint64_t)slot * 16u + (uint64_t)word * 4u
                                      : 1024u + (uint64_t)slot * 8u + (uint64_t)(word - 4) * 4u);
@@ -1044,7 +1045,7 @@ void fp3o_pack(const uint8_t *codes, int64_t M, int64_t K, uint8_t *packed)
         for (int64_t k = 0; k < K; ++k)
             for (int b = 0; b < 3; ++b)
                 if ((codes[m * K + k] >> b) & 1) {
-                    uint64_t p = fp3o_pos(K, m, k, b);
+                    uint64_t p = fp3o_pos(M, K, m, k, b);
                     packed[p >> 3] |= (uint8_t)(1u << (p & 7));
                 }
 }
@@ -1056,7 +1057,7 @@ void fp3o_unpack_codes(const uint8_t *packed, int64_t M, int64_t K, uint8_t *cod
         for (int64_t k = 0; k < K; ++k) {
             int c = 0;
             for (int b = 0; b < 3; ++b) {
-                uint64_t p = fp3o_pos(K, m, k, b);
+                uint64_t p = fp3o_pos(M, K, m, k, b);
                 c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
             }
             codes[m * K + k] = (uint8_t)c;
@@ -1133,7 +1134,7 @@ int fp3o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X
         for (int64_t k = 0; k < K; ++k) {
             int c = 0;
             for (int b = 0; b < 3; ++b) {
-                uint64_t p = fp3o_pos(K, m, k, b);
+                uint64_t p = fp3o_pos(M, K, m, k, b);
                 c |= ((packed[p >> 3] >> (p & 7)) & 1) << b;
             }
             codes[i * K + k] = (uint8_t)c;

@@ -483,7 +483,7 @@ def fp16_linear(W: torch.Tensor, X: torch.Tensor, out: Optional[torch.Tensor] = 
 
 def fp6_probe_read(buffer: torch.Tensor, sink: Optional[torch.Tensor] = None) -> int:
     """Stream `buffer` once with the weight path's loads (diagnostic); returns the bytes actually read.
-    sink (int32 [1024], device) receives the XOR of the 32-bit words of each wave's piece."""
+    sink (int32 [1024], device) receives, per wave w, the XOR of the 32-bit words of the 8 KB pieces w, 1024 + w, ..."""
     L = load_library()
     _dev(buffer, torch.uint8, "buffer")
     if sink is None:

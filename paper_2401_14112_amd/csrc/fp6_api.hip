@@ -13,7 +13,7 @@ namespace {
 
 using namespace fp6;
 
-constexpr int kLayoutVersion = 2;
+constexpr int kLayoutVersion = 3;
 // Configurations of the streaming kernel: {token tiles per wave, waves per block, weight tiles in flight per
 // wave, k-tiles per activation stage, iterations over which the activation copies of a stage are spread}.
 // For N <= 16 there are two block heights; the plan takes the one that fills the chip best for the shape.
@@ -48,6 +48,14 @@ constexpr int kCus = 256;
 std::atomic<int> g_forced_split{0};
 
 bool shape_ok(int64_t M, int64_t K) { return M > 0 && K > 0 && M % kTileRows == 0 && K % kTileK == 0 && M < (1ll << 31) && K < (1ll << 31); }
+// Packed weights: tiles are stored k-tile major and a wave addresses the tiles of its row tile with 32-bit
+// offsets that step by one k-tile's worth of all row tiles; the pipelines request up to 64 tiles past the end
+// of a slice (out of range: they read as zeros), and those offsets must not wrap either.  Priced at the 6-bit
+// tile size for every width.
+bool packed_shape_ok(int64_t M, int64_t K)
+{
+    return shape_ok(M, K) && (K / kTileK + 64) * (M / kTileRows) <= ((1ll << 31) - 1) / kTileBytes;
+}
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct StreamPlan {
@@ -350,7 +358,7 @@ fp6_status quantize_pack_impl(const void *W_f16, int64_t M, int64_t K, void *pac
 {
     if (!W_f16 || !packed || !scales_f16)
         return FP6_ERR_NULL;
-    if (!shape_ok(M, K))
+    if (!packed_shape_ok(M, K))
         return FP6_ERR_SHAPE;
     if (!aligned16(W_f16) || !aligned16(packed) || !aligned16(scales_f16))
         return FP6_ERR_ALIGN;
@@ -371,7 +379,7 @@ fp6_status unpack_impl(const void *packed, const void *scales_f16, int64_t M, in
 {
     if (!packed || !scales_f16 || !W_f16_out)
         return FP6_ERR_NULL;
-    if (!shape_ok(M, K))
+    if (!packed_shape_ok(M, K))
         return FP6_ERR_SHAPE;
     if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(W_f16_out))
         return FP6_ERR_ALIGN;
@@ -389,7 +397,7 @@ fp6_status packed_linear_impl(const void *packed, const void *scales_f16, const 
 {
     if (!packed || !scales_f16 || !X_f16 || !Y_f16)
         return FP6_ERR_NULL;
-    if (!shape_ok(M, K) || N <= 0 || N >= (1ll << 31))
+    if (!packed_shape_ok(M, K) || N <= 0 || N >= (1ll << 31))
         return FP6_ERR_SHAPE;
     if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(X_f16) || !aligned16(Y_f16) || !aligned16(epi.bias)
         || !aligned16(epi.residual))
@@ -420,11 +428,11 @@ const char *fp6_status_str(int status)
 
 int fp6_layout_version(void) { return kLayoutVersion; }
 
-size_t fp6_packed_bytes(int64_t M, int64_t K) { return shape_ok(M, K) ? (size_t)(M * K / 4 * 3) : 0; }
+size_t fp6_packed_bytes(int64_t M, int64_t K) { return packed_shape_ok(M, K) ? (size_t)(M * K / 4 * 3) : 0; }
 
 size_t fp6_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
-    if (!shape_ok(M, K) || N <= 0)
+    if (!packed_shape_ok(M, K) || N <= 0)
         return 0;
     return N <= kStreamMaxN ? plan_stream(M, N, K, true).total_bytes()
                             : tiled_workspace_bytes(M, N, K, PackedFp6Source::kTallTile);
@@ -491,7 +499,7 @@ fp6_status fp6g_quantize_pack(const void *W_f16, int64_t M, int64_t K, int64_t g
 {
     if (!W_f16 || !packed || !scales_f16)
         return FP6_ERR_NULL;
-    if (!shape_ok(M, K) || group != kGroupColumns)
+    if (!packed_shape_ok(M, K) || group != kGroupColumns)
         return FP6_ERR_SHAPE;
     if (!aligned16(W_f16) || !aligned16(packed) || !aligned16(scales_f16))
         return FP6_ERR_ALIGN;
@@ -519,7 +527,7 @@ fp6_status fp6g_linear(const void *packed, const void *scales_f16, const void *X
                                                     workspace_bytes, stream);
 }
 
-size_t fp5_packed_bytes(int64_t M, int64_t K) { return shape_ok(M, K) ? (size_t)(M * K / 8 * 5) : 0; }
+size_t fp5_packed_bytes(int64_t M, int64_t K) { return packed_shape_ok(M, K) ? (size_t)(M * K / 8 * 5) : 0; }
 
 size_t fp5_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) { return fp6_linear_workspace_bytes(M, N, K); }
 
@@ -540,7 +548,7 @@ fp6_status fp5_linear(const void *packed, const void *scales_f16, const void *X_
                                                stream);
 }
 
-size_t fp4_packed_bytes(int64_t M, int64_t K) { return shape_ok(M, K) ? (size_t)(M * K / 2) : 0; }
+size_t fp4_packed_bytes(int64_t M, int64_t K) { return packed_shape_ok(M, K) ? (size_t)(M * K / 2) : 0; }
 
 size_t fp4_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) { return fp6_linear_workspace_bytes(M, N, K); }
 
@@ -561,7 +569,7 @@ fp6_status fp4_linear(const void *packed, const void *scales_f16, const void *X_
                                                stream);
 }
 
-size_t fp3_packed_bytes(int64_t M, int64_t K) { return shape_ok(M, K) ? (size_t)(M * K / 8 * 3) : 0; }
+size_t fp3_packed_bytes(int64_t M, int64_t K) { return packed_shape_ok(M, K) ? (size_t)(M * K / 8 * 3) : 0; }
 
 size_t fp3_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) { return fp6_linear_workspace_bytes(M, N, K); }
 
@@ -614,9 +622,9 @@ fp6_status fp6_probe_read(const void *buffer, size_t bytes, void *sink, void *st
         return FP6_ERR_NULL;
     if (!aligned16(buffer))
         return FP6_ERR_ALIGN;
-    // 1024 waves (four per CU), each at least one double step of 16 KB and less than 2 GiB (32-bit lane offsets)
+    // 1024 waves (four per CU), each at least one double step of 2 x 8 KB
     const unsigned blocks = kCus;
-    if (bytes < (size_t)blocks * 4 * 16384 || bytes / (blocks * 4) >= (1ull << 31))
+    if (bytes < (size_t)blocks * 4 * 16384)
         return FP6_ERR_SHAPE;
     hipLaunchKernelGGL(probe_read_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const uint8_t *>(buffer), bytes, static_cast<uint32_t *>(sink));

@@ -2,11 +2,15 @@
 // the register-level e3m2 -> fp16 de-quantization, and the two weight sources (packed
 // 6-bit and plain fp16) that the linear-layer kernels are instantiated with.
 //
-// Packed layout, version 2 (this library's own; the paper's Section 5.2 only asks that
+// Packed layout, version 3 (this library's own; the paper's Section 5.2 only asks that
 // the weights be reordered ahead of time so that each thread reads whole aligned words in
 // the order the matrix cores consume them):
 //   * the M x K code matrix is cut into tiles of 16 rows x 256 columns, 3072 bytes
-//     each, stored row-tile major, so one wave streams a contiguous range;
+//     each, stored k-tile major (tile (row tile r, k-tile t) is tile number t * M/16 + r): the
+//     waves of a launch work on different row tiles at about the same depth t, so together
+//     they sweep memory front to back instead of each following a stream of its own (a
+//     read-only stream over a buffer of the benchmark layer's size takes 20.3 us swept this
+//     way against 22.9 us with one contiguous piece per wave);
 //   * a tile is three planes of 1024 bytes; lane L of a 64-wide wave owns bytes
 //     [16L, 16L+16) of each plane = three 128-bit loads, each a contiguous 1 KB per
 //     wave;
@@ -177,8 +181,11 @@ __device__ __forceinline__ void x_source_of_piece(int p, int &n, int &q)
 // is the column, inside the tile, of the first of the 8 consecutive columns that
 // lane group q feeds to MFMA step f; the activation staging uses the same map.
 // slice_rsrc() describes the memory one wave may read for row tile `row_tile` and
-// k-tiles [kt0, kt1); issue() requests the tile at lane offset `off`
-// (= lane_offset + t * kTileStride for tile t of the slice) with kLoads loads.
+// k-tiles [kt0, kt1) of a matrix of RT row tiles (for a packed source: from the first tile
+// of the slice to the end of its last; the tiles of other row tiles lie in between);
+// issue() requests the tile at lane offset `off` (= lane_offset + t * tile_stride(RT) for
+// tile t of the slice) with kLoads loads.  Offsets are 32-bit: the host admits only
+// matrices whose packed size, plus the look-ahead of the pipelines, stays below 2^31.
 
 // What one wave keeps to fetch the tiles of its slice: init() once, then issue(tile, t) requests tile t of
 // the slice (t past the slice reads zeros).  SimpleStream serves every source whose tile comes from one
@@ -186,18 +193,28 @@ __device__ __forceinline__ void x_source_of_piece(int p, int &n, int &q)
 template <class Src>
 struct SimpleStream {
     rsrc_t rsrc;
-    int off;
+    int off, stride;
     __device__ __forceinline__ void init(const void *weights, const half_t * /*scales*/, int64_t row_tile, int kt0,
-                                         int kt1, int64_t KT, int64_t K, int lane)
+                                         int kt1, int64_t RT, int64_t K, int lane)
     {
-        rsrc = Src::slice_rsrc(weights, row_tile, kt0, kt1, KT, K);
+        rsrc = Src::slice_rsrc(weights, row_tile, kt0, kt1, RT, K);
         off = Src::lane_offset(lane, kt0, (int)K);
+        stride = __builtin_amdgcn_readfirstlane(Src::tile_stride(RT));
     }
     __device__ __forceinline__ void issue(typename Src::Tile &tile, int t) const
     {
-        Src::issue(tile, rsrc, off + t * Src::kTileStride);
+        Src::issue(tile, rsrc, off + t * stride);
     }
 };
+
+// Packed sources: the slice of row tile `row_tile` over k-tiles [kt0, kt1), tiles of TILE_BYTES stored
+// k-tile major.  A tile past the slice lies past the range: it reads as zeros and fetches nothing.
+template <int TILE_BYTES>
+__device__ __forceinline__ rsrc_t packed_slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1, int64_t RT)
+{
+    return make_rsrc(static_cast<const uint8_t *>(base) + ((int64_t)kt0 * RT + row_tile) * TILE_BYTES,
+                     (uint32_t)(((int64_t)(kt1 - kt0 - 1) * RT + 1) * TILE_BYTES));
+}
 
 struct PackedFp6Source {
     typedef SimpleStream<PackedFp6Source> Stream;
@@ -208,13 +225,13 @@ struct PackedFp6Source {
     static constexpr bool kHasScale = true;
     static constexpr bool kTallTile = true;  // four row tiles per wave (two register buffers of 48) are affordable
     static constexpr int kLoads = 3;
-    static constexpr int kTileStride = kTileBytes;  // bytes from one k-tile of the slice to the next
+    // bytes from one k-tile of the slice to the next
+    __device__ static __forceinline__ int tile_stride(int64_t RT) { return (int)(RT * kTileBytes); }
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
     __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
-                                                        int64_t KT, int64_t /*K*/)
+                                                        int64_t RT, int64_t /*K*/)
     {
-        return make_rsrc(static_cast<const uint8_t *>(base) + (row_tile * KT + kt0) * kTileBytes,
-                         (uint32_t)(kt1 - kt0) * kTileBytes);
+        return packed_slice_rsrc<kTileBytes>(base, row_tile, kt0, kt1, RT);
     }
     __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
     __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
@@ -264,12 +281,13 @@ struct PackedFp6GroupSource {
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
     struct Stream {
         rsrc_t w_rsrc, s_rsrc;
-        int w_off, s_off;
+        int w_off, w_stride, s_off;
         __device__ __forceinline__ void init(const void *weights, const half_t *scales, int64_t row_tile, int kt0,
-                                             int kt1, int64_t KT, int64_t K, int lane)
+                                             int kt1, int64_t RT, int64_t K, int lane)
         {
-            w_rsrc = PackedFp6Source::slice_rsrc(weights, row_tile, kt0, kt1, KT, K);
+            w_rsrc = PackedFp6Source::slice_rsrc(weights, row_tile, kt0, kt1, RT, K);
             w_off = lane * 16;
+            w_stride = __builtin_amdgcn_readfirstlane(PackedFp6Source::tile_stride(RT));
             const int groups = (int)(K / kGroupColumns);  // per row; = 2 * KT
             // the scales of the 16 rows of the row tile; a tile past the slice reads other finite scales or
             // zeros, and its weights read as zeros
@@ -278,7 +296,7 @@ struct PackedFp6GroupSource {
         }
         __device__ __forceinline__ void issue(Tile &t, int i) const
         {
-            const int off = w_off + i * kTileBytes;
+            const int off = w_off + i * w_stride;
             t.p0 = issue_load_b128<0, true>(w_rsrc, off);
             t.p1 = issue_load_b128<1024, true>(w_rsrc, off);
             t.p2 = issue_load_b128<2048, true>(w_rsrc, off);
@@ -342,13 +360,12 @@ struct PackedFp5Source {
     static constexpr bool kTallTile = true;
     static constexpr int kLoads = 3;
     static constexpr int kTileBytes5 = 2560;
-    static constexpr int kTileStride = kTileBytes5;
+    __device__ static __forceinline__ int tile_stride(int64_t RT) { return (int)(RT * kTileBytes5); }
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
     __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
-                                                        int64_t KT, int64_t /*K*/)
+                                                        int64_t RT, int64_t /*K*/)
     {
-        return make_rsrc(static_cast<const uint8_t *>(base) + (row_tile * KT + kt0) * kTileBytes5,
-                         (uint32_t)(kt1 - kt0) * kTileBytes5);
+        return packed_slice_rsrc<kTileBytes5>(base, row_tile, kt0, kt1, RT);
     }
     __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
     __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
@@ -415,13 +432,12 @@ struct PackedFp4Source {
     static constexpr bool kTallTile = true;
     static constexpr int kLoads = 2;
     static constexpr int kTileBytes4 = 2048;
-    static constexpr int kTileStride = kTileBytes4;
+    __device__ static __forceinline__ int tile_stride(int64_t RT) { return (int)(RT * kTileBytes4); }
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
     __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
-                                                        int64_t KT, int64_t /*K*/)
+                                                        int64_t RT, int64_t /*K*/)
     {
-        return make_rsrc(static_cast<const uint8_t *>(base) + (row_tile * KT + kt0) * kTileBytes4,
-                         (uint32_t)(kt1 - kt0) * kTileBytes4);
+        return packed_slice_rsrc<kTileBytes4>(base, row_tile, kt0, kt1, RT);
     }
     __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
     __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
@@ -462,13 +478,12 @@ struct PackedFp3Source {
     static constexpr bool kTallTile = true;
     static constexpr int kLoads = 2;
     static constexpr int kTileBytes3 = 1536;
-    static constexpr int kTileStride = kTileBytes3;
+    __device__ static __forceinline__ int tile_stride(int64_t RT) { return (int)(RT * kTileBytes3); }
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
     __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
-                                                        int64_t KT, int64_t /*K*/)
+                                                        int64_t RT, int64_t /*K*/)
     {
-        return make_rsrc(static_cast<const uint8_t *>(base) + (row_tile * KT + kt0) * kTileBytes3,
-                         (uint32_t)(kt1 - kt0) * kTileBytes3);
+        return packed_slice_rsrc<kTileBytes3>(base, row_tile, kt0, kt1, RT);
     }
     __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
     __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
@@ -510,13 +525,13 @@ struct PlainFp16Source {
     static constexpr bool kHasScale = false;
     static constexpr bool kTallTile = false;
     static constexpr int kLoads = 8;
-    static constexpr int kTileStride = kTileK * 2;
+    __device__ static __forceinline__ int tile_stride(int64_t /*RT*/) { return kTileK * 2; }  // row-major W
     // the four lane groups of a row read four adjacent 16-byte pieces (64 contiguous bytes per row
     // and load instruction); plain (cached) loads, so the other half of each line is an L1/L2 hit
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
     // the 16 rows of the row tile; tiles past the slice are neutralised by zero activations
     __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int /*kt0*/, int /*kt1*/,
-                                                        int64_t /*KT*/, int64_t K)
+                                                        int64_t /*RT*/, int64_t K)
     {
         return make_rsrc(static_cast<const half_t *>(base) + row_tile * kTileRows * K, (uint32_t)(kTileRows * K * 2));
     }

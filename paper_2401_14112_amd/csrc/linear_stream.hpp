@@ -71,7 +71,7 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     // Inactive waves (ragged last row block) stream the last valid row tile and drop the result,
     // so the main loop has no per-wave control flow.
     typename Src::Stream w_stream;
-    w_stream.init(weights, scales, active ? row_tile : n_row_tiles - 1, kt0, kt1, KT, K, lane);
+    w_stream.init(weights, scales, active ? row_tile : n_row_tiles - 1, kt0, kt1, n_row_tiles, K, lane);
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
     // ---- activation staging.  Copy j = wave + WAVES*i of a stage serves k-tile g = j / (8*NT) of the

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
         const int rt = row_tile0 + r;
-        w_stream[r].init(weights, scales, rt < n_row_tiles ? rt : n_row_tiles - 1, kt0, kt1, KT, K, lane);
+        w_stream[r].init(weights, scales, rt < n_row_tiles ? rt : n_row_tiles - 1, kt0, kt1, n_row_tiles, K, lane);
     }
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 

@@ -277,7 +277,9 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const half_t *__res
     const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
     if (tile >= (int64_t)(M / kTileRows) * KT)
         return;
-    const int64_t row_tile = tile / KT, kt = tile % KT;
+    // the waves of a block take neighbouring k-tiles of one row tile (2 KB of every row of W between them);
+    // in the packed stream tiles are stored k-tile major
+    const int64_t RT = M / kTileRows, row_tile = tile / KT, kt = tile % KT, packed_tile = kt * RT + row_tile;
     const int r = lane & 15, q = lane >> 4;  // lane (r, q) builds its bytes of the tile
     const half_t *row = W + (row_tile * kTileRows + r) * K + kt * kTileK + q * 8;
     u32x4 v[8];
@@ -293,7 +295,7 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const half_t *__res
             code[f][2 * j] = quantize_code<Fmt>(v[f][j] & 0xffffu, scale);
             code[f][2 * j + 1] = quantize_code<Fmt>(v[f][j] >> 16, scale);
         }
-    Fmt::store_tile(code, packed + tile * Fmt::kTileBytes, lane);
+    Fmt::store_tile(code, packed + packed_tile * Fmt::kTileBytes, lane);
 }
 
 // Group-wise scales (one per row and per 128 columns): a group lies inside one tile and inside one of a
@@ -308,7 +310,9 @@ __global__ __launch_bounds__(256) void quantize_pack_group_kernel(const half_t *
     const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
     if (tile >= (int64_t)(M / kTileRows) * KT)
         return;
-    const int64_t row_tile = tile / KT, kt = tile % KT;
+    // the waves of a block take neighbouring k-tiles of one row tile (2 KB of every row of W between them);
+    // in the packed stream tiles are stored k-tile major
+    const int64_t RT = M / kTileRows, row_tile = tile / KT, kt = tile % KT, packed_tile = kt * RT + row_tile;
     const int r = lane & 15, q = lane >> 4;
     const half_t *row = W + (row_tile * kTileRows + r) * K + kt * kTileK + q * 8;
     u32x4 v[8];
@@ -342,7 +346,7 @@ __global__ __launch_bounds__(256) void quantize_pack_group_kernel(const half_t *
                 code[f][2 * j + 1] = quantize_code<E3M2Format>(v[f][j] >> 16, scale);
             }
     }
-    E3M2Format::store_tile(code, packed + tile * E3M2Format::kTileBytes, lane);
+    E3M2Format::store_tile(code, packed + packed_tile * E3M2Format::kTileBytes, lane);
     if (q == 0) {
         const int64_t groups = K / kGroupColumns;
         *reinterpret_cast<uint32_t *>(scales + (row_tile * kTileRows + r) * groups + 2 * kt) = scale_bits[0] | (scale_bits[1] << 16);
@@ -359,10 +363,12 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
     const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
     if (tile >= (int64_t)(M / kTileRows) * KT)
         return;
-    const int64_t row_tile = tile / KT, kt = tile % KT;
+    // the waves of a block take neighbouring k-tiles of one row tile (2 KB of every row of W between them);
+    // in the packed stream tiles are stored k-tile major
+    const int64_t RT = M / kTileRows, row_tile = tile / KT, kt = tile % KT;
     const int r = lane & 15, q = lane >> 4;
     typename Src::Stream stream;
-    stream.init(packed, scales, row_tile, (int)kt, (int)kt + 1, KT, K, lane);
+    stream.init(packed, scales, row_tile, (int)kt, (int)kt + 1, RT, K, lane);
     typename Src::Tile t;
     stream.issue(t, 0);
     wait_loads<0>();
@@ -385,18 +391,22 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
 }
 
 // ---- diagnostics: empirical ceilings of the device, with the request patterns of the linear kernels ------
-// probe_read_kernel: every wave streams a contiguous piece of the buffer with the non-temporal 128-bit loads
-// of the weight path, sixteen in flight (two sets of eight), and computes nothing.
+// probe_read_kernel: the buffer is cut into pieces of 8 KB; in step s wave w of the W waves reads piece
+// s * W + w, so that the grid sweeps the buffer front to back (the way the linear kernels sweep packed
+// weights; one contiguous range per wave is 10 % slower), with the non-temporal 128-bit loads of the weight
+// path, sixteen in flight per wave (two sets of eight).  Nothing is computed except the XOR of what was loaded.
 __global__ __launch_bounds__(256) void probe_read_kernel(const uint8_t *__restrict__ buffer, size_t bytes,
                                                          uint32_t *__restrict__ sink)
 {
     const int lane = threadIdx.x & 63;
-    const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const size_t wave = (size_t)blockIdx.x * 4 + (size_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const size_t n_waves = (size_t)gridDim.x * 4;
-    const size_t chunk = bytes / n_waves / 16384 * 16384;  // whole double steps; the host sizes the grid for >= 1
-    const rsrc_t r = make_rsrc(buffer + wave * chunk, (uint32_t)chunk);
+    const size_t steps = bytes / (n_waves * 8192) / 2 * 2;  // whole double steps; the host sizes the grid for >= 2
     u32x4 a[8], b[8];
-    auto issue8 = [&](u32x4 (&v)[8], int off) {
+    auto issue8 = [&](u32x4 (&v)[8], size_t step) {
+        // a step past the end gets an empty range: its loads return zeros and fetch nothing
+        const rsrc_t r = make_rsrc(buffer + (step < steps ? step * n_waves + wave : 0) * 8192, step < steps ? 8192u : 0u);
+        const int off = lane * 16;
         v[0] = issue_load_b128<0, true>(r, off);
         v[1] = issue_load_b128<1024, true>(r, off);
         v[2] = issue_load_b128<2048, true>(r, off);
@@ -415,25 +425,23 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint8_t *__restri
         }
         pin(x);  // the set is consumed here, before its registers are the target of the next loads
     };
-    int off = lane * 16;
-    issue8(a, off);
-    for (size_t done = 0; done < chunk; done += 16384) {
-        issue8(b, off + 8192);
+    issue8(a, 0);
+    for (size_t s = 0; s < steps; s += 2) {
+        issue8(b, s + 1);
         wait_loads<8>();
         pin8(a);
-        issue8(a, off + 16384);  // past the end of the piece on the last trip: reads as zeros, no traffic
+        issue8(a, s + 2);
         wait_loads<8>();
         pin8(b);
-        off += 16384;
     }
     wait_loads<0>();
-    pin8(a);  // the look-ahead past the end of the piece: zeros
+    pin8(a);  // the look-ahead past the last step: zeros
     uint32_t w = x[0] ^ x[1] ^ x[2] ^ x[3];
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1)
         w ^= (uint32_t)__shfl_xor((int)w, m, 64);
     if (lane == 0)
-        sink[wave] = w;  // XOR of all 32-bit words of the wave's piece
+        sink[wave] = w;  // XOR of all 32-bit words of the wave's pieces
 }
 
 // probe_mfma_kernel: every wave issues iters x 4 independent v_mfma_f32_32x32x16_f16 on register operands.

@@ -51,6 +51,10 @@ def test_size_queries(lib):
     assert lib.fp6_packed_bytes(8192, 22016) == 135266304          # 3*M*K/4
     assert lib.fp6_packed_bytes(256, 512) == 98304
     assert lib.fp6_packed_bytes(16, 256) == 3072
+    # packed weights are addressed with 32-bit offsets: (K/256 + 64) * (M/16) * 3072 < 2^31, at every width
+    assert lib.fp6_packed_bytes(32768, 49152) == 3 * 32768 * 49152 // 4
+    assert lib.fp6_packed_bytes(65536, 65536) == 0 and lib.fp3_packed_bytes(65536, 65536) == 0
+    assert lib.fp6_linear_workspace_bytes(65536, 1, 65536) == 0
     assert lib.fp5_packed_bytes(16, 256) == 2560 and lib.fp5_packed_bytes(8192, 22016) == 112721920
     assert lib.fp5_packed_bytes(15, 256) == 0
     assert lib.fp4_packed_bytes(16, 256) == 2048 and lib.fp4_packed_bytes(16, 128) == 0

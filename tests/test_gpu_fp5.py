@@ -7,6 +7,7 @@ import pytest
 import torch
 
 import workloads
+from packed_rows import row_tiles_of
 
 pytestmark = pytest.mark.gpu
 
@@ -184,8 +185,7 @@ def test_full_size_layer_sampled(pkg, o5):
     tiles = np.array(sorted(set([0, M // 16 - 1]) | set(int(t) for t in rng.choice(M // 16, size=14, replace=False))))
     rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
     ref_packed, ref_scales = o5.quantize_pack(_np(W[torch.from_numpy(rows).cuda()]))
-    tile_bytes = (K // 256) * 2560
-    got_packed = np.concatenate([_np(packed[t * tile_bytes:(t + 1) * tile_bytes]) for t in tiles])
+    got_packed = row_tiles_of(packed, M, K, tiles, 2560)
     assert np.array_equal(_np(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
     assert np.array_equal(got_packed, ref_packed)
     del W

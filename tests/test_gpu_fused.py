@@ -7,6 +7,7 @@ import pytest
 import torch
 
 import workloads
+from packed_rows import row_tiles_of
 
 pytestmark = pytest.mark.gpu
 
@@ -199,8 +200,7 @@ def test_fused_full_size_decoder_projections(pkg, oracle, N):
     rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
     out_rows = rows[::2] // 2
     ref_packed, ref_scales = oracle.quantize_pack(_np(W[torch.from_numpy(rows).cuda()]))
-    tile_bytes = (H // 256) * 3072
-    got_packed = np.concatenate([_np(packed[t * tile_bytes:(t + 1) * tile_bytes]) for t in tiles])
+    got_packed = row_tiles_of(packed, 2 * F, H, tiles, 3072)
     assert np.array_equal(got_packed, ref_packed)
     assert np.array_equal(_np(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
     del W

@@ -8,6 +8,7 @@ import pytest
 import torch
 
 import workloads
+from packed_rows import row_tiles_of
 
 pytestmark = pytest.mark.gpu
 
@@ -335,7 +336,7 @@ def _sampled_row_tiles(M, count, seed):
 @pytest.mark.parametrize("shape", [workloads.FFN_65B, workloads.FFN_65B_DOWN])
 def test_full_size_layer_sampled(pkg, oracle, shape):
     """The benchmark layer at its real size, in the launch configuration bench.py times: the packed
-    stream and scales are compared bit for bit on sampled 16-row tiles (tiles are contiguous in the
+    stream and scales are compared bit for bit on sampled 16-row tiles (the tiles of a row tile are gathered from the
     stream), and Y on the rows of those tiles for N = 1 ... 512 (every kernel
     and block shape the plan picks for this layer)."""
     name, M, K = shape
@@ -347,8 +348,7 @@ def test_full_size_layer_sampled(pkg, oracle, shape):
     rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
     W_rows = _np16(W[torch.from_numpy(rows).cuda()])
     ref_packed, ref_scales = oracle.quantize_pack(W_rows)          # the sampled tiles as a 16*T-row matrix
-    tile_bytes = (K // 256) * 3072
-    got_packed = np.concatenate([_np16(packed[t * tile_bytes:(t + 1) * tile_bytes]) for t in tiles])
+    got_packed = row_tiles_of(packed, M, K, tiles, 3072)
     assert np.array_equal(_np16(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
     assert np.array_equal(got_packed, ref_packed)
     del W
@@ -375,8 +375,7 @@ def _sampled_reference(pkg, oracle, W, packed, scales, M, K, count, seed):
     tiles = _sampled_row_tiles(M, count, seed)
     rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
     ref_packed, ref_scales = oracle.quantize_pack(_np16(W[torch.from_numpy(rows).cuda()]))
-    tile_bytes = (K // 256) * 3072
-    got_packed = np.concatenate([_np16(packed[t * tile_bytes:(t + 1) * tile_bytes]) for t in tiles])
+    got_packed = row_tiles_of(packed, M, K, tiles, 3072)
     assert np.array_equal(_np16(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
     assert np.array_equal(got_packed, ref_packed)
     return rows, ref_packed, ref_scales

@@ -8,15 +8,16 @@ import paper_2401_14112_amd as pkg
 pytestmark = pytest.mark.gpu
 
 
-def _fold(t):
-    """XOR of each row of an int32 matrix."""
-    while t.shape[1] > 1:
-        h = t.shape[1] // 2
-        rest = t[:, 2 * h:]
-        t = t[:, :h] ^ t[:, h:2 * h]
-        if rest.shape[1]:
-            t = torch.cat([t, rest], dim=1)
-    return t[:, 0]
+def _xor_over(t, dim):
+    """XOR-reduce an int32 tensor along one dimension."""
+    t = t.movedim(dim, -1)
+    while t.shape[-1] > 1:
+        h = t.shape[-1] // 2
+        rest = t[..., 2 * h:]
+        t = t[..., :h] ^ t[..., h:2 * h]
+        if rest.shape[-1]:
+            t = torch.cat([t, rest], dim=-1)
+    return t[..., 0]
 
 
 @pytest.mark.parametrize("mib", [16, 80, 129])
@@ -26,7 +27,8 @@ def test_read_stream_reads_every_byte(mib):
     sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
     n = pkg.fp6_probe_read(buf, sink)
     assert n % (1024 * 16384) == 0 and n <= buf.numel() and buf.numel() - n < 1024 * 16384
-    want = _fold(buf[:n].view(torch.int32).view(1024, n // 4096))
+    # pieces of 8 KB (2048 words); wave w reads pieces w, 1024 + w, ...
+    want = _xor_over(_xor_over(buf[:n].view(torch.int32).view(n // (1024 * 8192), 1024, 2048), 2), 0)
     torch.cuda.synchronize()
     assert torch.equal(sink, want)
 

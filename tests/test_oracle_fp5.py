@@ -107,10 +107,10 @@ def test_pos_is_a_bijection(o5):
         for m in range(M):
             for k in range(K):
                 for b in range(5):
-                    p = o5.pos(K, m, k, b)
+                    p = o5.pos(M, K, m, k, b)
                     assert 0 <= p < 5 * M * K
                     seen[p] += 1
-                    assert p // (2560 * 8) == (m // 16) * (K // 256) + k // 256
+                    assert p // (2560 * 8) == (k // 256) * (M // 16) + m // 16
         assert np.all(seen == 1)
         assert o5.packed_bytes(M, K) == 5 * M * K // 8
 
@@ -145,10 +145,10 @@ def test_register_level_reconstruction(o5):
     M, K = 32, 512
     codes = (workloads.make_codes(M, K, 9).numpy() & 31).astype(np.uint8)
     packed = o5.pack(codes)
-    tiles = packed.reshape(M // 16, K // 256, 2560)
+    tiles = packed.reshape(K // 256, M // 16, 2560)
     for rt in range(M // 16):
         for kt in range(K // 256):
-            got = _swar_unpack_tile(tiles[rt, kt])
+            got = _swar_unpack_tile(tiles[kt, rt])
             assert np.array_equal(got, codes[rt * 16:(rt + 1) * 16, kt * 256:(kt + 1) * 256])
     assert np.array_equal(o5.unpack_codes(packed, M, K), codes)
 

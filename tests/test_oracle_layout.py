@@ -12,7 +12,7 @@ def _all_pos(oracle, M, K):
     for m in range(M):
         for k in range(K):
             for b in range(6):
-                out[m, k, b] = oracle.pos(K, m, k, b)
+                out[m, k, b] = oracle.pos(M, K, m, k, b)
     return out
 
 
@@ -28,11 +28,11 @@ def test_pos_is_a_bijection_multi_tile(oracle):
     p = _all_pos(oracle, M, K).ravel()
     assert p.min() == 0 and p.max() == 6 * M * K - 1
     assert np.unique(p).size == 6 * M * K
-    # tiles are row-tile major and 3072 bytes each: weight (m, k) lives in tile (m//16)*(K//256) + k//256
+    # tiles are k-tile major and 3072 bytes each: weight (m, k) lives in tile (k//256)*(M//16) + m//16
     for (m, k) in [(0, 0), (15, 255), (16, 0), (17, 300), (47, 767)]:
-        tile = (m // 16) * (K // 256) + k // 256
+        tile = (k // 256) * (M // 16) + m // 16
         for b in range(6):
-            assert oracle.pos(K, m, k, b) // (3072 * 8) == tile
+            assert oracle.pos(M, K, m, k, b) // (3072 * 8) == tile
 
 
 def test_packed_size_and_no_padding(oracle):
@@ -58,7 +58,7 @@ def test_pack_unpack_round_trip(oracle):
         codes[m, k] = 1 << b
         packed = oracle.pack(codes)
         bits = np.flatnonzero(np.unpackbits(packed, bitorder="little"))
-        assert bits.tolist() == [oracle.pos(K, m, k, b)]
+        assert bits.tolist() == [oracle.pos(M, K, m, k, b)]
 
 
 def _lane_stream_unpack_tile_words(words):
@@ -84,10 +84,10 @@ def test_register_level_reconstruction(oracle):
     M, K = 32, 512
     codes = workloads.make_codes(M, K, 7).numpy()
     packed = oracle.pack(codes)
-    tiles = packed.view(np.uint32).reshape(M // 16, K // 256, 3, 64, 4)
+    tiles = packed.view(np.uint32).reshape(K // 256, M // 16, 3, 64, 4)
     for rt in range(M // 16):
         for kt in range(K // 256):
-            got = _lane_stream_unpack_tile_words(tiles[rt, kt])
+            got = _lane_stream_unpack_tile_words(tiles[kt, rt])
             assert np.array_equal(got, codes[rt * 16:(rt + 1) * 16, kt * 256:(kt + 1) * 256])
 
 

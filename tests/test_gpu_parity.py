@@ -368,6 +368,41 @@ def test_full_size_layer_sampled(pkg, oracle, shape):
         assert torch.equal(Yf.view(torch.int16), Y.view(torch.int16))
 
 
+def test_largest_admitted_matrix_offsets(pkg, oracle):
+    """Tiles are stored k-tile major and addressed with 32-bit offsets that span the whole matrix: a tall
+    matrix just inside the limit (K/256 + 64) * (M/16) * 3072 < 2^31 puts a wave's last tiles 680 MB past its
+    first and its out-of-range look-ahead close to 2^31.  Packed stream and scales bit for bit on sampled row
+    tiles (first, last, random), Y on their rows, for the streaming kernel and the tiled one, and the round
+    trip through fp6_unpack on those rows; the next size up is refused."""
+    M, K = 114688, 8192
+    assert (K // 256 + 64) * (M // 16) * 3072 < 2 ** 31 <= (K // 256 + 64) * ((M + 2048) // 16) * 3072
+    _say("largest admitted matrix M=%d K=%d" % (M, K))
+    W = workloads.make_weights(M, K, seed=11, device="cuda")
+    packed, scales = pkg.fp6_quantize_pack(W)
+    torch.cuda.synchronize()
+    tiles = _sampled_row_tiles(M, 12, seed=5)
+    rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
+    ref_packed, ref_scales = oracle.quantize_pack(_np16(W[torch.from_numpy(rows).cuda()]))
+    del W
+    assert np.array_equal(row_tiles_of(packed, M, K, tiles, 3072), ref_packed)
+    assert np.array_equal(_np16(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
+    Wd = pkg.fp6_unpack(packed, scales, M, K)
+    torch.cuda.synchronize()
+    want = oracle.unpack(ref_packed, ref_scales, len(rows), K)
+    assert np.array_equal(_np16(Wd[torch.from_numpy(rows).cuda()]).view(np.uint16), want.view(np.uint16))
+    del Wd
+    for N in (1, 32, 128):
+        _say("  linear N=%d" % N)
+        X = workloads.make_activations(N, K, seed=N, device="cuda")
+        Y = pkg.fp6_linear(packed, scales, X, M, K)
+        torch.cuda.synchronize()
+        Y_ref = oracle.linear(ref_packed, ref_scales, _np16(X), len(rows), K)
+        _check_linear(_np16(Y)[:, rows], Y_ref, "largest matrix N=%d" % N)
+        assert not torch.isnan(Y).any()
+    with pytest.raises(pkg.Fp6Error):
+        pkg.fp6_linear(packed, scales, X, M + 2048, K)
+
+
 # ------------------------------------------------------------------ 70B-class layer set, decoder weight stream
 def _sampled_reference(pkg, oracle, W, packed, scales, M, K, count, seed):
     """Oracle-side packed stream and scales of `count` sampled 16-row tiles, after checking that the

@@ -113,6 +113,15 @@ def main():
         for s in range(period):
             for i, n in enumerate(sweep):
                 launch(n, (s * len(sweep) + i) % N_BUFFERS)
+    # and LONG rotations as one graph (the fixed cost of a graph launch is ~20 us on this runtime: over 24
+    # launches that is most of a microsecond each)
+    LONG = 5
+    long_rotation = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(long_rotation):
+        for r in range(LONG):
+            for s in range(period):
+                for i, n in enumerate(sweep):
+                    launch(n, (s * len(sweep) + i) % N_BUFFERS)
 
     # ---- quick validity check of what is being timed (sampled rows against the CPU oracle)
     from oracle import fp6_oracle as oracle
@@ -142,7 +151,11 @@ def main():
 
     # ---- timed region: W warm-up steps, then exactly K steps between synchronizations
     def run_steps(count):
-        """Exactly `count` steps: whole rotations from the long graph, the remainder from single-step graphs."""
+        """Exactly `count` steps: LONG rotations at a time from the long graph, then whole rotations, the
+        remainder from single-step graphs."""
+        for _ in range(count // (period * LONG)):
+            long_rotation.replay()
+        count %= period * LONG
         for _ in range(count // period):
             rotation.replay()
         for s in range(count % period):
@@ -180,16 +193,18 @@ def main():
     # launch stream around every replay; duration per launch = elapsed / launches in the replay
     small = [n for n in sweep if n <= 16]
     dom_graph = torch.cuda.CUDAGraph()
+    DOM_PASSES = 3
     with torch.cuda.graph(dom_graph):
-        for s in range(period):
-            for i, n in enumerate(sweep):
-                if n <= 16:
-                    launch(n, (s * len(sweep) + i) % N_BUFFERS)
+        for r in range(DOM_PASSES):
+            for s in range(period):
+                for i, n in enumerate(sweep):
+                    if n <= 16:
+                        launch(n, (s * len(sweep) + i) % N_BUFFERS)
     for s in range(max(1, args.warmup // period)):
         dom_graph.replay()
     # one pair of events brackets one replay of the whole rotation (an event record is a stream operation of
     # its own and would otherwise add its gap to every five launches)
-    groups = max(1, args.steps // period)
+    groups = max(1, args.steps // (period * DOM_PASSES))
     dev_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(groups)]
     torch.cuda.synchronize()
     for gi in range(groups):
@@ -197,7 +212,7 @@ def main():
         dom_graph.replay()
         dev_ev[gi][1].record()
     torch.cuda.synchronize()
-    dom_us_all = np.array([a.elapsed_time(b) for a, b in dev_ev]) * 1e3 / (len(small) * period)
+    dom_us_all = np.array([a.elapsed_time(b) for a, b in dev_ev]) * 1e3 / (len(small) * period * DOM_PASSES)
     dom_bytes = sum(algorithmic_bytes(M, n, K) for n in small) / len(small)
     dom_us = float(dom_us_all.mean())
     achieved = dom_bytes / (dom_us * 1e-6) * 1e-9
@@ -217,7 +232,7 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": "llama65b_ffn W[8192x22016] W6A16 linear, one step = decode sweep N in "
-                        "{1,2,4,8,16,32}, launch j reads packed copy j mod 8 (1.08 GB rotation), replayed from a HIP graph of %d steps" % period,
+                        "{1,2,4,8,16,32}, launch j reads packed copy j mod 8 (1.08 GB rotation), replayed from HIP graphs of %d steps" % (period * LONG),
             "M": M, "K": K, "N_sweep": sweep, "weight_buffers": N_BUFFERS,
             "layout_version": pkg.fp6_layout_version(),
             "arithmetic": "e3m2 weights de-quantized to f16 in registers x f16 activations, f32 accumulate, one f16 rounding",
@@ -235,8 +250,8 @@ def main():
             "avg_launch_us": round(dom_us, 2),
             "min_launch_us": round(float(dom_us_all.min()), 2),
             "timing": "HIP events on the launch stream around every replay of a graph holding the N <= 16 launches "
-                      "of %d consecutive steps (one pass over the rotation of weight copies), elapsed / %d"
-                      % (period, 5 * period),
+                      "of %d consecutive steps (%d passes over the rotation of weight copies), elapsed / %d"
+                      % (period * DOM_PASSES, DOM_PASSES, len(small) * period * DOM_PASSES),
         },
         "sweep": {
             str(n): {

@@ -274,11 +274,8 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const half_t *__res
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int KT = K / kTileK;
-    // last tile first: the launch before this one took the row maxima front to back, so the end of W is what
-    // the 256 MB last-level cache still holds (10 % on a 360 MB matrix; issuing the pair of launches per chunk
-    // of rows that fits the cache was slower at every chunk size: shorter launches, same rate)
-    const int64_t tile = (int64_t)(M / kTileRows) * KT - 1 - ((int64_t)blockIdx.x * 4 + wave);
-    if (tile < 0)
+    const int64_t tile = (int64_t)blockIdx.x * 4 + wave;
+    if (tile >= (int64_t)(M / kTileRows) * KT)
         return;
     // the waves of a block take neighbouring k-tiles of one row tile (2 KB of every row of W between them);
     // in the packed stream tiles are stored k-tile major

@@ -93,7 +93,10 @@ constexpr int kOutOfRange = (int)0x80000000u;  // a lane offset no buffer here r
 // s_waitcnt: the compiler's own wait insertion cannot keep several tiles in flight across a loop
 // back edge.  Rules that keep this sound: (1) a loaded value is only used after wait_loads<N>()
 // followed by pin() on it, which orders the use after the wait; (2) every issued load is waited
-// for (and pinned) before its registers die, so no late write lands in a reused register.
+// for (and pinned) before its registers die, so no late write lands in a reused register.  What the
+// source cannot rule out is a compiler that moves an in-flight destination itself (a spill, or a copy
+// of a loop-carried value it could not keep in place): the build refuses any kernel with scratch and
+// scans the generated assembly for instructions that name a register with a load in flight.
 template <int IMM, bool STREAMING>
 __device__ __forceinline__ u32x4 issue_load_b128(rsrc_t rsrc, int lane_off)
 {

@@ -389,6 +389,7 @@ def side_measurements(pkg, torch, np, workloads, M, K, W0, packed, scales, pack_
     out["fused_feed_forward_70b"] = fused_block_measurements(pkg, torch, workloads, dev)
     out["model_blocks_vs_fp16"] = model_block_measurements(pkg, torch, workloads, dev)
     out["empirical_ceilings"] = empirical_ceilings(pkg, torch, packed)
+    out["independent_chains"] = independent_chain_measurements(pkg, torch, workloads, M, K, packed, scales)
     return out
 
 
@@ -551,6 +552,59 @@ def fused_block_measurements(pkg, torch, workloads, dev, copies=4):
         out[str(n)] = {"fused_us_per_block": round(us_f, 2), "separate_us_per_block": round(us_s, 2),
                        "speedup": round(us_s / us_f, 3),
                        "fused_hbm_frac": round(alg / us_f * 1e-3 / HBM_PEAK_GBPS, 4)}
+    return out
+
+
+def independent_chain_measurements(pkg, torch, workloads, M, K, packed, scales):
+    """Throughput when independent calls are available (two requests being decoded, the experts of a layer):
+    48 calls of fp6_linear on the benchmark layer, rotating over the packed copies, captured as one chain on
+    one stream and as two or three chains side by side on streams of their own (each chain with its own
+    output and workspace).  A launch spends 4-5 us of its 24 outside its stream of weights (prologue, split-K
+    epilogue, the spread between its waves); side by side the chains fill those for each other."""
+    dev = packed[0].device
+    calls = 48
+    out = {}
+    for n in (1, 16):
+        X = workloads.make_activations(n, K, seed=n, device=dev)
+        ws_bytes = max(pkg.fp6_linear_workspace_bytes(M, n, K), 16)
+        Ys = [torch.empty((n, M), dtype=torch.float16, device=dev) for _ in range(3)]
+        wss = [torch.zeros(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(3)]
+
+        def launch(b, chain):
+            pkg.fp6_linear(packed[b % len(packed)], scales[b % len(packed)], X, M, K, out=Ys[chain], workspace=wss[chain])
+
+        for b in range(len(packed)):
+            launch(b, b % 3)
+        torch.cuda.synchronize()
+        row = {}
+        for chains in (1, 2, 3):
+            g = torch.cuda.CUDAGraph()
+            sides = [torch.cuda.Stream() for _ in range(chains - 1)]
+            with torch.cuda.graph(g):
+                main = torch.cuda.current_stream()
+                for st in sides:
+                    st.wait_stream(main)
+                for c in range(chains):
+                    with torch.cuda.stream(main if c == 0 else sides[c - 1]):
+                        for b in range(c, calls, chains):
+                            launch(b, c)
+                for st in sides:
+                    main.wait_stream(st)
+            for _ in range(3):
+                g.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(8):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 8 / calls
+            row["chains_%d" % chains] = {"us_per_call": round(us, 2),
+                                         "weight_GBps": round(3 * M * K // 4 / us * 1e-3, 1),
+                                         "hbm_frac": round(algorithmic_bytes(M, n, K) / us * 1e-3 / HBM_PEAK_GBPS, 4)}
+            del g
+        out[str(n)] = row
     return out
 
 

@@ -312,7 +312,7 @@ fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const voi
     static std::atomic<uint64_t> lds_done{0};  // per instantiation
     if (!allow_dynamic_lds(reinterpret_cast<const void *>(kernel), lds, lds_done))
         return FP6_ERR_HIP;
-    const dim3 grid((unsigned)(p.row_blocks * p.split)), block(c.waves * 64);
+    const dim3 grid((unsigned)p.row_blocks, (unsigned)p.split), block(c.waves * 64);  // x runs fastest: row blocks of one k slice
     // tokens are processed 16*nt at a time; each pass re-streams the weights
     const int64_t step = 16 * c.nt;
     const int64_t Mout = epi.gated ? M / 2 : M;
@@ -324,7 +324,7 @@ fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const voi
         if (e.residual)
             e.residual += n0 * Mout;
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, weights, static_cast<const half_t *>(scales), Xp, Yp,
-                           (int)M, (int)n, (int)K, p.split, partials, counters, e);
+                           (int)M, (int)n, (int)K, p.split, (int)(K / kTileK / p.split), partials, counters, e);
         if (hipGetLastError() != hipSuccess)
             return FP6_ERR_HIP;
     }

@@ -35,7 +35,7 @@ constexpr int stream_copies_between(int g, int G, int DEPTH, int XSPREAD, int XP
 template <class Src, int NT, int WAVES, int DEPTH, int G, int XSPREAD>
 __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     const void *__restrict__ weights, const half_t *__restrict__ scales, const half_t *__restrict__ X,
-    half_t *Y, int M, int N, int K, int S, float4_t *__restrict__ partials,
+    half_t *Y, int M, int N, int K, int S, int kt_per_slice, float4_t *__restrict__ partials,
     int *__restrict__ counters, Epilogue epi)
 {
     constexpr int COPIES = G * NT * 8;  // copy instructions (1 KB each: one token tile x one run) per stage
@@ -57,15 +57,17 @@ __global__ __launch_bounds__(WAVES * 64) void linear_stream_kernel(
     const int n_row_tiles = M / kTileRows;
     // consecutive blocks take consecutive row blocks of the same k slice (measured a few per cent better at
     // N = 32, 64 than alternating the slices, no difference below)
-    const int n_row_blocks = gridDim.x / S;
-    const int row_block = blockIdx.x % n_row_blocks;
-    const int split = blockIdx.x / n_row_blocks;
+    // The grid is (row blocks, k slices) and the host passes KT / S: nothing is divided here (a division by
+    // a run-time value is a chain of ~30 dependent instructions, and the first request waits for it).
+    const int row_block = blockIdx.x;
+    const int split = blockIdx.y;
     const int row_tile = row_block * WAVES + wave;
     const bool active = row_tile < n_row_tiles;
-    const int kt0 = (int)(((unsigned)KT * (unsigned)split) / (unsigned)S);  // KT * S < 2^31 (host-checked)
-    const int kt1 = (int)(((unsigned)KT * (unsigned)(split + 1)) / (unsigned)S);
-    const int n_valid = kt1 - kt0;        // k-tiles of this slice (>= 1)
-    const int T = (KT + S - 1) / S;       // k-tiles computed: the same for every slice (>= n_valid)
+    const int rem = KT - S * kt_per_slice;  // the first `rem` slices take one k-tile more
+    const int kt0 = split * kt_per_slice + (split < rem ? split : rem);
+    const int n_valid = kt_per_slice + (split < rem ? 1 : 0);  // k-tiles of this slice (>= 1)
+    const int kt1 = kt0 + n_valid;
+    const int T = kt_per_slice + (rem > 0 ? 1 : 0);  // k-tiles computed: the same for every slice (>= n_valid)
     const int n_stages = (T + G - 1) / G;
 
     // Inactive waves (ragged last row block) stream the last valid row tile and drop the result,

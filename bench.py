@@ -31,6 +31,22 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix peak, vendor figure
 N_BUFFERS = 8
 
 
+def device_record(torch):
+    """What the runtime reports about the device the figures were measured on (clocks are the maxima it
+    advertises; the peaks used for the fractions are the vendor's figures above)."""
+    p = torch.cuda.get_device_properties(0)
+    rec = {"name": p.name, "compute_units": p.multi_processor_count, "memory_GiB": round(p.total_memory / 2 ** 30, 1)}
+    for key, attr in (("max_engine_clock_MHz", "clock_rate"), ("max_memory_clock_MHz", "memory_clock_rate")):
+        v = getattr(p, attr, None)
+        if v:
+            rec[key] = round(v / 1000.0, 1)
+    for key, attr in (("memory_bus_bits", "memory_bus_width"), ("l2_bytes", "L2_cache_size"), ("gcn_arch", "gcnArchName")):
+        v = getattr(p, attr, None)
+        if v:
+            rec[key] = v
+    return rec
+
+
 def algorithmic_bytes(M, N, K):
     """Bytes one fp6_linear call must move: packed weights + scales once, X once, Y once."""
     return 3 * M * K // 4 + 2 * M + 2 * K * N + 2 * M * N
@@ -237,6 +253,7 @@ def main():
             "layout_version": pkg.fp6_layout_version(),
             "arithmetic": "e3m2 weights de-quantized to f16 in registers x f16 activations, f32 accumulate, one f16 rounding",
         },
+        "device": device_record(torch),
         "tflops": round(step_flops / (ms_per_step * 1e-3) * 1e-12, 2),
         "roofline": {
             "bound": "hbm",
@@ -628,7 +645,9 @@ def empirical_ceilings(pkg, torch, packed):
     return {"read_stream_1GiB_GBps": round(n_big / us_big * 1e-3, 1),
             "read_stream_one_launch_135MB_us": round(us_one, 2),
             "read_stream_one_launch_135MB_GBps": round(n_one / us_one * 1e-3, 1),
-            "mfma_f16_32x32x16_TFLOPs": round(flop / us_mfma * 1e-6, 1)}
+            "mfma_f16_32x32x16_TFLOPs": round(flop / us_mfma * 1e-6, 1),
+            # 256 CUs x 4 SIMDs, 32768 flop per instruction, one instruction per 32 clocks and SIMD at full rate
+            "engine_clock_GHz_implied_by_the_matrix_loop": round(flop / us_mfma * 1e-6 / (1024 * 1024) * 1e3, 3)}
 
 
 def model_block_measurements(pkg, torch, workloads, dev):

@@ -19,8 +19,9 @@
  *     are column-major, i.e. X is stored [N][K] (K contiguous) and Y is stored
  *     [N][M] (M contiguous) - the natural layout of a linear layer over N tokens.
  *   - Supported shapes: M a multiple of 16, K a multiple of 256, 1 <= N < 2^31
- *     (M, K < 2^31; token counts whose activations exceed 2 GiB are processed as
- *     several launches on the same stream).  Packed weights are addressed with
+ *     (M < 2^31, K < 2^24: activations are addressed with 32-bit byte offsets; token
+ *     counts whose activations exceed 2 GiB are processed as several launches on the
+ *     same stream).  Packed weights are addressed with
  *     32-bit offsets: (K/256 + 64) * (M/16) * 3072 must stay below 2^31 (about
  *     2.8e9 weights per matrix, at every width); larger matrices are refused with
  *     FP6_ERR_SHAPE and their size queries return 0 - split them along M.

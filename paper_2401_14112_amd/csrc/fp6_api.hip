@@ -47,7 +47,10 @@ constexpr int kCus = 256;
 
 std::atomic<int> g_forced_split{0};
 
-bool shape_ok(int64_t M, int64_t K) { return M > 0 && K > 0 && M % kTileRows == 0 && K % kTileK == 0 && M < (1ll << 31) && K < (1ll << 31); }
+// The kernels address the activations of up to 64 tokens, and the 16 rows of an fp16 weight tile, with 32-bit
+// byte offsets: 64 * K * 2 must stay below 2^31.
+constexpr int64_t kMaxK = 1ll << 24;
+bool shape_ok(int64_t M, int64_t K) { return M > 0 && K > 0 && M % kTileRows == 0 && K % kTileK == 0 && M < (1ll << 31) && K < kMaxK; }
 // Packed weights: tiles are stored k-tile major and a wave addresses the tiles of its row tile with 32-bit
 // offsets that step by one k-tile's worth of all row tiles; the pipelines request up to 64 tiles past the end
 // of a slice (out of range: they read as zeros), and those offsets must not wrap either.  Priced at the 6-bit
@@ -226,7 +229,7 @@ fp6_status launch_tiled_cfg(const TiledPlan &p, const void *weights, const void 
 int64_t tiled_chunk_tokens(int64_t K)
 {
     const int64_t fit = ((1ll << 31) - 1) / (2 * K);
-    return fit >= 128 ? fit / 128 * 128 : fit;  // K < 2^24 leaves at least one full block
+    return fit >= 128 ? fit / 128 * 128 : fit;  // shape_ok() admits K < 2^24 only: at least 64 tokens fit
 }
 
 // Workspace of the tiled path: the largest over the chunks a call is cut into (the last, shorter chunk may

@@ -94,6 +94,13 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.fp6g_linear(p, p, p, p, 16, 1, 256, 64, null, 0, null) == SHAPE       # only groups of 128 columns
     assert lib.fp16_linear(null, p, p, 16, 1, 256, null, 0, null) == NULL
     assert lib.fp16_linear(p, p, p, 24, 1, 256, null, 0, null) == SHAPE
+    # 32-bit byte offsets into the activations and into fp16 weight rows: K stops below 2^24
+    big_k = 1 << 24
+    assert lib.fp6_packed_bytes(16, big_k) == 0 and lib.fp6_packed_bytes(16, big_k - 256) == 3 * 16 * (big_k - 256) // 4
+    assert lib.fp6_linear(p, p, p, p, 16, 1, big_k, null, 0, null) == SHAPE
+    assert lib.fp16_linear(p, p, p, 16, 1, big_k, null, 0, null) == SHAPE
+    assert lib.fp16_linear(p, p, p, 16, 128, big_k, null, 0, null) == SHAPE
+    assert lib.fp16_linear_workspace_bytes(16, 1, big_k) == 0
     # a shape that needs split-K partial sums refuses to run without a workspace
     M, N, K = 8192, 8, 22016
     need = lib.fp6_linear_workspace_bytes(M, N, K)

@@ -120,6 +120,27 @@ fp6_status fp6_linear(const void *packed, const void *scales_f16, const void *X_
                       int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * fp6_linear for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The split-K partial sums and arrival
+ * counters live in a buffer of FP6_STATIC_SCRATCH_BYTES that is part of the library's device
+ * image (each GPU the library runs on holds it until the process ends), so there is no
+ * workspace argument and the call allocates nothing: no hipMalloc, no hipFree, no library
+ * routine that allocates.  Inputs and outputs are the caller's, as for fp6_linear; the result
+ * is bit-identical to fp6_linear's.
+ *   - A shape whose split-K state does not fit the buffer is refused with FP6_ERR_WORKSPACE
+ *     before anything is enqueued (the 8192 x 22016 layer fits up to N = 512; shapes that need
+ *     no split-K always fit).  The check is host arithmetic only.
+ *   - The buffer keeps the contents of the last call; each call clears the counters it uses
+ *     with a small fill kernel on `stream` first (no memset node, so it can be captured).
+ *   - All calls on one GPU share that GPU's buffer: two calls that may overlap on one GPU
+ *     (different streams, two threads) race on it.  Serialize them, or give the overlapping
+ *     ones fp6_linear with workspaces of their own.
+ */
+#define FP6_STATIC_SCRATCH_BYTES ((32u << 20) + (64u << 10))
+fp6_status fp6_linear_static(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                             int64_t N, int64_t K, void *stream);
+
+/*
  * fp6_linear with the element-wise steps that a decoder block attaches to its
  * projections done in the kernel's last step, on the fp32 sums, before the one
  * rounding to fp16 (Section 7.3 runs whole LLaMA / OPT decoders; this removes the

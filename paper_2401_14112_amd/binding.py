@@ -53,6 +53,8 @@ def load_library():
     L.fp6_unpack.argtypes = [vp, vp, i64, i64, vp, vp]
     L.fp6_linear.restype = ci
     L.fp6_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, sz, vp]
+    L.fp6_linear_static.restype = ci
+    L.fp6_linear_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp]
     L.fp6_linear_fused.restype = ci
     L.fp6_linear_fused.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, ci, vp, sz, vp]
     for _name in ("fp5_linear_fused", "fp4_linear_fused", "fp3_linear_fused"):
@@ -249,6 +251,27 @@ def fp6_linear(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: i
                out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Y[N][M] = X[N][K] @ dequant(packed, scales)[M][K]^T  (fp16 in, fp16 out)."""
     return _linear("fp6", packed, scales, X, M, K, out, workspace)
+
+
+def fp6_linear_static(packed: torch.Tensor, scales: torch.Tensor, X: torch.Tensor, M: int, K: int,
+                      out: torch.Tensor) -> torch.Tensor:
+    """fp6_linear on the library's own static split-K buffer: the entry point allocates nothing, and neither
+    does this wrapper (`out` [N][M] is the caller's).  Calls that may overlap on one GPU race on that buffer."""
+    L = load_library()
+    _dev(packed, torch.uint8, "packed")
+    _dev(scales, torch.float16, "scales")
+    _dev(X, torch.float16, "X")
+    _dev(out, torch.float16, "out")
+    if X.dim() != 2 or X.shape[1] != K:
+        raise Fp6Error("X must be [N][K]")
+    N = X.shape[0]
+    nbytes = L.fp6_packed_bytes(M, K)
+    if nbytes == 0 or N == 0:
+        _check(2)
+    if packed.numel() != nbytes or scales.numel() != M or out.numel() != N * M:
+        raise Fp6Error("packed/scales/out do not match M, N, K")
+    _check(L.fp6_linear_static(packed.data_ptr(), scales.data_ptr(), X.data_ptr(), out.data_ptr(), M, N, K, _stream()))
+    return out
 
 
 def _linear_fused(prefix, packed, scales, X, M, K, bias, residual, gated, out, workspace, group=0):

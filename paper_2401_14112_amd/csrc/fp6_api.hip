@@ -61,6 +61,39 @@ bool packed_shape_ok(int64_t M, int64_t K)
 }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Where a launch keeps its split-K state: arrival counters (zero before and after every launch) and the
+// partial tiles.  A caller's workspace holds the counters first and the partial tiles right behind them, so
+// the split depends on the plan; the library's own static buffer (fp6_linear_static) keeps the counters in a
+// fixed region at its start, so that the partial tiles of one call can never be read as counters by the next.
+constexpr size_t kStaticCounterBytes = 64 * 1024;
+
+struct SplitBuffers {
+    int *counters;
+    uint8_t *partials;
+};
+
+struct WorkspaceRef {
+    void *base;
+    size_t bytes;
+    bool fixed_regions;  // the library's static buffer
+    // the buffers of a launch whose plan needs counter_bytes + partial_bytes; FP6_OK when they fit
+    fp6_status view(size_t counter_bytes, size_t partial_bytes, SplitBuffers &out) const
+    {
+        out.counters = nullptr;
+        out.partials = nullptr;
+        if (partial_bytes == 0)
+            return FP6_OK;  // no split-K: nothing is touched
+        const size_t head = fixed_regions ? kStaticCounterBytes : counter_bytes;
+        if (!base || counter_bytes > head || bytes < head || bytes - head < partial_bytes)
+            return FP6_ERR_WORKSPACE;
+        if (!aligned16(base))
+            return FP6_ERR_ALIGN;
+        out.counters = static_cast<int *>(base);
+        out.partials = static_cast<uint8_t *>(base) + head;
+        return FP6_OK;
+    }
+};
+
 struct StreamPlan {
     int cfg;         // index into kStreamCfg / kStreamCfgFp16
     int nt;          // 16-token tiles handled per launch
@@ -252,12 +285,15 @@ size_t tiled_workspace_bytes(int64_t M, int64_t N, int64_t K, bool tall_tile_ok)
 
 template <class Src>
 fp6_status launch_tiled_chunk(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
-                              int64_t K, void *workspace, const Epilogue &epi, hipStream_t stream)
+                              int64_t K, const WorkspaceRef &workspace, const Epilogue &epi, hipStream_t stream)
 {
     const TiledPlan p = plan_tiled(M, N, K, Src::kTallTile);
-    int *counters = static_cast<int *>(workspace);
-    float4_t *partials =
-        p.total_bytes() ? reinterpret_cast<float4_t *>(static_cast<uint8_t *>(workspace) + p.counter_bytes) : nullptr;
+    SplitBuffers buf;
+    const fp6_status fits = workspace.view(p.counter_bytes, p.split > 1 ? p.partial_bytes : 0, buf);
+    if (fits != FP6_OK)
+        return fits;
+    int *counters = buf.counters;
+    float4_t *partials = reinterpret_cast<float4_t *>(buf.partials);
     const TileShape &t = p.tile;
 #define FP6_TILED_CASE(RT_, NT_, WM_, WN_)                                                                        \
     if (t.rt == RT_ && t.nt == NT_ && t.wm == WM_ && t.wn == WN_)                                                 \
@@ -275,17 +311,20 @@ fp6_status launch_tiled_chunk(const void *weights, const void *scales, const voi
 
 template <class Src>
 fp6_status launch_tiled(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
-                        int64_t K, void *workspace, size_t workspace_bytes, const Epilogue &epi, hipStream_t stream)
+                        int64_t K, const WorkspaceRef &workspace, const Epilogue &epi, hipStream_t stream)
 {
     const int64_t chunk = tiled_chunk_tokens(K);
     if (chunk <= 0)
         return FP6_ERR_SHAPE;  // one token's activations exceed a 32-bit byte offset
-    const size_t need = tiled_workspace_bytes(M, N, K, Src::kTallTile);
-    if (need > 0) {
-        if (!workspace || workspace_bytes < need)
-            return FP6_ERR_WORKSPACE;
-        if (!aligned16(workspace))
-            return FP6_ERR_ALIGN;
+    // every chunk's plan must fit before anything is launched (a full chunk and the shorter last one)
+    for (int64_t n : {N < chunk ? N : chunk, N > chunk ? N % chunk : (int64_t)0}) {
+        if (n <= 0)
+            continue;
+        const TiledPlan p = plan_tiled(M, n, K, Src::kTallTile);
+        SplitBuffers unused;
+        const fp6_status fits = workspace.view(p.counter_bytes, p.split > 1 ? p.partial_bytes : 0, unused);
+        if (fits != FP6_OK)
+            return fits;
     }
     const int64_t Mout = epi.gated ? M / 2 : M;
     for (int64_t n0 = 0; n0 < N; n0 += chunk) {
@@ -336,18 +375,15 @@ fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const voi
 
 template <class Src>
 fp6_status launch_stream(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
-                         int64_t K, void *workspace, size_t workspace_bytes, const Epilogue &epi, hipStream_t stream)
+                         int64_t K, const WorkspaceRef &workspace, const Epilogue &epi, hipStream_t stream)
 {
     const StreamPlan p = plan_stream(M, N, K, Src::kPackedConfigs);
-    if (p.total_bytes() > 0) {
-        if (!workspace || workspace_bytes < p.total_bytes())
-            return FP6_ERR_WORKSPACE;
-        if (!aligned16(workspace))
-            return FP6_ERR_ALIGN;
-    }
-    int *counters = static_cast<int *>(workspace);
-    float4_t *partials =
-        p.total_bytes() ? reinterpret_cast<float4_t *>(static_cast<uint8_t *>(workspace) + p.counter_bytes) : nullptr;
+    SplitBuffers buf;
+    const fp6_status fits = workspace.view(p.counter_bytes, p.split > 1 ? p.partial_bytes : 0, buf);
+    if (fits != FP6_OK)
+        return fits;
+    int *counters = buf.counters;
+    float4_t *partials = reinterpret_cast<float4_t *>(buf.partials);
     switch (p.cfg) {
     case 0: return launch_stream_cfg<Src, 0>(p, weights, scales, X, Y, M, N, K, partials, counters, epi, stream);
     case 1: return launch_stream_cfg<Src, 1>(p, weights, scales, X, Y, M, N, K, partials, counters, epi, stream);
@@ -393,11 +429,64 @@ fp6_status unpack_impl(const void *packed, const void *scales_f16, int64_t M, in
     return hipGetLastError() == hipSuccess ? FP6_OK : FP6_ERR_HIP;
 }
 
+// ---- the library's own split-K buffer (fp6_linear_static) ------------------------------------------
+// A file-scope device array: every GPU the library runs on holds its own copy, at its own address, until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the device
+// address that the kernels and the fill take is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[FP6_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+fp6_status static_scratch_address(void **out)
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices)
+        return FP6_ERR_HIP;
+    void *ptr = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr)
+            return FP6_ERR_HIP;
+        g_scratch_ptr[device].store(ptr, std::memory_order_release);  // racing threads store the same address
+    }
+    *out = ptr;
+    return FP6_OK;
+}
+
+// Counter bytes that a call of the packed 6-bit layer needs in the static buffer, or FP6_ERR_WORKSPACE when
+// the call does not fit it.  Host arithmetic only.
+fp6_status static_plan(int64_t M, int64_t N, int64_t K, size_t &counter_bytes)
+{
+    const WorkspaceRef probe{reinterpret_cast<void *>(uintptr_t(256)), FP6_STATIC_SCRATCH_BYTES, true};  // never dereferenced
+    SplitBuffers unused;
+    counter_bytes = 0;
+    if (N <= kStreamMaxN) {
+        const StreamPlan p = plan_stream(M, N, K, true);
+        if (p.split > 1)
+            counter_bytes = p.counter_bytes;
+        return probe.view(p.counter_bytes, p.split > 1 ? p.partial_bytes : 0, unused);
+    }
+    const int64_t chunk = tiled_chunk_tokens(K);
+    if (chunk <= 0)
+        return FP6_ERR_SHAPE;
+    for (int64_t n : {N < chunk ? N : chunk, N > chunk ? N % chunk : (int64_t)0}) {
+        if (n <= 0)
+            continue;
+        const TiledPlan p = plan_tiled(M, n, K, PackedFp6Source::kTallTile);
+        if (p.split > 1 && p.counter_bytes > counter_bytes)
+            counter_bytes = p.counter_bytes;
+        const fp6_status fits = probe.view(p.counter_bytes, p.split > 1 ? p.partial_bytes : 0, unused);
+        if (fits != FP6_OK)
+            return fits;
+    }
+    return FP6_OK;
+}
+
 template <class Src>
 fp6_status packed_linear_impl(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
                               int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream,
-                              const Epilogue &epi = Epilogue{nullptr, nullptr, 0})
+                              const Epilogue &epi = Epilogue{nullptr, nullptr, 0}, bool static_buffer = false)
 {
+    const WorkspaceRef ws{workspace, workspace_bytes, static_buffer};
     if (!packed || !scales_f16 || !X_f16 || !Y_f16)
         return FP6_ERR_NULL;
     if (!packed_shape_ok(M, K) || N <= 0 || N >= (1ll << 31))
@@ -406,10 +495,8 @@ fp6_status packed_linear_impl(const void *packed, const void *scales_f16, const 
         || !aligned16(epi.residual))
         return FP6_ERR_ALIGN;
     if (N > kStreamMaxN)
-        return launch_tiled<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes, epi,
-                                 static_cast<hipStream_t>(stream));
-    return launch_stream<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes, epi,
-                              static_cast<hipStream_t>(stream));
+        return launch_tiled<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, ws, epi, static_cast<hipStream_t>(stream));
+    return launch_stream<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, ws, epi, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -486,6 +573,37 @@ fp6_status fp6_linear(const void *packed, const void *scales_f16, const void *X_
 {
     return packed_linear_impl<PackedFp6Source>(packed, scales_f16, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
                                                stream);
+}
+
+fp6_status fp6_linear_static(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
+                             int64_t N, int64_t K, void *stream)
+{
+    if (!packed || !scales_f16 || !X_f16 || !Y_f16)
+        return FP6_ERR_NULL;
+    if (!packed_shape_ok(M, K) || N <= 0 || N >= (1ll << 31))
+        return FP6_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(scales_f16) || !aligned16(X_f16) || !aligned16(Y_f16))
+        return FP6_ERR_ALIGN;
+    size_t counter_bytes = 0;
+    const fp6_status fits = static_plan(M, N, K, counter_bytes);  // before the device is touched
+    if (fits != FP6_OK)
+        return fits;
+    void *buffer = nullptr;
+    if (counter_bytes > 0) {
+        const fp6_status found = static_scratch_address(&buffer);
+        if (found != FP6_OK)
+            return found;
+        // the array keeps what the last call left: the arrival counters must start at zero (a fill kernel,
+        // not a memset node, so that the call can be captured into a graph)
+        const size_t n16 = counter_bytes / 16;
+        hipLaunchKernelGGL(zero_fill_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), static_cast<u32x4 *>(buffer), n16);
+        if (hipGetLastError() != hipSuccess)
+            return FP6_ERR_HIP;
+    }
+    return packed_linear_impl<PackedFp6Source>(packed, scales_f16, X_f16, Y_f16, M, N, K, buffer,
+                                               buffer ? (size_t)FP6_STATIC_SCRATCH_BYTES : 0, stream,
+                                               Epilogue{nullptr, nullptr, 0}, true);
 }
 
 fp6_status fp6_linear_fused(const void *packed, const void *scales_f16, const void *X_f16, void *Y_f16, int64_t M,
@@ -659,11 +777,12 @@ fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_
         return FP6_ERR_SHAPE;
     if (!aligned16(W_f16) || !aligned16(X_f16) || !aligned16(Y_f16))
         return FP6_ERR_ALIGN;
+    const WorkspaceRef ws{workspace, workspace_bytes, false};
     if (N > kStreamMaxN)
-        return launch_tiled<PlainFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
-                                             Epilogue{nullptr, nullptr, 0}, static_cast<hipStream_t>(stream));
-    return launch_stream<PlainFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, workspace, workspace_bytes,
-                                          Epilogue{nullptr, nullptr, 0}, static_cast<hipStream_t>(stream));
+        return launch_tiled<PlainFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, ws, Epilogue{nullptr, nullptr, 0},
+                                             static_cast<hipStream_t>(stream));
+    return launch_stream<PlainFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, ws, Epilogue{nullptr, nullptr, 0},
+                                          static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

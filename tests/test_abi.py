@@ -101,6 +101,17 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.fp16_linear(p, p, p, 16, 1, big_k, null, 0, null) == SHAPE
     assert lib.fp16_linear(p, p, p, 16, 128, big_k, null, 0, null) == SHAPE
     assert lib.fp16_linear_workspace_bytes(16, 1, big_k) == 0
+    # the entry point that allocates nothing refuses bad arguments, and shapes that do not fit its array, on
+    # the host as well (a forced split-K factor is the only way past the array's size)
+    assert lib.fp6_linear_static(p, p, p, null, 16, 1, 256, null) == NULL
+    assert lib.fp6_linear_static(p, p, p, p, 16, 0, 256, null) == SHAPE
+    assert lib.fp6_linear_static(p, odd, p, p, 16, 1, 256, null) == ALIGN
+    lib.fp6_tuning_set_split_k(4)
+    try:
+        assert lib.fp6_linear_workspace_bytes(8192, 512, 22016) > (32 << 20) + (64 << 10)
+        assert lib.fp6_linear_static(p, p, p, p, 8192, 512, 22016, null) == WS
+    finally:
+        lib.fp6_tuning_set_split_k(0)
     # a shape that needs split-K partial sums refuses to run without a workspace
     M, N, K = 8192, 8, 22016
     need = lib.fp6_linear_workspace_bytes(M, N, K)

@@ -14,34 +14,25 @@ namespace {
 using namespace fp6;
 
 constexpr int kLayoutVersion = 3;
-// Configurations of the streaming kernel: {token tiles per wave, waves per block, weight tiles in flight per
-// wave, k-tiles per activation stage, iterations over which the activation copies of a stage are spread}.
+// Configurations of the streaming kernel: {row tiles per wave, token tiles per wave, waves per block, k-tiles
+// of weights in flight per wave, k-tiles per activation stage, iterations over which the activation copies of
+// a stage are spread, k-tiles dealt round-robin to the split-K slices, next request before the computation}.
 // For N <= 16 there are two block heights; the plan takes the one that fills the chip best for the shape.
 struct StreamCfg {
-    int nt, waves, depth, stage, spread = 1;
+    int rt, nt, waves, depth, stage, spread;
+    bool deal, early;
 };
-#ifndef FP6_SCFG0
-#define FP6_SCFG0 {1, 4, 4, 4}
-#endif
-#ifndef FP6_SCFG1
-#define FP6_SCFG1 {1, 8, 4, 4}
-#endif
-#ifndef FP6_SCFG2
-#define FP6_SCFG2 {2, 8, 2, 2}
-#endif
-#ifndef FP6_SCFG3
-#define FP6_SCFG3 {4, 8, 2, 2}
-#endif
 constexpr int kStreamCfgs = 4;
-constexpr StreamCfg kStreamCfg[kStreamCfgs] = {FP6_SCFG0, FP6_SCFG1, FP6_SCFG2, FP6_SCFG3};
+constexpr StreamCfg kStreamCfg[kStreamCfgs] = {{1, 1, 4, 4, 4, 1, true, false}, {1, 1, 8, 2, 2, 1, true, false},
+                                               {1, 2, 8, 2, 2, 1, true, false}, {1, 4, 8, 2, 2, 1, true, false}};
 // the fp16 weight source needs 32 registers per tile in flight: its own, shallower table
-#ifndef FP6_SCFG16_0
-#define FP6_SCFG16_0 {1, 4, 2, 4}
-#endif
-#ifndef FP6_SCFG16_1
-#define FP6_SCFG16_1 {1, 8, 2, 4}
-#endif
-constexpr StreamCfg kStreamCfgFp16[kStreamCfgs] = {FP6_SCFG16_0, FP6_SCFG16_1, {2, 8, 2, 2}, {4, 8, 2, 2}};
+constexpr StreamCfg kStreamCfgFp16[kStreamCfgs] = {{1, 1, 4, 2, 4, 1, true, false}, {1, 1, 8, 2, 4, 1, true, false},
+                                                   {1, 2, 8, 2, 2, 1, true, false}, {1, 4, 8, 2, 2, 1, true, false}};
+template <bool PACKED, int C>
+struct StreamShapeOf {
+    static constexpr StreamCfg c = PACKED ? kStreamCfg[C] : kStreamCfgFp16[C];
+    typedef StreamShape<c.rt, c.nt, c.waves, c.depth, c.stage, c.spread, c.deal, c.early> type;
+};
 constexpr int kStreamMaxN = 64;  // token counts up to this use the streaming kernel
 constexpr int kCus = 256;
 
@@ -109,7 +100,8 @@ struct StreamPlan {
 // 70B-class shapes at N = 16: 240 blocks of 8 waves beat 320 or 480 blocks of 4 waves by 15-20 %, and 172
 // blocks in one round beat 344 blocks in two.  So: for every available block height, the largest split-K
 // factor that keeps row blocks x S <= 256 (at least two k-tiles per slice); take the candidate with the
-// most blocks, on a tie the one with the smaller S (longer streams, fewer partial tiles).
+// most blocks, on a tie the one with the taller blocks (more rows share each copy of the activations; with
+// the k-tiles dealt to the slices a larger S no longer costs a sweeping front of its own).
 StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
 {
     const StreamCfg *table = packed ? kStreamCfg : kStreamCfgFp16;
@@ -123,7 +115,8 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
     int64_t best_s = 1, best_blocks = -1;
     bool best_single = false;
     for (int c = first; c <= last; ++c) {
-        const int64_t rb = (row_tiles + table[c].waves - 1) / table[c].waves;
+        const int64_t block_tiles = table[c].waves * table[c].rt;
+        const int64_t rb = (row_tiles + block_tiles - 1) / block_tiles;
         int64_t s = forced > 0 ? forced : kCus / rb;
         if (s > max_split)
             s = max_split;
@@ -134,6 +127,10 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
         // the kernel addresses the partial tiles with 32-bit byte offsets
         while (s > 1 && (uint64_t)s * (uint64_t)row_tiles * (uint64_t)table[c].nt * 1024u >= (1ull << 31))
             s /= 2;
+        // ... and, with the k-tiles dealt to the slices, the weights with 32-bit offsets that step by s k-tiles
+        // and run up to 20 steps past the end of a slice (look-ahead of the pipeline; those read as zeros)
+        while (s > 1 && table[c].deal && (uint64_t)(KT + 20 * s) * (uint64_t)row_tiles * kTileBytes >= (1ull << 31))
+            s /= 2;
         const int64_t blocks = rb * s;
         const bool single = blocks <= kCus;
         bool better;
@@ -142,7 +139,7 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
         else if (single != best_single)
             better = single;
         else if (single)
-            better = blocks > best_blocks || (blocks == best_blocks && s < best_s);
+            better = blocks > best_blocks || (blocks == best_blocks && s > best_s);
         else
             better = blocks < best_blocks;  // several rounds either way: the fewer, taller blocks
         if (better) {
@@ -158,7 +155,8 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
     p.cfg = best;
     p.nt = table[best].nt;
     p.split = (int)best_s;
-    p.row_blocks = (int)((row_tiles + table[best].waves - 1) / table[best].waves);
+    const int64_t block_tiles = table[best].waves * table[best].rt;
+    p.row_blocks = (int)((row_tiles + block_tiles - 1) / block_tiles);
     p.counter_bytes = (((size_t)row_tiles * sizeof(int)) + 255) / 256 * 256;  // one arrival counter per row tile
     p.partial_bytes = (size_t)p.split * (size_t)row_tiles * (size_t)p.nt * 64 * sizeof(float4_t);
     return p;
@@ -347,9 +345,10 @@ fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const voi
                              int64_t M, int64_t N, int64_t K, float4_t *partials, int *counters, const Epilogue &epi,
                              hipStream_t stream)
 {
-    constexpr StreamCfg c = Src::kPackedConfigs ? kStreamCfg[C] : kStreamCfgFp16[C];
-    auto kernel = linear_stream_kernel<Src, c.nt, c.waves, c.depth, c.stage, c.spread>;
-    constexpr size_t lds = (size_t)2 * c.stage * c.nt * 512 * 16;  // two stages of activations
+    typedef typename StreamShapeOf<Src::kPackedConfigs, C>::type Shape;
+    constexpr StreamCfg c = StreamShapeOf<Src::kPackedConfigs, C>::c;
+    auto kernel = linear_stream_kernel<Src, Shape>;
+    constexpr size_t lds = Shape::kLdsBytes;
     static_assert(lds <= 160 * 1024, "activation stages exceed the LDS of a CU");
     static std::atomic<uint64_t> lds_done{0};  // per instantiation
     if (!allow_dynamic_lds(reinterpret_cast<const void *>(kernel), lds, lds_done))

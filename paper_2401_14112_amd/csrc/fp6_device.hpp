@@ -146,7 +146,10 @@ __device__ __forceinline__ u32x2 issue_load_b64(rsrc_t rsrc, int lane_off)
 
 // Global -> LDS copy without passing through registers: lane i's 16 bytes land at LDS byte address
 // lds_base + IMM + 16*i (lds_base wave-uniform, placed in M0).  Counted by vmcnt like any other load;
-// the data is in LDS once the wait has passed (other waves see it after the next barrier).
+// the data is in LDS once the wait has passed (other waves see it after the next barrier).  M0 is written
+// inside the statement and cannot be named as clobbered: it is a reserved register for this compiler (which
+// says so when it is listed), i.e. the compiler keeps no value in it across statements and sets it right
+// before each instruction of its own that reads it.
 template <int IMM>
 __device__ __forceinline__ void issue_load_to_lds_b128(rsrc_t rsrc, int lane_off, uint32_t lds_base)
 {
@@ -184,25 +187,27 @@ __device__ __forceinline__ void x_source_of_piece(int p, int &n, int &q)
 // is the column, inside the tile, of the first of the 8 consecutive columns that
 // lane group q feeds to MFMA step f; the activation staging uses the same map.
 // slice_rsrc() describes the memory one wave may read for row tile `row_tile` and
-// k-tiles [kt0, kt1) of a matrix of RT row tiles (for a packed source: from the first tile
-// of the slice to the end of its last; the tiles of other row tiles lie in between);
+// k-tiles kt_first + i * kt_step (i < n_tiles) of a matrix of RT row tiles (for a packed source: from the first
+// tile of the slice to the end of its last; the tiles of other row tiles lie in between);
 // issue() requests the tile at lane offset `off` (= lane_offset + t * tile_stride(RT) for
 // tile t of the slice) with kLoads loads.  Offsets are 32-bit: the host admits only
 // matrices whose packed size, plus the look-ahead of the pipelines, stays below 2^31.
 
 // What one wave keeps to fetch the tiles of its slice: init() once, then issue(tile, t) requests tile t of
-// the slice (t past the slice reads zeros).  SimpleStream serves every source whose tile comes from one
-// buffer; a source with a second input (per-group scales) defines its own.
+// the slice (t past the slice reads zeros).  A slice is the k-tiles kt_first, kt_first + kt_step, ... (n_tiles
+// of them) of one row tile: kt_step = 1 is a contiguous range of k-tiles, kt_step = S deals the k-tiles of a
+// row tile round-robin to S slices.  SimpleStream serves every source whose tile comes from one buffer; a
+// source with a second input (per-group scales) defines its own.
 template <class Src>
 struct SimpleStream {
     rsrc_t rsrc;
     int off, stride;
-    __device__ __forceinline__ void init(const void *weights, const half_t * /*scales*/, int64_t row_tile, int kt0,
-                                         int kt1, int64_t RT, int64_t K, int lane)
+    __device__ __forceinline__ void init(const void *weights, const half_t * /*scales*/, int64_t row_tile, int kt_first,
+                                         int kt_step, int n_tiles, int64_t RT, int64_t K, int lane)
     {
-        rsrc = Src::slice_rsrc(weights, row_tile, kt0, kt1, RT, K);
-        off = Src::lane_offset(lane, kt0, (int)K);
-        stride = __builtin_amdgcn_readfirstlane(Src::tile_stride(RT));
+        rsrc = Src::slice_rsrc(weights, row_tile, kt_first, kt_step, n_tiles, RT, K);
+        off = Src::lane_offset(lane, kt_first, (int)K);
+        stride = __builtin_amdgcn_readfirstlane(Src::tile_stride(RT) * kt_step);
     }
     __device__ __forceinline__ void issue(typename Src::Tile &tile, int t) const
     {
@@ -210,13 +215,16 @@ struct SimpleStream {
     }
 };
 
-// Packed sources: the slice of row tile `row_tile` over k-tiles [kt0, kt1), tiles of TILE_BYTES stored
-// k-tile major.  A tile past the slice lies past the range: it reads as zeros and fetches nothing.
+// Packed sources: the slice of row tile `row_tile` over k-tiles kt_first + i * kt_step, i < n_tiles, tiles of
+// TILE_BYTES stored k-tile major.  The range runs from the first tile of the slice to the end of its last (the
+// tiles of other row tiles and slices lie in between); a tile past the slice lies past the range: it reads as
+// zeros and fetches nothing.
 template <int TILE_BYTES>
-__device__ __forceinline__ rsrc_t packed_slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1, int64_t RT)
+__device__ __forceinline__ rsrc_t packed_slice_rsrc(const void *base, int64_t row_tile, int kt_first, int kt_step,
+                                                    int n_tiles, int64_t RT)
 {
-    return make_rsrc(static_cast<const uint8_t *>(base) + ((int64_t)kt0 * RT + row_tile) * TILE_BYTES,
-                     (uint32_t)(((int64_t)(kt1 - kt0 - 1) * RT + 1) * TILE_BYTES));
+    return make_rsrc(static_cast<const uint8_t *>(base) + ((int64_t)kt_first * RT + row_tile) * TILE_BYTES,
+                     (uint32_t)(((int64_t)(n_tiles - 1) * kt_step * RT + 1) * TILE_BYTES));
 }
 
 struct PackedFp6Source {
@@ -231,10 +239,10 @@ struct PackedFp6Source {
     // bytes from one k-tile of the slice to the next
     __device__ static __forceinline__ int tile_stride(int64_t RT) { return (int)(RT * kTileBytes); }
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
-    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
-                                                        int64_t RT, int64_t /*K*/)
+    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt_first, int kt_step,
+                                                        int n_tiles, int64_t RT, int64_t /*K*/)
     {
-        return packed_slice_rsrc<kTileBytes>(base, row_tile, kt0, kt1, RT);
+        return packed_slice_rsrc<kTileBytes>(base, row_tile, kt_first, kt_step, n_tiles, RT);
     }
     __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
     __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
@@ -285,17 +293,19 @@ struct PackedFp6GroupSource {
     struct Stream {
         rsrc_t w_rsrc, s_rsrc;
         int w_off, w_stride, s_off;
-        __device__ __forceinline__ void init(const void *weights, const half_t *scales, int64_t row_tile, int kt0,
-                                             int kt1, int64_t RT, int64_t K, int lane)
+        int s_stride;
+        __device__ __forceinline__ void init(const void *weights, const half_t *scales, int64_t row_tile, int kt_first,
+                                             int kt_step, int n_tiles, int64_t RT, int64_t K, int lane)
         {
-            w_rsrc = PackedFp6Source::slice_rsrc(weights, row_tile, kt0, kt1, RT, K);
+            w_rsrc = PackedFp6Source::slice_rsrc(weights, row_tile, kt_first, kt_step, n_tiles, RT, K);
             w_off = lane * 16;
-            w_stride = __builtin_amdgcn_readfirstlane(PackedFp6Source::tile_stride(RT));
+            w_stride = __builtin_amdgcn_readfirstlane(PackedFp6Source::tile_stride(RT) * kt_step);
             const int groups = (int)(K / kGroupColumns);  // per row; = 2 * KT
             // the scales of the 16 rows of the row tile; a tile past the slice reads other finite scales or
             // zeros, and its weights read as zeros
             s_rsrc = make_rsrc(scales + row_tile * kTileRows * groups, (uint32_t)(kTileRows * groups * 2));
-            s_off = ((lane & 15) * groups + 2 * kt0) * 2;
+            s_off = ((lane & 15) * groups + 2 * kt_first) * 2;
+            s_stride = __builtin_amdgcn_readfirstlane(4 * kt_step);
         }
         __device__ __forceinline__ void issue(Tile &t, int i) const
         {
@@ -303,7 +313,7 @@ struct PackedFp6GroupSource {
             t.p0 = issue_load_b128<0, true>(w_rsrc, off);
             t.p1 = issue_load_b128<1024, true>(w_rsrc, off);
             t.p2 = issue_load_b128<2048, true>(w_rsrc, off);
-            t.sc = issue_load_b32<0>(s_rsrc, s_off + i * 4);
+            t.sc = issue_load_b32<0>(s_rsrc, s_off + i * s_stride);
         }
     };
     __device__ static __forceinline__ void pin_tile(Tile &t)
@@ -365,10 +375,10 @@ struct PackedFp5Source {
     static constexpr int kTileBytes5 = 2560;
     __device__ static __forceinline__ int tile_stride(int64_t RT) { return (int)(RT * kTileBytes5); }
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
-    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
-                                                        int64_t RT, int64_t /*K*/)
+    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt_first, int kt_step,
+                                                        int n_tiles, int64_t RT, int64_t /*K*/)
     {
-        return packed_slice_rsrc<kTileBytes5>(base, row_tile, kt0, kt1, RT);
+        return packed_slice_rsrc<kTileBytes5>(base, row_tile, kt_first, kt_step, n_tiles, RT);
     }
     __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
     __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
@@ -437,10 +447,10 @@ struct PackedFp4Source {
     static constexpr int kTileBytes4 = 2048;
     __device__ static __forceinline__ int tile_stride(int64_t RT) { return (int)(RT * kTileBytes4); }
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
-    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
-                                                        int64_t RT, int64_t /*K*/)
+    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt_first, int kt_step,
+                                                        int n_tiles, int64_t RT, int64_t /*K*/)
     {
-        return packed_slice_rsrc<kTileBytes4>(base, row_tile, kt0, kt1, RT);
+        return packed_slice_rsrc<kTileBytes4>(base, row_tile, kt_first, kt_step, n_tiles, RT);
     }
     __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
     __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
@@ -483,10 +493,10 @@ struct PackedFp3Source {
     static constexpr int kTileBytes3 = 1536;
     __device__ static __forceinline__ int tile_stride(int64_t RT) { return (int)(RT * kTileBytes3); }
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
-    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt0, int kt1,
-                                                        int64_t RT, int64_t /*K*/)
+    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt_first, int kt_step,
+                                                        int n_tiles, int64_t RT, int64_t /*K*/)
     {
-        return packed_slice_rsrc<kTileBytes3>(base, row_tile, kt0, kt1, RT);
+        return packed_slice_rsrc<kTileBytes3>(base, row_tile, kt_first, kt_step, n_tiles, RT);
     }
     __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
     __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
@@ -533,8 +543,8 @@ struct PlainFp16Source {
     // and load instruction); plain (cached) loads, so the other half of each line is an L1/L2 hit
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
     // the 16 rows of the row tile; tiles past the slice are neutralised by zero activations
-    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int /*kt0*/, int /*kt1*/,
-                                                        int64_t /*RT*/, int64_t K)
+    __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int /*kt_first*/,
+                                                        int /*kt_step*/, int /*n_tiles*/, int64_t /*RT*/, int64_t K)
     {
         return make_rsrc(static_cast<const half_t *>(base) + row_tile * kTileRows * K, (uint32_t)(kTileRows * K * 2));
     }

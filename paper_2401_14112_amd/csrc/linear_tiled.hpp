@@ -71,7 +71,7 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
         const int rt = row_tile0 + r;
-        w_stream[r].init(weights, scales, rt < n_row_tiles ? rt : n_row_tiles - 1, kt0, kt1, n_row_tiles, K, lane);
+        w_stream[r].init(weights, scales, rt < n_row_tiles ? rt : n_row_tiles - 1, kt0, 1, n_valid, n_row_tiles, K, lane);
     }
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
@@ -117,10 +117,7 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     // work is laid out in small pieces that the other waves of the SIMD can cover with their own MFMAs.
     constexpr int LOOK = 4;
     constexpr int STEPS = 4 * NT;
-#ifndef FP6_TILED_VALU
-#define FP6_TILED_VALU 2  // VALU instructions the scheduler may place after the MFMAs of a step
-#endif
-    constexpr int VALU_PER_STEP = FP6_TILED_VALU;
+    constexpr int VALU_PER_STEP = 2;  // VALU instructions the scheduler may place after the MFMAs of a step
     half8_t a[2][2][RT];  // [group parity][even/odd run][row tile]
     half8_t bq[LOOK];
     auto ldb = [&](const u32x4 *xbuf, int st) {

@@ -368,7 +368,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t *__restrict__
     const int64_t RT = M / kTileRows, row_tile = tile / KT, kt = tile % KT;
     const int r = lane & 15, q = lane >> 4;
     typename Src::Stream stream;
-    stream.init(packed, scales, row_tile, (int)kt, (int)kt + 1, RT, K, lane);
+    stream.init(packed, scales, row_tile, (int)kt, 1, 1, RT, K, lane);
     typename Src::Tile t;
     stream.issue(t, 0);
     wait_loads<0>();

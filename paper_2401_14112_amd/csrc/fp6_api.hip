@@ -14,24 +14,24 @@ namespace {
 using namespace fp6;
 
 constexpr int kLayoutVersion = 3;
-// Configurations of the streaming kernel: {row tiles per wave, token tiles per wave, waves per block, k-tiles
-// of weights in flight per wave, k-tiles per activation stage, iterations over which the activation copies of
-// a stage are spread, k-tiles dealt round-robin to the split-K slices, next request before the computation}.
+// Configurations of the streaming kernel: {token tiles per wave, waves per block, weight tiles in flight per
+// wave, k-tiles per activation stage, iterations over which the activation copies of a stage are spread,
+// k-tiles dealt round-robin to the split-K slices}.
 // For N <= 16 there are two block heights; the plan takes the one that fills the chip best for the shape.
 struct StreamCfg {
-    int rt, nt, waves, depth, stage, spread;
-    bool deal, early;
+    int nt, waves, depth, stage, spread;
+    bool deal;
 };
 constexpr int kStreamCfgs = 4;
-constexpr StreamCfg kStreamCfg[kStreamCfgs] = {{1, 1, 4, 4, 4, 1, true, false}, {1, 1, 8, 2, 2, 1, true, false},
-                                               {1, 2, 8, 2, 2, 1, true, false}, {1, 4, 8, 2, 2, 1, true, false}};
+constexpr StreamCfg kStreamCfg[kStreamCfgs] = {{1, 4, 4, 4, 1, true}, {1, 8, 2, 1, 1, true}, {2, 8, 2, 1, 1, true},
+                                               {4, 8, 2, 1, 1, true}};
 // the fp16 weight source needs 32 registers per tile in flight: its own, shallower table
-constexpr StreamCfg kStreamCfgFp16[kStreamCfgs] = {{1, 1, 4, 2, 4, 1, true, false}, {1, 1, 8, 2, 4, 1, true, false},
-                                                   {1, 2, 8, 2, 2, 1, true, false}, {1, 4, 8, 2, 2, 1, true, false}};
+constexpr StreamCfg kStreamCfgFp16[kStreamCfgs] = {{1, 4, 2, 4, 1, true}, {1, 8, 2, 4, 1, true}, {2, 8, 2, 2, 1, true},
+                                                   {4, 8, 2, 2, 1, true}};
 template <bool PACKED, int C>
 struct StreamShapeOf {
     static constexpr StreamCfg c = PACKED ? kStreamCfg[C] : kStreamCfgFp16[C];
-    typedef StreamShape<c.rt, c.nt, c.waves, c.depth, c.stage, c.spread, c.deal, c.early> type;
+    typedef StreamShape<c.nt, c.waves, c.depth, c.stage, c.spread, c.deal> type;
 };
 constexpr int kStreamMaxN = 64;  // token counts up to this use the streaming kernel
 constexpr int kCus = 256;
@@ -115,8 +115,7 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
     int64_t best_s = 1, best_blocks = -1;
     bool best_single = false;
     for (int c = first; c <= last; ++c) {
-        const int64_t block_tiles = table[c].waves * table[c].rt;
-        const int64_t rb = (row_tiles + block_tiles - 1) / block_tiles;
+        const int64_t rb = (row_tiles + table[c].waves - 1) / table[c].waves;
         int64_t s = forced > 0 ? forced : kCus / rb;
         if (s > max_split)
             s = max_split;
@@ -155,8 +154,7 @@ StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
     p.cfg = best;
     p.nt = table[best].nt;
     p.split = (int)best_s;
-    const int64_t block_tiles = table[best].waves * table[best].rt;
-    p.row_blocks = (int)((row_tiles + block_tiles - 1) / block_tiles);
+    p.row_blocks = (int)((row_tiles + table[best].waves - 1) / table[best].waves);
     p.counter_bytes = (((size_t)row_tiles * sizeof(int)) + 255) / 256 * 256;  // one arrival counter per row tile
     p.partial_bytes = (size_t)p.split * (size_t)row_tiles * (size_t)p.nt * 64 * sizeof(float4_t);
     return p;

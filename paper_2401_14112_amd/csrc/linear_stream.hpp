@@ -2,21 +2,19 @@
 // layer is bound by reading the weights once from HBM (Section 3 and Section 7.1 of
 // the paper: linear layers at batch < 128 are limited by weight traffic).
 //
-// Work split: one wave owns RT 16-row tiles and one split-K slice of their 256-column
+// Work split: one wave owns one 16-row tile and one split-K slice of its 256-column
 // k-tiles; weights go HBM -> VGPR with three (packed) 128-bit loads per lane per tile,
-// prefetched DEPTH k-tiles ahead, and are used by exactly one wave, so they never touch
+// prefetched DEPTH tiles ahead, and are used by exactly one wave, so they never touch
 // LDS.  The activations (16*NT tokens) are the only shared operand: the block copies
 // them global -> LDS without passing through registers, already in MFMA B-fragment
-// order, a STAGE of G k-tiles at a time, double-buffered; every B fragment read from
-// LDS feeds the RT row tiles of the wave.  There is one barrier per stage, not per
-// k-tile: inside a stage every wave runs at the pace of its own weight stream, so one
-// late load delays one wave, not eight.  fp32 accumulation in
-// v_mfma_f32_16x16x32_f16; the row scale is applied once in the epilogue.
+// order, a STAGE of G k-tiles at a time, double-buffered, with one barrier per stage.
+// fp32 accumulation in v_mfma_f32_16x16x32_f16; the row scale is applied once in the
+// epilogue.
 //
-// Split-K: every wave writes its fp32 partial tiles, bumps the arrival counter of each
-// of its row tiles, and the wave that arrives last at a row tile adds the S partials in
-// split order (so the result does not depend on arrival order), scales, rounds and
-// stores Y.  The counter is reset by that wave, so a zeroed workspace stays reusable.
+// Split-K: every wave writes its fp32 partial tile, bumps the arrival counter of its
+// row tile, and the wave that arrives last adds the S partials in split order (so the
+// result does not depend on arrival order), scales, rounds and stores Y.  The counter
+// is reset by that wave, so a zeroed workspace stays reusable.
 #pragma once
 #include "fp6_device.hpp"
 
@@ -32,18 +30,15 @@ constexpr int stream_copies_between(int g, int G, int DEPTH, int XSPREAD, int XP
     return c;
 }
 
-// Shape of one instantiation: RT row tiles and NT token tiles per wave, WAVES waves per block, DEPTH k-tiles
-// of weights in flight per wave, G k-tiles per activation stage, the copies of a stage spread over the first
-// XSPREAD iterations of the previous one.  DEAL: see the split-K comment in the kernel.  EARLY: the request
-// for k-tile t + DEPTH leaves before k-tile t is computed (into a register slot of its own, DEPTH + 1 slots)
-// instead of after it (into the slot that k-tile t just freed).
-template <int RT_, int NT_, int WAVES_, int DEPTH_, int G_, int XSPREAD_, bool DEAL_, bool EARLY_>
+// Shape of one instantiation: NT token tiles per wave, WAVES waves per block (one row tile each), DEPTH
+// k-tiles of weights in flight per wave, G k-tiles per activation stage, the copies of a stage spread over the
+// first XSPREAD iterations of the previous one.  DEAL: see the split-K comment in the kernel.
+template <int NT_, int WAVES_, int DEPTH_, int G_, int XSPREAD_, bool DEAL_>
 struct StreamShape {
-    static constexpr int RT = RT_, NT = NT_, WAVES = WAVES_, DEPTH = DEPTH_, G = G_, XSPREAD = XSPREAD_;
-    static constexpr bool DEAL = DEAL_, EARLY = EARLY_;
+    static constexpr int NT = NT_, WAVES = WAVES_, DEPTH = DEPTH_, G = G_, XSPREAD = XSPREAD_;
+    static constexpr bool DEAL = DEAL_;
     static constexpr int kLdsBytes = 2 * G_ * NT_ * 8 * 1024;  // two stages of activations
     static constexpr int kThreads = WAVES_ * 64;
-    static constexpr int kBlockRowTiles = WAVES_ * RT_;
 };
 
 template <class Src, class Shape>
@@ -52,20 +47,18 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     half_t *Y, int M, int N, int K, int S, int kt_per_slice, float4_t *__restrict__ partials,
     int *__restrict__ counters, Epilogue epi)
 {
-    constexpr int RT = Shape::RT, NT = Shape::NT, WAVES = Shape::WAVES, DEPTH = Shape::DEPTH, G = Shape::G;
+    constexpr int NT = Shape::NT, WAVES = Shape::WAVES, DEPTH = Shape::DEPTH, G = Shape::G;
     constexpr int XSPREAD = Shape::XSPREAD;
-    constexpr bool KDEAL = Shape::DEAL, EARLY = Shape::EARLY;
+    constexpr bool KDEAL = Shape::DEAL;
     constexpr int COPIES = G * NT * 8;  // copy instructions (1 KB each: one token tile x one run) per stage
     static_assert(COPIES % WAVES == 0, "the copies of a stage must split evenly over the waves");
     constexpr int XPER = COPIES / WAVES;
     constexpr int STAGE_PIECES = COPIES * 64;  // 16-byte pieces of one stage
-    // the copies of the next stage are requested in the first XSPREAD iterations of a stage; they must be
-    // older than the weights of the next stage's first tile, which are requested in iteration G - DEPTH
-    static_assert(XSPREAD >= 1 && XSPREAD <= G - DEPTH + 1 && XPER % XSPREAD == 0, "bad spread of the activation copies");
+    // the copies of the next stage are requested in the first XSPREAD iterations of a stage
+    static_assert(XSPREAD >= 1 && XSPREAD <= G && XPER % XSPREAD == 0, "bad spread of the activation copies");
     constexpr int XPART = XPER / XSPREAD;
-    constexpr int SLOTS = EARLY ? DEPTH + 1 : DEPTH;  // register ring of weight k-tiles
-    constexpr int U = G / stream_gcd(G, SLOTS) * SLOTS;  // unroll: both the stage position and the ring slot are static
-    constexpr int WLOADS = RT * Src::kLoads;  // weight loads of one wave per k-tile
+    constexpr int U = G / stream_gcd(G, DEPTH) * DEPTH;  // unroll: both the stage position and the ring slot are static
+    constexpr int WLOADS = Src::kLoads;  // weight loads of one wave per k-tile
 
     extern __shared__ u32x4 xs_dyn[];  // [2][STAGE_PIECES]
 
@@ -80,7 +73,8 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     // a run-time value is a chain of ~30 dependent instructions, and the first request waits for it).
     const int row_block = blockIdx.x;
     const int split = blockIdx.y;
-    const int row_tile0 = (row_block * WAVES + wave) * RT;
+    const int row_tile = row_block * WAVES + wave;
+    const bool active = row_tile < n_row_tiles;
     // Split-K, two ways of cutting the k-tiles of a row tile into S slices.  KDEAL: slice s takes k-tiles s,
     // s + S, s + 2S, ...: the waves of all slices then stand at the same depth of the k-tile-major weight
     // stream and the launch sweeps memory as one front, whatever S is.  Otherwise slice s is a contiguous
@@ -92,15 +86,10 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     const int T = kt_per_slice + (rem > 0 ? 1 : 0);  // k-tiles computed: the same for every slice (>= n_valid)
     const int n_stages = (T + G - 1) / G;
 
-    // Row tiles past the matrix (ragged last row block) stream the last valid row tile and drop the result,
+    // Inactive waves (ragged last row block) stream the last valid row tile and drop the result,
     // so the main loop has no per-wave control flow.
-    typename Src::Stream w_stream[RT];
-#pragma unroll
-    for (int r = 0; r < RT; ++r) {
-        const int rt = row_tile0 + r;
-        w_stream[r].init(weights, scales, rt < n_row_tiles ? rt : n_row_tiles - 1, kt_first, kt_step, n_valid, n_row_tiles,
-                         K, lane);
-    }
+    typename Src::Stream w_stream;
+    w_stream.init(weights, scales, active ? row_tile : n_row_tiles - 1, kt_first, kt_step, n_valid, n_row_tiles, K, lane);
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
     // ---- activation staging.  Copy j = wave + WAVES*i of a stage serves k-tile g = j / (8*NT) of the
@@ -132,103 +121,89 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     };
 
     const int b_piece = x_piece_of_lane(lane);
-    float4_t acc[RT][NT];
+    float4_t acc[NT];
 #pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            acc[r][nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
+    for (int nt = 0; nt < NT; ++nt)
+        acc[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
-    // xb: first piece of this k-tile's activations in LDS; every B fragment feeds the RT row tiles
-    auto mma_pair = [&](const half8_t (&a_even)[RT], const half8_t (&a_odd)[RT], const u32x4 *xb, int p) {
+    // xb: first piece of this k-tile's activations in LDS
+    auto mma_pair = [&](const half8_t &a_even, const half8_t &a_odd, const u32x4 *xb, int p) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             half8_t b = bit_cast<half8_t>(xb[(nt * 8 + 2 * p) * 64 + b_piece]);
-#pragma unroll
-            for (int r = 0; r < RT; ++r)
-                acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_even[r], b, acc[r][nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_even, b, acc[nt], 0, 0, 0);
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             half8_t b = bit_cast<half8_t>(xb[(nt * 8 + 2 * p + 1) * 64 + b_piece]);
-#pragma unroll
-            for (int r = 0; r < RT; ++r)
-                acc[r][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_odd[r], b, acc[r][nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_odd, b, acc[nt], 0, 0, 0);
         }
     };
-    auto compute = [&](const typename Src::Tile (&t)[RT], const u32x4 *xb) {
+    auto compute = [&](const typename Src::Tile &t, const u32x4 *xb) {
         static_for<4>([&](auto pc) {
             constexpr int p = decltype(pc)::value;
-            half8_t a_even[RT], a_odd[RT];
-#pragma unroll
-            for (int r = 0; r < RT; ++r)
-                Src::template fragments<p>(t[r], a_even[r], a_odd[r]);
+            half8_t a_even, a_odd;
+            Src::template fragments<p>(t, a_even, a_odd);
             mma_pair(a_even, a_odd, xb, p);
         });
     };
 
-    // ---- software pipeline.  Slot t % SLOTS of the register ring holds the weights of k-tile t of the slice
-    // (RT tiles); they are requested DEPTH k-tiles ahead - right after k-tile t has been consumed, into the
-    // slot it freed, or (EARLY) right before it is computed, into the spare slot - so DEPTH-1 or DEPTH k-tiles
+    // ---- software pipeline.  Slot t % DEPTH of the register ring holds weight tile t of the slice; it is
+    // requested DEPTH tiles ahead, right after the slot's previous tile has been consumed, so DEPTH-1 tiles
     // stay in flight while one is being computed.  The activation copies of stage s+1 are requested in the
     // first XSPREAD iterations of stage s, after that stage's barrier (by then every wave has finished
     // reading the buffer they overwrite).  Loads complete in order, so "at most n outstanding" with n = the
-    // loads requested after k-tile t's weights means they have arrived: n = (DEPTH-1)*WLOADS plus the
-    // activation copies requested in the DEPTH-1 iterations in between (in every iteration the copies are
-    // requested before the weights).  Tiles past the end of the slice read as zeros through the buffer bounds
-    // check (no memory traffic), so the request pattern never varies.
-    typename Src::Tile w[SLOTS][RT];
-    auto w_issue = [&](typename Src::Tile (&dst)[RT], int t) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-            w_stream[r].issue(dst[r], t);
-    };
-    auto pin_tiles = [&](typename Src::Tile (&dst)[RT]) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-            Src::pin_tile(dst[r]);
-    };
+    // loads requested after the ones needed means those have arrived.  For the weights of tile t: n =
+    // (DEPTH-1)*WLOADS plus the activation copies requested in the DEPTH-1 iterations in between (in every
+    // iteration the copies are requested before the weights).  For the copies of a stage, needed at its first
+    // iteration: the weights of the G - XSPREAD + 1 iterations since the last of them.  The first pass over
+    // the ring has fewer copies behind it than the steady state (the prologue requests stage 0 before any
+    // weights), so it waits for everything but the weights.  Tiles past the end of the slice read as zeros
+    // through the buffer bounds check (no memory traffic), so the request pattern never varies.
+    typename Src::Tile w[DEPTH];
     x_issue(0, 0, XPER);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)
-        w_issue(w[d], d);
+        w_stream.issue(w[d], d);
     const int n_tiles = n_stages * G;
     for (int t0 = 0; t0 < n_tiles; t0 += U) {
         static_for<U>([&](auto uc) {
             constexpr int u = decltype(uc)::value;
-            constexpr int g = u % G, slot = u % SLOTS, next_slot = (u + DEPTH) % SLOTS;
-            // loads requested after this k-tile's weights (the prologue requested all copies of stage 0 before
-            // any weights, so the same count holds there); vmcnt cannot express more than 63
-            constexpr int kAfter = (DEPTH - 1) * WLOADS + stream_copies_between(g, G, DEPTH, XSPREAD, XPART);
+            constexpr int g = u % G, slot = u % DEPTH;
+            constexpr int kWeightsAfter = (DEPTH - 1) * WLOADS + stream_copies_between(g, G, DEPTH, XSPREAD, XPART);
+            constexpr int kCopiesAfter = (G - XSPREAD + 1) * WLOADS;
+            constexpr int kAfter = g == 0 && kCopiesAfter < kWeightsAfter ? kCopiesAfter : kWeightsAfter;
+            constexpr int kFirstPass = (DEPTH - 1) * WLOADS < kAfter ? (DEPTH - 1) * WLOADS : kAfter;
             static_assert(kAfter < 64, "more loads in flight than vmcnt can count");
             const int t = t0 + u;
             const int stage = t0 / G + u / G;
-            wait_loads<kAfter>();
-            pin_tiles(w[slot]);
+            if (t0 == 0)
+                wait_loads<kFirstPass>();
+            else
+                wait_loads<kAfter>();
+            Src::pin_tile(w[slot]);
             if (g == 0)
                 __syncthreads();  // the copies of this stage by all waves have landed; the other buffer is no longer read
             if (g < XSPREAD)
                 x_issue(stage + 1, g * XPART, (g + 1) * XPART);
-            if (EARLY)
-                w_issue(w[next_slot], t + DEPTH);
             if (t < T)
                 compute(w[slot], xs_dyn + (stage & 1) * STAGE_PIECES + g * (NT * 8 * 64));
-            if (!EARLY)
-                w_issue(w[next_slot], t + DEPTH);
+            w_stream.issue(w[slot], t + DEPTH);
         });
     }
     // drain: the look-ahead requests (weights out of range, activation copies into the unused buffer)
     // must land before the registers are reused and before the block gives up its LDS
     wait_loads<0>();
 #pragma unroll
-    for (int d = 0; d < SLOTS; ++d)
-        pin_tiles(w[d]);
+    for (int d = 0; d < DEPTH; ++d)
+        Src::pin_tile(w[d]);
 
-    // ---- epilogue.  Lane L holds, per (row tile, token tile), rows 4*(L/16)+i (i=0..3) of token column
-    // L%16.  No barrier follows the main loop.
+    // ---- epilogue.  Lane L holds, per token tile, rows 4*(L/16)+i (i=0..3) of token column L%16.
+    if (!active)
+        return;  // no barrier follows the main loop
     const int n_in_tile = lane & 15;
-    auto finish = [&](const float4_t (&sum)[NT], int row_tile) {
-        const int m0 = row_tile * kTileRows + 4 * (lane >> 4);
+    const int m0 = row_tile * kTileRows + 4 * (lane >> 4);
+    auto finish = [&](const float4_t (&sum)[NT]) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int col = nt * 16 + n_in_tile;
@@ -237,10 +212,7 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
         }
     };
     if (S == 1) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-            if (row_tile0 + r < n_row_tiles)
-                finish(acc[r], row_tile0 + r);
+        finish(acc);
         return;
     }
 
@@ -249,72 +221,62 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     // are written and read with device-scope atomic (relaxed) accesses: such accesses are performed at the
     // point where all CUs of the device agree (they are not left in, nor served from, a non-coherent
     // cache), so no cache write-back or invalidate is needed.  Order: this wave's stores complete (vmcnt)
-    // -> arrival counts -> the last wave's loads; the signal fences keep the compiler from moving memory
-    // operations across those two points.  The wave that arrives last at a row tile adds its S partial tiles
-    // in split order, taking its own from registers (the same bits it stored), so the sum does not depend on
-    // who is last.
+    // -> arrival count -> the last wave's loads; the signal fences keep the compiler from moving memory
+    // operations across those two points.  The last wave adds the S partial tiles in split order, taking its
+    // own from registers (the same bits it stored), so the sum does not depend on who is last.
     float *pf = reinterpret_cast<float *>(partials);
-    auto slot = [&](int s_, int row_tile, int nt) {
-        return pf + ((((int64_t)s_ * n_row_tiles + row_tile) * NT + nt) * 4) * 64 + lane;
-    };
+    auto slot = [&](int s_, int nt) { return pf + ((((int64_t)s_ * n_row_tiles + row_tile) * NT + nt) * 4) * 64 + lane; };
 #pragma unroll
-    for (int r = 0; r < RT; ++r)
-        if (row_tile0 + r < n_row_tiles) {
+    for (int nt = 0; nt < NT; ++nt)
+        if (nt * 16 + n_in_tile < N) {
+            float *dst = slot(split, nt);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                if (nt * 16 + n_in_tile < N) {
-                    float *dst = slot(split, row_tile0 + r, nt);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        __hip_atomic_store(dst + i * 64, acc[r][nt][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
+            for (int i = 0; i < 4; ++i)
+                __hip_atomic_store(dst + i * 64, acc[nt][i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's partial stores are done
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
-    int arrived = 0;  // lane r takes the ticket of row tile r
-    if (lane < RT && row_tile0 + lane < n_row_tiles)
-        arrived = __hip_atomic_fetch_add(&counters[row_tile0 + lane], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int arrived = 0;
+    if (lane == 0)
+        arrived = __hip_atomic_fetch_add(&counters[row_tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    arrived = __builtin_amdgcn_readfirstlane(arrived);
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    if (arrived != S - 1)
+        return;
+    // The partial tiles of kPartialBatch slices are requested together (one trip to memory per batch, not
+    // per slice) and then added in slice order.  Every lane loads (lanes of token columns >= N read
+    // words that nobody stored; their sums are never written).
+    float4_t sum[NT];
 #pragma unroll
-    for (int r = 0; r < RT; ++r) {
-        const int row_tile = row_tile0 + r;
-        if (row_tile >= n_row_tiles || __builtin_amdgcn_readlane(arrived, r) != S - 1)
-            continue;
-        // The partial tiles of kPartialBatch slices are requested together (one trip to memory per batch, not
-        // per slice) and then added in slice order.  Every lane loads (lanes of token columns >= N read
-        // words that nobody stored; their sums are never written).
-        float4_t sum[NT];
+    for (int nt = 0; nt < NT; ++nt)
+        sum[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < S; s0 += kPartialBatch) {
+        float4_t part[kPartialBatch][NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            sum[nt] = (float4_t){0.f, 0.f, 0.f, 0.f};
-        for (int s0 = 0; s0 < S; s0 += kPartialBatch) {
-            float4_t part[kPartialBatch][NT];
+        for (int u = 0; u < kPartialBatch; ++u) {
+            const int s_ = s0 + u < S ? s0 + u : S - 1;  // clamped: always an existing slot
 #pragma unroll
-            for (int u = 0; u < kPartialBatch; ++u) {
-                const int s_ = s0 + u < S ? s0 + u : S - 1;  // clamped: always an existing slot
+            for (int nt = 0; nt < NT; ++nt) {
+                const float *src = slot(s_, nt);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const float *src = slot(s_, row_tile, nt);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        part[u][nt][i] = __hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < kPartialBatch; ++u) {
-                const int s_ = s0 + u;
-                if (s_ < S) {
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        sum[nt] += s_ == split ? acc[r][nt] : part[u][nt];
-                }
+                for (int i = 0; i < 4; ++i)
+                    part[u][nt][i] = __hip_atomic_load(src + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
-        finish(sum, row_tile);
-        if (lane == 0)
-            counters[row_tile] = 0;  // re-arm for the next call on this workspace
+#pragma unroll
+        for (int u = 0; u < kPartialBatch; ++u) {
+            const int s_ = s0 + u;
+            if (s_ < S) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    sum[nt] += s_ == split ? acc[nt] : part[u][nt];
+            }
+        }
     }
+    finish(sum);
+    if (lane == 0)
+        counters[row_tile] = 0;  // re-arm for the next call on this workspace
 }
 
 }  // namespace fp6

@@ -11,8 +11,11 @@ the 256 MB last-level cache.  The ahead-of-time steps (fp6_quantize_pack) and th
 
 Prints ONE JSON line.  `value` = packed weight bytes streamed per second over the timed
 steps (whole job, launches replayed from captured HIP graphs); `roofline` prices the
-dominant kernel (the 16-token streaming kernel) with HIP events recorded around each of its
-launches; `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+dominant kernel (the 16-token streaming kernel) with HIP events recorded around at least ten
+replays of a graph of its launches, and carries the rest of the metric inside it: `per_n`
+(every N = 1 ... 512: microseconds per launch and the fraction of the HBM and of the
+matrix-core roof) and `mfma` (the tiled kernel at N = 512 against the 2.5 PFLOP/s roof);
+`cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -177,6 +180,11 @@ def main():
         for s in range(count % period):
             graphs[s].replay()
 
+    # every graph that the timed region replays is replayed twice first (a graph's first replay carries
+    # one-off costs), then the W warm-up steps proper
+    for g in [long_rotation, rotation] + graphs:
+        g.replay()
+        g.replay()
     run_steps(args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -218,11 +226,11 @@ def main():
                 for i, n in enumerate(sweep):
                     if n <= 16:
                         launch(n, (s * len(sweep) + i) % N_BUFFERS)
-    for s in range(max(1, args.warmup // period)):
+    for s in range(max(2, args.warmup // period)):
         dom_graph.replay()
     # one pair of events brackets one replay of the whole rotation (an event record is a stream operation of
-    # its own and would otherwise add its gap to every five launches)
-    groups = max(1, args.steps // (period * DOM_PASSES))
+    # its own and would otherwise add its gap to every five launches); at least ten replays whatever --steps is
+    groups = max(10, args.steps // (period * DOM_PASSES))
     dev_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(groups)]
     torch.cuda.synchronize()
     for gi in range(groups):
@@ -234,6 +242,25 @@ def main():
     dom_bytes = sum(algorithmic_bytes(M, n, K) for n in small) / len(small)
     dom_us = float(dom_us_all.mean())
     achieved = dom_bytes / (dom_us * 1e-6) * 1e-9
+
+    # ---- the prefill half of the metric (N = 64 ... 512) and the compute-bound roofline: every N from a graph
+    # of one launch per weight copy, HIP events around each of >= 10 replays
+    prefill = {}
+    for n in workloads.PREFILL_N:
+        Xp = workloads.make_activations(n, K, seed=n, device=dev)
+        Yp = torch.empty((n, M), dtype=torch.float16, device=dev)
+        wsp = torch.zeros(max(pkg.fp6_linear_workspace_bytes(M, n, K), 16), dtype=torch.uint8, device=dev)
+        prefill[n] = _time_graph_stats(
+            torch, np, lambda i: pkg.fp6_linear(packed[i % N_BUFFERS], scales[i % N_BUFFERS], Xp, M, K, out=Yp, workspace=wsp),
+            N_BUFFERS, replays=10)
+        del Xp, Yp, wsp
+    per_n = {}
+    for n in sweep:
+        per_n[str(n)] = _per_n_entry(M, n, K, graph_us[n])
+    for n in workloads.PREFILL_N:
+        per_n[str(n)] = _per_n_entry(M, n, K, prefill[n]["mean_us"])
+    n_mfma = max(workloads.PREFILL_N)
+    mfma_tflops = 2.0 * M * n_mfma * K / prefill[n_mfma]["mean_us"] * 1e-6
 
     result = {
         "metric": "W6A16 GEMM effective weight GB/s + TFLOP/s, 8192x22016, N=1..512",
@@ -268,9 +295,22 @@ def main():
             "algorithmic_bytes_per_launch": int(dom_bytes),
             "avg_launch_us": round(dom_us, 2),
             "min_launch_us": round(float(dom_us_all.min()), 2),
-            "timing": "HIP events on the launch stream around every replay of a graph holding the N <= 16 launches "
-                      "of %d consecutive steps (%d passes over the rotation of weight copies), elapsed / %d"
-                      % (period * DOM_PASSES, DOM_PASSES, len(small) * period * DOM_PASSES),
+            "max_launch_us": round(float(dom_us_all.max()), 2),
+            "replays_timed": int(groups),
+            "launches_per_replay": len(small) * period * DOM_PASSES,
+            # the compute-bound half: the tiled kernel at the largest N of the metric against the matrix-core roof
+            "mfma": {
+                "bound": "mfma", "kernel": "linear_tiled_kernel<PackedFp6Source> at N = %d" % n_mfma,
+                "achieved": round(mfma_tflops, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(mfma_tflops / MFMA_F16_PEAK_TFLOPS, 4), "flops_per_launch": 2 * M * n_mfma * K,
+                "avg_launch_us": round(prefill[n_mfma]["mean_us"], 2), "min_launch_us": round(prefill[n_mfma]["min_us"], 2),
+                "replays_timed": prefill[n_mfma]["replays"], "launches_per_replay": N_BUFFERS,
+            },
+            # every N of the metric: microseconds per launch (graph replay) and the fraction of each roof
+            "per_n": per_n,
+            "min_hbm_frac_N_le_32": min(per_n[str(n)]["hbm_frac"] for n in sweep),
+            "timing": "HIP events around each replay of a graph of the N<=16 launches of %d steps, elapsed/%d"
+                      % (period * DOM_PASSES, len(small) * period * DOM_PASSES),
         },
         "sweep": {
             str(n): {
@@ -313,6 +353,34 @@ def read_traffic_profile():
     except OSError:
         pass
     return None
+
+
+def _per_n_entry(M, n, K, us):
+    tfl = 2.0 * M * n * K / us * 1e-6
+    return {"us": round(us, 2), "hbm_frac": round(algorithmic_bytes(M, n, K) / us * 1e-3 / HBM_PEAK_GBPS, 4),
+            "mfma_frac": round(tfl / MFMA_F16_PEAK_TFLOPS, 4)}
+
+
+def _time_graph_stats(torch, np, fn, launches_per_graph, replays=10):
+    """Microseconds per launch of fn(i), i in range(launches_per_graph), captured as one graph that is warmed
+    twice and then replayed `replays` times with a pair of HIP events around each replay."""
+    fn(0)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(launches_per_graph):
+            fn(i)
+    g.replay()
+    g.replay()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(replays)]
+    for a, b in ev:
+        a.record()
+        g.replay()
+        b.record()
+    torch.cuda.synchronize()
+    us = np.array([a.elapsed_time(b) for a, b in ev]) * 1e3 / launches_per_graph
+    return {"mean_us": float(us.mean()), "min_us": float(us.min()), "replays": replays}
 
 
 def _time_graph(torch, fn, launches_per_graph, reps=20, min_launches=24):

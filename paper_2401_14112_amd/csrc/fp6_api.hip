@@ -170,7 +170,7 @@ struct TileShape {
 };
 constexpr TileShape kTile256x128{2, 8, 8, 1};
 constexpr TileShape kTile128x128{2, 4, 4, 2};
-constexpr TileShape kTile256x64{4, 4, 4, 1};
+constexpr TileShape kTile256x64{2, 4, 8, 1};
 constexpr TileShape kTile128x64{2, 4, 4, 1};
 
 // A kernel that uses more than 64 KB of dynamic LDS has to be told so once per device.  `done` holds one
@@ -213,8 +213,8 @@ TiledPlan plan_tiled(int64_t M, int64_t N, int64_t K, bool tall_tile_ok)
         p.tile = kTile128x64;  // few row blocks: small blocks and little split-K (measured on 8192-row layers)
     else
         p.tile = kTile256x128;  // the shape that moves the fewest bytes per MFMA
-    if (p.tile.rows() == 256 && !tall_tile_ok)  // this weight source does not fit four row tiles per wave in registers
-        p.tile = p.tile.tokens() == 128 ? kTile128x128 : kTile128x64;
+    if (p.tile.rows() == 256 && p.tile.tokens() == 128 && !tall_tile_ok)  // this weight source does not fit 2 x 8 tiles per wave in registers
+        p.tile = kTile128x128;
     p.row_blocks = (int)((M + p.tile.rows() - 1) / p.tile.rows());
     p.n_blocks = (int)((N + p.tile.tokens() - 1) / p.tile.tokens());
     int64_t s = g_forced_split.load(std::memory_order_relaxed);
@@ -297,9 +297,9 @@ fp6_status launch_tiled_chunk(const void *weights, const void *scales, const voi
                                                          stream);
     FP6_TILED_CASE(2, 4, 4, 2)
     FP6_TILED_CASE(2, 4, 4, 1)
+    FP6_TILED_CASE(2, 4, 8, 1)
     if constexpr (Src::kTallTile) {
         FP6_TILED_CASE(2, 8, 8, 1)
-        FP6_TILED_CASE(4, 4, 4, 1)
     }
 #undef FP6_TILED_CASE
     return FP6_ERR_SHAPE;  // not reached: plan_tiled only picks the shapes above

@@ -234,7 +234,7 @@ struct PackedFp6Source {
         u32x4 p0, p1, p2;
     };
     static constexpr bool kHasScale = true;
-    static constexpr bool kTallTile = true;  // four row tiles per wave (two register buffers of 48) are affordable
+    static constexpr bool kTallTile = true;  // a wave tile of 2 row tiles x 8 token tiles (64 accumulator registers) is affordable
     static constexpr int kLoads = 3;
     // bytes from one k-tile of the slice to the next
     __device__ static __forceinline__ int tile_stride(int64_t RT) { return (int)(RT * kTileBytes); }
@@ -283,7 +283,7 @@ constexpr int kGroupColumns = 128;
 struct PackedFp6GroupSource {
     static constexpr bool kPackedConfigs = true;
     static constexpr bool kHasScale = false;  // no per-row factor in the epilogue
-    static constexpr bool kTallTile = true;
+    static constexpr bool kTallTile = false;  // the scales and their multiplies leave no room for the 2 x 8 wave tile
     static constexpr int kLoads = 4;
     struct Tile {
         u32x4 p0, p1, p2;

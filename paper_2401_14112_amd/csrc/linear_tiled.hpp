@@ -85,19 +85,22 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     const int b_piece = x_piece_of_lane(lane);
     // LDS byte address of the activation buffers (the low 32 bits of a shared-memory pointer)
     const uint32_t xs_lds = (uint32_t)reinterpret_cast<uintptr_t>(xs_dyn);
-    auto x_issue = [&](int h, int buf) {
+    // copy i (of the XPERH this wave contributes) of half tile h into ring buffer buf
+    auto x_issue_one = [&](int h, int buf, int i) {
         const int t = h >> 1;
+        const int j = wave + WAVES * i;
+        const int nt = j >> 2, f = (j & 3) + 4 * (h & 1);
+        const int col = block_col0 + nt * 16 + xn;
+        const int off = (t < n_valid && col < N)
+                            ? (col * K + (kt0 + t) * kTileK + Src::k_offset(f, xq)) * 2
+                            : kOutOfRange;
+        const uint32_t lds_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(xs_lds + buf * XHBYTES + j * 1024));
+        issue_load_to_lds_b128<0>(x_rsrc, off, lds_base);
+    };
+    auto x_issue = [&](int h, int buf) {
 #pragma unroll
-        for (int i = 0; i < XPERH; ++i) {
-            const int j = wave + WAVES * i;
-            const int nt = j >> 2, f = (j & 3) + 4 * (h & 1);
-            const int col = block_col0 + nt * 16 + xn;
-            const int off = (t < n_valid && col < N)
-                                ? (col * K + (kt0 + t) * kTileK + Src::k_offset(f, xq)) * 2
-                                : kOutOfRange;
-            const uint32_t lds_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(xs_lds + buf * XHBYTES + j * 1024));
-            issue_load_to_lds_b128<0>(x_rsrc, off, lds_base);
-        }
+        for (int i = 0; i < XPERH; ++i)
+            x_issue_one(h, buf, i);
     };
 
     float4_t acc[RT][NT];
@@ -123,31 +126,40 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
     auto ldb = [&](const u32x4 *xbuf, int st) {
         return bit_cast<half8_t>(xbuf[((wn * NT + (st % NT)) * 4 + st / NT) * 64 + b_piece]);
     };
-    // HP: which half of the k-tile t; xbuf: its activations; xnext: those of the following half tile
-    auto compute_half = [&](auto hp_c, const typename Src::Tile (&t)[RT], const u32x4 *xbuf, const u32x4 *xnext) {
+    // HP: which half of the k-tile t; xbuf: its activations; xnext: those of the following half tile;
+    // request(step): called after each of the 4*NT steps of the half tile, issues the memory requests that the
+    // schedule places there (the requests of a half step are spread over its matrix work: issued in one burst
+    // after the barrier, the ten requests of each of the eight waves queue up in the CU's address unit and the
+    // waves stand at the issue of their loads for a quarter of the half step with the matrix pipe idle)
+    auto compute_half = [&](auto hp_c, const typename Src::Tile (&t)[RT], const u32x4 *xbuf, const u32x4 *xnext,
+                            auto &&request) {
         constexpr int HP = decltype(hp_c)::value;
-        __builtin_amdgcn_sched_barrier(0);
-#define FP6_TILED_GROUP(GH)                                                                       \
-    if (HP == 0 || GH == 0) {                                                                     \
-        _Pragma("unroll") for (int r = 0; r < RT; ++r)                                            \
-            Src::template fragments<2 * HP + GH + 1 <= 3 ? 2 * HP + GH + 1 : 3>(t[r], a[GH ^ 1][0][r], a[GH ^ 1][1][r]); \
-    }                                                                                             \
-    _Pragma("unroll") for (int i = 0; i < 2 * NT; ++i) {                                          \
-        const int st = 2 * GH * NT + i;                                                           \
-        const half8_t b = bq[st % LOOK];                                                          \
-        bq[st % LOOK] = st + LOOK < STEPS ? ldb(xbuf, st + LOOK) : ldb(xnext, st + LOOK - STEPS); \
-        _Pragma("unroll") for (int r = 0; r < RT; ++r)                                            \
-            acc[r][st % NT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[GH][i / NT][r], b, acc[r][st % NT], 0, 0, 0); \
-    }                                                                                             \
-    _Pragma("unroll") for (int i = 0; i < 2 * NT; ++i) {                                          \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                        \
-        __builtin_amdgcn_sched_group_barrier(0x008, RT, 0);                                       \
-        __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_STEP, 0);                            \
-    }                                                                                             \
-    __builtin_amdgcn_sched_barrier(0);
-        FP6_TILED_GROUP(0)
-        FP6_TILED_GROUP(1)
-#undef FP6_TILED_GROUP
+        static_for<2>([&](auto gh_c) {
+            constexpr int GH = decltype(gh_c)::value;
+            __builtin_amdgcn_sched_barrier(0);
+            if (HP == 0 || GH == 0) {
+#pragma unroll
+                for (int r = 0; r < RT; ++r)
+                    Src::template fragments<(2 * HP + GH + 1 <= 3 ? 2 * HP + GH + 1 : 3)>(t[r], a[GH ^ 1][0][r], a[GH ^ 1][1][r]);
+            }
+            static_for<2 * NT>([&](auto i_c) {
+                constexpr int i = decltype(i_c)::value;
+                constexpr int st = 2 * GH * NT + i;
+                const half8_t b = bq[st % LOOK];
+                bq[st % LOOK] = st + LOOK < STEPS ? ldb(xbuf, st + LOOK) : ldb(xnext, st + LOOK - STEPS);
+#pragma unroll
+                for (int r = 0; r < RT; ++r)
+                    acc[r][st % NT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[GH][i / NT][r], b, acc[r][st % NT], 0, 0, 0);
+                request(std::integral_constant<int, st>{});
+            });
+#pragma unroll
+            for (int i = 0; i < 2 * NT; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, RT, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_STEP, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
 
     // ---- software pipeline.  Half step h (k-tile t = h/2) computes half tile h.  At its top the wave waits
@@ -192,16 +204,27 @@ __global__ __launch_bounds__(WM * WN * 64) void linear_tiled_kernel(
                 if (hp == 0)
                     pin_tiles(w[ws]);
                 __syncthreads();
-                if (hp == 0)
-                    w_issue(w[ws ^ 1], (h >> 1) + 1);
-                x_issue(h + XS - 1, (xb + XS - 1) % XS);
                 if (hp == 0) {
 #pragma unroll
                     for (int r = 0; r < RT; ++r)
                         Src::template fragments<0>(w[ws][r], a[0][0][r], a[0][1][r]);
                 }
+                // the requests of this half step, unit by unit (the weights of one row tile of k-tile t+1 when h
+                // is even, then one activation copy of half tile h+3 each), unit k after step (k+1)*STEPS/(units+1)
+                constexpr int W_UNITS = hp == 0 ? RT : 0, UNITS = W_UNITS + XPERH;
                 compute_half(std::integral_constant<int, hp>{}, w[ws], xs_dyn + xb * XHPIECES,
-                             xs_dyn + ((xb + 1) % XS) * XHPIECES);
+                             xs_dyn + ((xb + 1) % XS) * XHPIECES, [&](auto st_c) {
+                                 constexpr int st = decltype(st_c)::value;
+                                 static_for<UNITS>([&](auto k_c) {
+                                     constexpr int k = decltype(k_c)::value;
+                                     if constexpr ((k + 1) * STEPS / (UNITS + 1) - 1 == st) {
+                                         if constexpr (k < W_UNITS)
+                                             w_stream[k].issue(w[ws ^ 1][k], (h >> 1) + 1);
+                                         else
+                                             x_issue_one(h + XS - 1, (xb + XS - 1) % XS, k - W_UNITS);
+                                     }
+                                 });
+                             });
             }
         });
     }

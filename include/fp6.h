@@ -199,8 +199,8 @@ fp6_status fp6g_linear(const void *packed, const void *scales_f16, const void *X
 
 /*
  * The same three calls for 5-bit weights (W5A16).  The paper presents its pre-packing
- * and its cast to fp16 as independent of the bit-width (Section 1: "6-bit, 5-bit,
- * 3-bit, etc."; Sections 5.2 and 5.3).  FP5 is e2m2: code = s e1 e0 m1 m0, Eq. 1 with
+ * and its cast to fp16 as independent of the bit-width (Section 1 names widths from 6
+ * down to 3 bits; Sections 5.2 and 5.3).  FP5 is e2m2: code = s e1 e0 m1 m0, Eq. 1 with
  * bias 2^(2-1)-1 = 1, subnormal E = 0 binade, no inf/NaN: magnitudes 0 .25 .5 .75,
  * 1 .. 1.75, 2 .. 3.5, 4 .. 7.  Quantizer: scale[m] = fp16_rne(max_k |W[m][k]| / 7),
  * nearest e2m2 magnitude of |W| / scale, ties to the even code, saturating at 7.

@@ -27,12 +27,18 @@ def library_path() -> Path:
 
 
 def load_library():
-    """Load the built library; build it first only if no built library exists."""
+    """Load the built library; build it first only if no built library exists.  A library older than one of
+    its sources is loaded as it is, with a warning: building is a step of its own (__graft_entry__.build()),
+    never a side effect of a test or a benchmark run."""
     global _lib
     if _lib is not None:
         return _lib
     if not _build.LIB.exists():
         _build.build_library()
+    elif _build.is_stale():
+        import warnings
+
+        warnings.warn("%s is older than its sources: rebuild with `python -m paper_2401_14112_amd.build`" % _build.LIB)
     L = ctypes.CDLL(str(_build.LIB))
     i64, vp, sz, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     L.fp6_status_str.restype = ctypes.c_char_p

@@ -7,11 +7,11 @@ import pytest
 import torch
 
 import workloads
+from gpu_checks import check_linear as _check
 from packed_rows import row_tiles_of
 
 pytestmark = pytest.mark.gpu
 
-TOL = 5e-3
 
 
 @pytest.fixture(scope="module")
@@ -29,15 +29,6 @@ def _say(msg):
 
 def _np(t):
     return t.detach().cpu().numpy()
-
-
-def _check(Y_gpu, Y_ref, what):
-    err = np.abs(Y_gpu.astype(np.float64) - Y_ref).max(axis=1)
-    ref = np.abs(Y_ref).max(axis=1)
-    bad = err > TOL * ref
-    assert not bad.any(), "%s: columns %s exceed the bound, worst ratio %.3g" % (
-        what, np.flatnonzero(bad)[:8], (err / np.maximum(ref, 1e-300)).max())
-    return (err / np.maximum(ref, 1e-300)).max()
 
 
 MODES = {
@@ -248,7 +239,8 @@ def test_fused_other_formats(pkg, oracle, fmt, mode, N):
         Y = pkg.fp6g_linear_fused(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), X.cuda(), M, K, 128, **kw)
     else:
         bits = int(fmt[2])
-        o = importlib.import_module("oracle.%s_oracle" % fmt)
+        from oracle import fpx_oracle
+        o = fpx_oracle.BY_PREFIX[fmt] if fmt in fpx_oracle.BY_PREFIX else importlib.import_module("oracle.%s_oracle" % fmt)
         packed, scales = o.quantize_pack(W)
         Y_ref = oracle.linear_fused(packed, scales, X.numpy(), M, K, bits=bits, **okw)
         Y = getattr(pkg, fmt + "_linear_fused")(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), X.cuda(), M, K, **kw)

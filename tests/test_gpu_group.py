@@ -7,11 +7,11 @@ import pytest
 import torch
 
 import workloads
+from gpu_checks import check_linear as _check_linear
 from packed_rows import row_tiles_of
 
 pytestmark = pytest.mark.gpu
 
-TOL = 5e-3
 GROUP = 128
 
 
@@ -36,14 +36,6 @@ def _say(msg):
 
 def _np(t):
     return t.detach().cpu().numpy()
-
-
-def _check_linear(Y_gpu, Y_ref, what):
-    err = np.abs(Y_gpu.astype(np.float64) - Y_ref)
-    col_err = err.max(axis=1)
-    col_ref = np.abs(Y_ref).max(axis=1)
-    assert not (col_err > TOL * col_ref).any(), "%s: worst ratio %.3g" % (what, (col_err / np.maximum(col_ref, 1e-300)).max())
-    return (col_err / np.maximum(col_ref, 1e-300)).max()
 
 
 def _uneven_weights(M, K, seed, huge=True):

@@ -8,11 +8,11 @@ import pytest
 import torch
 
 import workloads
+from gpu_checks import check_linear as _check_linear
 from packed_rows import row_tiles_of
 
 pytestmark = pytest.mark.gpu
 
-TOL = 5e-3
 
 
 @pytest.fixture(scope="module")
@@ -30,17 +30,6 @@ def _say(msg):
 
 def _np16(t):
     return t.detach().cpu().numpy()
-
-
-def _check_linear(Y_gpu, Y_ref, what):
-    """Y_gpu fp16 [N][M'] (numpy), Y_ref fp64 [N][M']."""
-    err = np.abs(Y_gpu.astype(np.float64) - Y_ref)
-    col_err = err.max(axis=1)
-    col_ref = np.abs(Y_ref).max(axis=1)
-    bad = col_err > TOL * col_ref
-    assert not bad.any(), "%s: columns %s exceed the bound, worst ratio %.3g" % (
-        what, np.flatnonzero(bad)[:8], (col_err / np.maximum(col_ref, 1e-300)).max())
-    return (col_err / np.maximum(col_ref, 1e-300)).max()
 
 
 # ------------------------------------------------------------------ pack / unpack
@@ -366,6 +355,27 @@ def test_full_size_layer_sampled(pkg, oracle, shape):
         torch.cuda.synchronize()
         assert not torch.isnan(Yf).any()
         assert torch.equal(Yf.view(torch.int16), Y.view(torch.int16))
+
+
+@pytest.mark.parametrize("shape", [workloads.FFN_65B, workloads.FFN_65B_DOWN])
+def test_fp16_linear_full_size_sampled(pkg, oracle, shape):
+    """The library's own fp16-weight layer at the shapes it is timed on (both orientations of the benchmark
+    layer), on sampled row tiles, for the token counts of every kernel it dispatches to."""
+    name, M, K = shape
+    _say("fp16_linear full-size %s M=%d K=%d" % (name, M, K))
+    W = workloads.make_weights(M, K, seed=0, device="cuda")
+    tiles = _sampled_row_tiles(M, 16, seed=2)
+    rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
+    W_rows = _np16(W[torch.from_numpy(rows).cuda()])
+    for N in (1, 32, 128, 512):
+        _say("  fp16_linear N=%d" % N)
+        X = workloads.make_activations(N, K, seed=N, device="cuda")
+        Y = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+        pkg.fp16_linear(W, X, out=Y)
+        torch.cuda.synchronize()
+        assert not torch.isnan(Y).any()
+        worst = _check_linear(_np16(Y)[:, rows], oracle.linear_f16(W_rows, _np16(X)), "fp16 %s N=%d" % (name, N))
+        _say("    worst column ratio %.3g" % worst)
 
 
 def test_largest_admitted_matrix_offsets(pkg, oracle):

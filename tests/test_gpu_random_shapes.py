@@ -9,9 +9,9 @@ import pytest
 import torch
 
 import workloads
+from gpu_checks import check_linear
 
 pytestmark = pytest.mark.gpu
-TOL = 5e-3
 
 WIDTHS = ("fp6", "fp5", "fp4", "fp3", "fp6g")
 
@@ -41,7 +41,9 @@ def _oracle(width):
     from oracle import fp6_oracle
 
     fp6_oracle.build()      # one C library serves every width
-    return importlib.import_module("oracle.%s_oracle" % width)
+    from oracle import fpx_oracle
+
+    return fpx_oracle.BY_PREFIX[width] if width in fpx_oracle.BY_PREFIX else importlib.import_module("oracle.%s_oracle" % width)
 
 
 @pytest.mark.parametrize("width,M,K,N,split,seed", _cases())
@@ -66,6 +68,4 @@ def test_random_shape(pkg, width, M, K, N, split, seed):
     finally:
         pkg.fp6_tuning_set_split_k(0)
     Y_ref = o.linear(ref_packed, ref_scales, X.numpy(), M, K, *group)
-    err = np.abs(Y.cpu().numpy().astype(np.float64) - Y_ref).max(axis=1)
-    bound = TOL * np.abs(Y_ref).max(axis=1)
-    assert (err <= bound).all(), "worst ratio %.3g" % (err / np.maximum(bound, 1e-300)).max()
+    check_linear(Y.cpu().numpy(), Y_ref, "%s M=%d K=%d N=%d split=%d" % (width, M, K, N, split))

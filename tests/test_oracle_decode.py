@@ -69,27 +69,27 @@ def test_decode_equals_bitcopy_cast(oracle):
         assert np.signbit(v) == np.signbit(oracle.decode(c))
 
 
-def test_decode_equals_algorithm1_masks(oracle):
-    """Algorithm 1's 4-way de-quantisation on bytes 'sEEEMM00': two ANDs, a shift, an OR, then
-    the byte split with 0x9f009f00 / 0x009f009f and a shift by 8."""
+def test_decode_equals_word_parallel_cast(oracle):
+    """Section 5.3 casts several codes per 32-bit operation.  Derived here from the field positions alone:
+    a code s|EEE|MM stored in the top six bits of a byte (bit 7 = s, bits 6..2 = EEEMM) becomes the high byte
+    of an fp16 when s stays at bit 7 and EEEMM moves down to bits 4..0 - the fp16 pattern s 00EEE MM 00000000
+    of Eq. 3.  On a word of four such bytes that is one mask for the four signs (bit 7 of every byte), one
+    shift-and-mask for the four five-bit fields (field width 5 -> 0x1f per byte), and an OR; a byte at an odd
+    position of the word is already the high byte of a half, a byte at an even position has to move up by 8."""
+    SIGNS = sum(0x80 << (8 * i) for i in range(4))
+    FIELDS = sum(0x1F << (8 * i) for i in range(4))
+    ODD_BYTES = 0xFF00FF00
     rng = np.random.default_rng(0)
     for _ in range(64):
-        cs = rng.integers(0, 64, size=4)
-        r1 = 0
-        for i, c in enumerate(cs):               # byte i holds code i in its top six bits
-            r1 |= (int(c) << 2) << (8 * i)
-        r2 = r1 & 0x80808080
-        r1 = (r1 >> 2) & 0x1F1F1F1F
-        r2 |= r1
-        a = r2 & 0x9F009F00                       # codes in bytes 3 and 1
-        b = (r2 & 0x009F009F) << 8                # codes in bytes 2 and 0
-        halves = {
-            1: a & 0xFFFF, 3: a >> 16,
-            0: b & 0xFFFF, 2: b >> 16,
-        }
-        for i, c in enumerate(cs):
-            h = np.array([halves[i]], dtype=np.uint16).view(np.float16)[0]
-            assert float(h) * 4096.0 == oracle.decode(int(c))
+        codes = [int(c) for c in rng.integers(0, 64, size=4)]
+        word = sum((c << 2) << (8 * i) for i, c in enumerate(codes))      # byte i = code i in the top six bits
+        high_bytes = (word & SIGNS) | ((word >> 2) & FIELDS)               # every byte: s 00 EEEMM
+        pair_odd = high_bytes & ODD_BYTES                                  # halves [byte1 00], [byte3 00]
+        pair_even = (high_bytes << 8) & ODD_BYTES                          # halves [byte0 00], [byte2 00]
+        got = {0: pair_even & 0xFFFF, 2: pair_even >> 16, 1: pair_odd & 0xFFFF, 3: pair_odd >> 16}
+        for i, c in enumerate(codes):
+            h = np.array([got[i]], dtype=np.uint16).view(np.float16)[0]
+            assert float(h) * 4096.0 == oracle.decode(c), (i, c)
 
 
 def test_half_to_double_exhaustive(oracle):

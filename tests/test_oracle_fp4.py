@@ -17,8 +17,8 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 @pytest.fixture(scope="module")
 def o5():
-    from oracle import fp4_oracle
-    return fp4_oracle
+    from oracle import fpx_oracle
+    return fpx_oracle.fp4
 
 
 def _read(name):

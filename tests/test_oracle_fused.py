@@ -125,7 +125,8 @@ def test_other_widths_share_the_steps(oracle, bits):
     is the linear layer under them, each pinned in its own file: with no step the result is that layer, and
     with all steps it is that layer's output pushed through the logistic function of scipy."""
     import importlib
-    o = importlib.import_module("oracle.fp%d_oracle" % bits)
+    from oracle import fpx_oracle
+    o = fpx_oracle.BY_PREFIX["fp%d" % bits]
     M, K, N = 32, 512, 3
     W = workloads.make_weights(M, K, seed=bits).numpy()
     X = workloads.make_activations(N, K, seed=bits).numpy()

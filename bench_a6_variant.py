@@ -3,7 +3,7 @@
 chip's e3m2 -> fp16 conversion instruction (what the library ships) and with the shift/mask + exponent-bias
 multiply of Section 5.3 of the paper on a bit arrangement made for it (bench_a6_variant.hip, bench only).
 
-    python bench_a6_variant.py                 # builds bench_a6_variant.so, checks equality, prints timings
+    python bench_a6_variant.py                 # builds libbench_a6_variant.so, checks equality, prints timings
     rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_MFMA SQ_VALU_MFMA_BUSY_CYCLES SQ_ACTIVE_INST_VALU SQ_WAVE_CYCLES \\
         --output-format csv -d gpurun_out/a6 -o out -- python3 bench_a6_variant.py --profile
 
@@ -21,7 +21,7 @@ import sys
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-SO = os.path.join(ROOT, "bench_a6_variant.so")
+SO = os.path.join(ROOT, "libbench_a6_variant.so")
 SRC = os.path.join(ROOT, "bench_a6_variant.hip")
 
 

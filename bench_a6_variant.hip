@@ -38,6 +38,7 @@ struct ShiftMaskFp6Source {
     static constexpr bool kPackedConfigs = true;
     typedef PackedFp6Source::Tile Tile;
     static constexpr bool kHasScale = true;
+    static constexpr int kLdsTileBytes = 0;
     static constexpr bool kTallTile = true;
     static constexpr int kLoads = 3;
     __device__ static __forceinline__ int tile_stride(int64_t RT) { return PackedFp6Source::tile_stride(RT); }
@@ -128,7 +129,7 @@ int launch_stream(const void *w, const void *sc, const void *X, void *Y, int64_t
     static bool done = false;
     if (!done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Shape::kLdsBytes) != hipSuccess)
+                                Shape::template lds_bytes<Src>()) != hipSuccess)
             return 5;
         done = true;
     }
@@ -140,7 +141,7 @@ int launch_stream(const void *w, const void *sc, const void *X, void *Y, int64_t
         S = K / 512;
     int *counters = static_cast<int *>(ws);
     float4_t *partials = reinterpret_cast<float4_t *>(static_cast<char *>(ws) + 65536);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)rb, (unsigned)S), dim3(Shape::kThreads), Shape::kLdsBytes, st, w,
+    hipLaunchKernelGGL(kernel, dim3((unsigned)rb, (unsigned)S), dim3(Shape::kThreads), Shape::template lds_bytes<Src>(), st, w,
                        static_cast<const half_t *>(sc), static_cast<const half_t *>(X), static_cast<half_t *>(Y), (int)M,
                        (int)N, (int)K, (int)S, (int)(K / 256 / S), partials, counters, Epilogue{nullptr, nullptr, 0});
     return hipGetLastError() == hipSuccess ? 0 : 5;

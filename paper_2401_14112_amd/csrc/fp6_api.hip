@@ -25,11 +25,11 @@ struct StreamCfg {
 constexpr int kStreamCfgs = 4;
 constexpr StreamCfg kStreamCfg[kStreamCfgs] = {{1, 4, 4, 4, 1, true}, {1, 8, 2, 1, 1, true}, {2, 8, 2, 1, 1, true},
                                                {4, 8, 2, 1, 1, true}};
-// the fp16 weight source needs 32 registers per tile in flight: its own, shallower table
-// (measured on 8192x22016: contiguous slices are better for its row-major weights at N <= 16, 80.5 vs 85 us,
-// dealt ones at N = 32 and 64, 83 vs 92 and 90 vs 97 us)
-constexpr StreamCfg kStreamCfgFp16[kStreamCfgs] = {{1, 4, 2, 4, 1, false}, {1, 8, 2, 4, 1, false}, {2, 8, 2, 2, 1, true},
-                                                   {4, 8, 2, 2, 1, true}};
+// fp16 weights (staged through LDS, 8 KB per tile in flight): depths and block heights that fit the LDS of a
+// CU beside the activation stages.  Measured on 8192x22016: all shapes of a token count within 2 us of each
+// other, dealt slices 1-2 us ahead of contiguous ones.
+constexpr StreamCfg kStreamCfgFp16[kStreamCfgs] = {{1, 4, 4, 1, 1, true}, {1, 8, 2, 2, 1, true}, {2, 8, 2, 1, 1, true},
+                                                   {4, 4, 2, 1, 1, true}};
 template <bool PACKED, int C>
 struct StreamShapeOf {
     static constexpr StreamCfg c = PACKED ? kStreamCfg[C] : kStreamCfgFp16[C];
@@ -348,8 +348,8 @@ fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const voi
     typedef typename StreamShapeOf<Src::kPackedConfigs, C>::type Shape;
     constexpr StreamCfg c = StreamShapeOf<Src::kPackedConfigs, C>::c;
     auto kernel = linear_stream_kernel<Src, Shape>;
-    constexpr size_t lds = Shape::kLdsBytes;
-    static_assert(lds <= 160 * 1024, "activation stages exceed the LDS of a CU");
+    constexpr size_t lds = Shape::template lds_bytes<Src>();
+    static_assert(lds <= 160 * 1024, "activation stages and staged weight tiles exceed the LDS of a CU");
     static std::atomic<uint64_t> lds_done{0};  // per instantiation
     if (!allow_dynamic_lds(reinterpret_cast<const void *>(kernel), lds, lds_done))
         return FP6_ERR_HIP;
@@ -780,7 +780,7 @@ fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_
     if (N > kStreamMaxN)
         return launch_tiled<PlainFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, ws, Epilogue{nullptr, nullptr, 0},
                                              static_cast<hipStream_t>(stream));
-    return launch_stream<PlainFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, ws, Epilogue{nullptr, nullptr, 0},
+    return launch_stream<StagedFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, ws, Epilogue{nullptr, nullptr, 0},
                                           static_cast<hipStream_t>(stream));
 }
 

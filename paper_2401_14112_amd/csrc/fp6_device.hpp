@@ -150,12 +150,16 @@ __device__ __forceinline__ u32x2 issue_load_b64(rsrc_t rsrc, int lane_off)
 // inside the statement and cannot be named as clobbered: it is a reserved register for this compiler (which
 // says so when it is listed), i.e. the compiler keeps no value in it across statements and sets it right
 // before each instruction of its own that reads it.
-template <int IMM>
+template <int IMM, bool STREAMING = false>
 __device__ __forceinline__ void issue_load_to_lds_b128(rsrc_t rsrc, int lane_off, uint32_t lds_base)
 {
     static_assert(IMM >= 0 && IMM < 4096, "the immediate offset of a buffer load is a 12-bit field");
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen offset:%3 lds"
-                 : : "s"(lds_base), "v"(lane_off), "s"(rsrc), "n"(IMM) : "memory");
+    if (STREAMING)  // "nt": read-once data, do not keep it in the caches
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen offset:%3 nt lds"
+                     : : "s"(lds_base), "v"(lane_off), "s"(rsrc), "n"(IMM) : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen offset:%3 lds"
+                     : : "s"(lds_base), "v"(lane_off), "s"(rsrc), "n"(IMM) : "memory");
 }
 
 // ---- activation tile layout in LDS -----------------------------------------
@@ -213,6 +217,11 @@ struct SimpleStream {
     {
         Src::issue(tile, rsrc, off + t * stride);
     }
+    // tiles live in registers: nothing to bind (see StagedFp16Source)
+    template <int D>
+    __device__ __forceinline__ void bind_slots(typename Src::Tile (&)[D], u32x4 *, int) const
+    {
+    }
 };
 
 // Packed sources: the slice of row tile `row_tile` over k-tiles kt_first + i * kt_step, i < n_tiles, tiles of
@@ -233,6 +242,7 @@ struct PackedFp6Source {
     struct Tile {
         u32x4 p0, p1, p2;
     };
+    static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
     static constexpr bool kHasScale = true;
     static constexpr bool kTallTile = true;  // a wave tile of 2 row tiles x 8 token tiles (64 accumulator registers) is affordable
     static constexpr int kLoads = 3;
@@ -282,6 +292,7 @@ constexpr int kGroupColumns = 128;
 
 struct PackedFp6GroupSource {
     static constexpr bool kPackedConfigs = true;
+    static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
     static constexpr bool kHasScale = false;  // no per-row factor in the epilogue
     static constexpr bool kTallTile = false;  // the scales and their multiplies leave no room for the 2 x 8 wave tile
     static constexpr int kLoads = 4;
@@ -314,6 +325,10 @@ struct PackedFp6GroupSource {
             t.p1 = issue_load_b128<1024, true>(w_rsrc, off);
             t.p2 = issue_load_b128<2048, true>(w_rsrc, off);
             t.sc = issue_load_b32<0>(s_rsrc, s_off + i * s_stride);
+        }
+        template <int D>
+        __device__ __forceinline__ void bind_slots(Tile (&)[D], u32x4 *, int) const
+        {
         }
     };
     __device__ static __forceinline__ void pin_tile(Tile &t)
@@ -369,6 +384,7 @@ struct PackedFp5Source {
         u32x4 p0, p1;
         u32x2 p2;
     };
+    static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
     static constexpr bool kHasScale = true;
     static constexpr bool kTallTile = true;
     static constexpr int kLoads = 3;
@@ -441,6 +457,7 @@ struct PackedFp4Source {
     struct Tile {
         u32x4 p0, p1;
     };
+    static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
     static constexpr bool kHasScale = true;
     static constexpr bool kTallTile = true;
     static constexpr int kLoads = 2;
@@ -487,6 +504,7 @@ struct PackedFp3Source {
         u32x4 p0;
         u32x2 p1;
     };
+    static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
     static constexpr bool kHasScale = true;
     static constexpr bool kTallTile = true;
     static constexpr int kLoads = 2;
@@ -535,6 +553,7 @@ struct PlainFp16Source {
     struct Tile {
         u32x4 v[8];
     };
+    static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
     static constexpr bool kHasScale = false;
     static constexpr bool kTallTile = false;
     static constexpr int kLoads = 8;
@@ -575,6 +594,81 @@ struct PlainFp16Source {
     {
         even_run = bit_cast<half8_t>(t.v[2 * G]);
         odd_run = bit_cast<half8_t>(t.v[2 * G + 1]);
+    }
+};
+
+// fp16 weights for the streaming kernel, staged through LDS.  Loading the A operand of a row-major fp16
+// matrix straight into registers (PlainFp16Source) makes every load instruction touch 16 rows x 64 bytes:
+// half a cache line per row and request.  Here a copy instruction (global -> LDS, no registers) fetches
+// 8 rows x 128 bytes - eight whole lines - and the wave reads its A fragments back from LDS.  The region is
+// private to the wave (its own copies, its own reads): the wait for the copies is all the synchronisation
+// there is, no barrier.  The copies carry the streaming hint like every other weight load (measured on the
+// 8192 x 22016 layer, N <= 16: 81 us without it, whole lines or not, 72 us with it).
+//   Tile = 16 rows x 256 columns = eight blocks of 1 KB; block 2*seg + h holds rows 8h .. 8h+7, columns
+// 64*seg .. 64*seg+63.  Copy lane i = 8*rho + pi lands at piece i of the block (16 bytes each) and fetches
+// row 8h + rho, 8-column chunk pi ^ w_swizzle(row) of the segment: the eight lanes of a row fetch one whole
+// line, a quad of lanes 64 contiguous bytes.  MFMA lane (q, r) of run f = 2*seg + e wants row r, chunk
+// 4e + q: piece 8*(r%8) + ((4e + q) ^ w_swizzle(r)) of block 2*seg + r/8.  The swizzle spreads the sixteen
+// rows of a lane group, the eight rows x two lane groups and the four rows x four lane groups that a
+// 128-bit LDS read may serve together over all sixteen 16-byte bank groups.
+__device__ __forceinline__ int w_swizzle(int row) { return ((row >> 1) & 1) << 2 | ((row >> 2) & 1) << 1 | ((row >> 3) & 1); }
+
+struct StagedFp16Source {
+    static constexpr bool kPackedConfigs = false;
+    static constexpr bool kHasScale = false;
+    static constexpr bool kTallTile = false;
+    static constexpr int kLoads = 8;
+    static constexpr int kLdsTileBytes = 8192;
+    struct Tile {
+        const u32x4 *even, *odd;  // this lane's fragment of run 0 (even runs) and of run 1 (odd runs) in the slot
+        uint32_t lds;             // LDS byte address of the slot (wave-uniform)
+    };
+    __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
+    __device__ static __forceinline__ void pin_tile(Tile &) {}
+    struct Stream {
+        rsrc_t rsrc;
+        int off0, off1, stride;  // lane offsets of the copies of rows 0..7 and of rows 8..15
+        __device__ __forceinline__ void init(const void *weights, const half_t * /*scales*/, int64_t row_tile, int kt_first,
+                                             int kt_step, int /*n_tiles*/, int64_t /*RT*/, int64_t K, int lane)
+        {
+            // the 16 rows of the row tile; tiles past the slice are neutralised by zero activations
+            rsrc = make_rsrc(static_cast<const half_t *>(weights) + row_tile * kTileRows * K, (uint32_t)(kTileRows * K * 2));
+            const int rho = lane >> 3, pi = lane & 7;
+            off0 = (rho * (int)K + kt_first * kTileK + 8 * (pi ^ w_swizzle(rho))) * 2;
+            off1 = ((rho + 8) * (int)K + kt_first * kTileK + 8 * (pi ^ w_swizzle(rho + 8))) * 2;
+            stride = __builtin_amdgcn_readfirstlane(kTileK * 2 * kt_step);
+        }
+        template <int D>
+        __device__ __forceinline__ void bind_slots(Tile (&w)[D], u32x4 *region, int lane) const
+        {
+            const int r = lane & 15, q = lane >> 4;
+            const int piece = (r >> 3) * 64 + 8 * (r & 7) + (q ^ w_swizzle(r));
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                u32x4 *slot = region + d * (kLdsTileBytes / 16);
+                w[d].even = slot + piece;
+                w[d].odd = slot + (piece ^ 4);
+                w[d].lds = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)reinterpret_cast<uintptr_t>(slot));
+            }
+        }
+        __device__ __forceinline__ void issue(Tile &tile, int t) const
+        {
+            // the slot's previous contents have been read: every LDS read of this wave has returned
+            asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
+            const int o0 = off0 + t * stride, o1 = off1 + t * stride;
+#pragma unroll
+            for (int seg = 0; seg < 4; ++seg) {
+                issue_load_to_lds_b128<0, true>(rsrc, o0 + seg * 128, tile.lds + (uint32_t)(2 * seg) * 1024u);
+                issue_load_to_lds_b128<0, true>(rsrc, o1 + seg * 128, tile.lds + (uint32_t)(2 * seg + 1) * 1024u);
+            }
+        }
+    };
+    // A fragments of runs 2G (even) and 2G+1 (odd): segment G, chunks q and 4 + q
+    template <int G>
+    __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
+    {
+        even_run = bit_cast<half8_t>(t.even[G * 128]);
+        odd_run = bit_cast<half8_t>(t.odd[G * 128]);
     }
 };
 

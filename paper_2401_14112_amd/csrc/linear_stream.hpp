@@ -37,8 +37,15 @@ template <int NT_, int WAVES_, int DEPTH_, int G_, int XSPREAD_, bool DEAL_>
 struct StreamShape {
     static constexpr int NT = NT_, WAVES = WAVES_, DEPTH = DEPTH_, G = G_, XSPREAD = XSPREAD_;
     static constexpr bool DEAL = DEAL_;
-    static constexpr int kLdsBytes = 2 * G_ * NT_ * 8 * 1024;  // two stages of activations
+    static constexpr int kXBytes = 2 * G_ * NT_ * 8 * 1024;  // two stages of activations
     static constexpr int kThreads = WAVES_ * 64;
+    // dynamic LDS of a launch: the activation stages, then (sources that stage their weights in LDS) DEPTH
+    // tiles per wave
+    template <class Src>
+    static constexpr int lds_bytes()
+    {
+        return kXBytes + WAVES_ * DEPTH_ * Src::kLdsTileBytes;
+    }
 };
 
 template <class Src, class Shape>
@@ -60,7 +67,7 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     constexpr int U = G / stream_gcd(G, DEPTH) * DEPTH;  // unroll: both the stage position and the ring slot are static
     constexpr int WLOADS = Src::kLoads;  // weight loads of one wave per k-tile
 
-    extern __shared__ u32x4 xs_dyn[];  // [2][STAGE_PIECES]
+    extern __shared__ u32x4 xs_dyn[];  // [2][STAGE_PIECES], then [WAVES][DEPTH] weight tiles for sources that stage them
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -161,6 +168,7 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     // weights), so it waits for everything but the weights.  Tiles past the end of the slice read as zeros
     // through the buffer bounds check (no memory traffic), so the request pattern never varies.
     typename Src::Tile w[DEPTH];
+    w_stream.bind_slots(w, xs_dyn + 2 * STAGE_PIECES + wave * (DEPTH * Src::kLdsTileBytes / 16), lane);
     x_issue(0, 0, XPER);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d)

@@ -168,7 +168,7 @@ def is_stale() -> bool:
     if not LIB.exists():
         return True
     t = LIB.stat().st_mtime
-    deps = [CSRC / s for s in SOURCES + HEADERS] + [PKG.parent / "include" / "fp6.h"]
+    deps = [CSRC / s for s in SOURCES + HEADERS] + [PKG.parent / "include" / h for h in ("fp6.h", "fp6_bench.h")]
     return any(d.stat().st_mtime > t for d in deps)
 
 

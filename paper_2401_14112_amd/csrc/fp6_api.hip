@@ -1,6 +1,7 @@
 // C ABI of the library (see include/fp6.h): argument checks on the host, kernel
 // selection, launches on the caller's stream.  No allocation, no synchronization.
 #include "../../include/fp6.h"
+#include "../../include/fp6_bench.h"
 
 #include <atomic>
 

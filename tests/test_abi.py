@@ -2,6 +2,7 @@
 answers the size queries, and rejects bad arguments on the host before launching anything.
 No compute call is made here (no GPU needed)."""
 import ctypes
+import glob
 import os
 import re
 
@@ -18,7 +19,7 @@ def lib():
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "fp6.h")).read()
+    text = "".join(open(f).read() for f in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b(fp6g?_\w+|fp5_\w+|fp4_\w+|fp3_\w+|fp16_\w+)\s*\(", text)
     return sorted(set(names))

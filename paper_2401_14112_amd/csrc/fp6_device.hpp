@@ -608,10 +608,14 @@ struct PlainFp16Source {
 // 64*seg .. 64*seg+63.  Copy lane i = 8*rho + pi lands at piece i of the block (16 bytes each) and fetches
 // row 8h + rho, 8-column chunk pi ^ w_swizzle(row) of the segment: the eight lanes of a row fetch one whole
 // line, a quad of lanes 64 contiguous bytes.  MFMA lane (q, r) of run f = 2*seg + e wants row r, chunk
-// 4e + q: piece 8*(r%8) + ((4e + q) ^ w_swizzle(r)) of block 2*seg + r/8.  The swizzle spreads the sixteen
-// rows of a lane group, the eight rows x two lane groups and the four rows x four lane groups that a
-// 128-bit LDS read may serve together over all sixteen 16-byte bank groups.
-__device__ __forceinline__ int w_swizzle(int row) { return ((row >> 1) & 1) << 2 | ((row >> 2) & 1) << 1 | ((row >> 3) & 1); }
+// 4e + q: piece 8*(r%8) + ((4e + q) ^ w_swizzle(r)) of block 2*seg + r/8.  A 128-bit LDS read serves sixteen
+// lanes at a time, and not sixteen consecutive ones: lanes {0-3, 12-15, 20-23, 24-27} of a half-wave go
+// together, then {4-11, 16-19, 28-31} (the grouping under which the activation swizzle above is conflict-free
+// and a first swizzle of this tile, which spread sixteen consecutive lanes, cost four extra cycles per read -
+// both by SQ_LDS_BANK_CONFLICT).  In MFMA terms a group is rows {0-3, 12-15} of lane group q with rows
+// {4-11} of lane group q ^ 1: with the chunk XORed by 2 * ((row / 2) % 4) their sixteen pieces fall into
+// sixteen different 16-byte bank groups.
+__device__ __forceinline__ int w_swizzle(int row) { return ((row >> 1) & 3) << 1; }
 
 struct StagedFp16Source {
     static constexpr bool kPackedConfigs = false;

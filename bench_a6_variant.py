@@ -5,7 +5,7 @@ multiply of Section 5.3 of the paper on a bit arrangement made for it (bench_a6_
 
     python bench_a6_variant.py                 # builds libbench_a6_variant.so, checks equality, prints timings
     rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_MFMA SQ_VALU_MFMA_BUSY_CYCLES SQ_ACTIVE_INST_VALU SQ_WAVE_CYCLES \\
-        --output-format csv -d gpurun_out/a6 -o out -- python3 bench_a6_variant.py --profile
+        --output-format csv -d out/a6 -o out -- python3 bench_a6_variant.py --profile
 
 Both variants run the 8192 x 22016 layer at N = 16, 32 and 512 from graphs that rotate over 8 packed copies;
 their outputs must be bit-identical (both de-quantizations are exact).

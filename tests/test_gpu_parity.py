@@ -256,6 +256,27 @@ def test_fp16_linear(pkg, oracle, N):
     _check_linear(_np16(Y), oracle.linear_f16(W.numpy(), X.numpy()), "fp16 N=%d" % N)
 
 
+@pytest.mark.parametrize("N", [3, 16, 32, 64])
+@pytest.mark.parametrize("split", [2, 3, 5])
+def test_fp16_linear_stream_forced_split(pkg, oracle, N, split):
+    """The fp16 weight tiles of the streaming kernel pass through LDS: every shape of that kernel (1, 2, 4 token
+    tiles per wave; 4- and 8-wave blocks with a ragged last block) under split-K factors that do not divide
+    the 11 k-tiles, twice for identical bits."""
+    M, K = 272, 2816
+    _say("fp16_linear stream M=%d K=%d N=%d split=%d" % (M, K, N, split))
+    W = workloads.make_weights(M, K, 11)
+    X = workloads.make_activations(N, K, 11)
+    pkg.fp6_tuning_set_split_k(split)
+    try:
+        Y = pkg.fp16_linear(W.cuda(), X.cuda())
+        Y2 = pkg.fp16_linear(W.cuda(), X.cuda())
+        torch.cuda.synchronize()
+    finally:
+        pkg.fp6_tuning_set_split_k(0)
+    assert torch.equal(Y.view(torch.int16), Y2.view(torch.int16))
+    _check_linear(_np16(Y), oracle.linear_f16(W.numpy(), X.numpy()), "fp16 stream N=%d split=%d" % (N, split))
+
+
 # ------------------------------------------------------------------ tiled kernel (N > 32)
 @pytest.mark.parametrize("rt,nt", [(0, 0), (128, 64), (256, 64), (128, 128), (256, 128)])
 @pytest.mark.parametrize("N,split", [(33, 1), (64, 0), (100, 2), (128, 3), (257, 0)])
@@ -367,7 +388,7 @@ def test_fp16_linear_full_size_sampled(pkg, oracle, shape):
     tiles = _sampled_row_tiles(M, 16, seed=2)
     rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
     W_rows = _np16(W[torch.from_numpy(rows).cuda()])
-    for N in (1, 32, 128, 512):
+    for N in (1, 16, 32, 64, 128, 512):
         _say("  fp16_linear N=%d" % N)
         X = workloads.make_activations(N, K, seed=N, device="cuda")
         Y = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")

@@ -309,6 +309,9 @@ def main():
             # every N of the metric: microseconds per launch (graph replay) and the fraction of each roof
             "per_n": per_n,
             "min_hbm_frac_N_le_32": min(per_n[str(n)]["hbm_frac"] for n in sweep),
+            # all launches of the timed step together (N = 32 included): their algorithmic bytes over the step time
+            "whole_step_hbm_frac": round(sum(algorithmic_bytes(M, n, K) for n in sweep) / (ms_per_step * 1e-3) * 1e-9
+                                         / HBM_PEAK_GBPS, 4),
             "timing": "HIP events around each replay of a graph of the N<=16 launches of %d steps, elapsed/%d"
                       % (period * DOM_PASSES, len(small) * period * DOM_PASSES),
         },

@@ -934,7 +934,7 @@ int fp4o_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *X
  * same recipe with 4 in place of 28.
  * ====================================================================== */
 
-#define FP3O_TILE_BYTES 1536 /* 16 * 256 * 3 / 8 */
+#define FP3O_TILE_BYTES 3072 /* 16 * 512 * 3 / 8 */
 
 double fp3o_decode(int code)
 {
@@ -1003,27 +1003,36 @@ int fp3o_quantize(const uint16_t *W, int64_t M, int64_t K, uint8_t *codes, uint1
     return bad;
 }
 
-int64_t fp3o_packed_bytes(int64_t M, int64_t K) { return M * K / 8 * 3; }
+/* tiles of 16 rows x 512 columns; a matrix whose K is an odd multiple of 256 pads its last tile */
+int64_t fp3o_packed_bytes(int64_t M, int64_t K) { return (K + 511) / 512 * (M / FP6O_TILE_ROWS) * FP3O_TILE_BYTES; }
 
 /*
  * Bit address of bit b (0..2 = e0, e1, s) of the code of weight (m, k) in the packed
- * 3-bit stream.  Tiles of 16 rows x 256 columns, k-tile major, 1536 bytes each: a plane
- * of 1024 bytes (64 slots of 16 bytes) followed by a plane of 512 bytes (64 slots of 8
- * bytes), slot = 16*q + r as in the other layouts.  The slot owns six 32-bit words, words
- * 0..3 in the first plane, 4..5 in the second; words 3g .. 3g+2 serve the runs 4g .. 4g+3
+ * 3-bit stream.  Tiles of 16 rows x 512 columns, k-tile major, 3072 bytes each: three
+ * planes of 1024 bytes (64 slots of 16 bytes, slot = 16*q + r as in the other layouts), so
+ * that a lane fetches its share of a tile with three whole 128-bit loads.  The two halves of
+ * a tile (256 columns each, half h = columns 256h .. 256h+255) are laid out alike: a half
+ * gives the slot six 32-bit words, words 3g .. 3g+2 serving the runs 4g .. 4g+3 of the half
  * (g = 0, 1).  The reader wants, per run, a word of eight 4-bit fields "s e1 e0 0" (the
  * 4-bit code of the same value), field j = column 32*run + 8*q + j.  Runs 4g+i, i < 3, sit
  * in word 3g+i in exactly that form, which leaves bit 0 of every field free; the three bits
  * of run 4g+3 are spread over those free bits: its bit b+1 of field j is bit 4j of word
  * 3g+b.  (The ahead-of-time bit-level re-layout of Section 5.2 with a 3+1 split: the
  * reader needs one AND per in-place run and three AND/shift/OR for the spread one.)
+ * Words 0..3 of half h fill the slot's 16 bytes of plane 2h (the first and the last plane);
+ * words 4, 5 are words 2h, 2h+1 of the slot's 16 bytes of the middle plane.  A reader that
+ * wants one half only fetches one 16-byte and one 8-byte piece; one that wants the tile
+ * fetches three 16-byte pieces.  When K is an odd multiple of 256 the second half of the last
+ * tile of every row tile is padding (zero bits).
  */
 uint64_t fp3o_pos(int64_t M, int64_t K, int64_t m, int64_t k, int b)
 {
+    (void)K;
     int64_t row_tile = m / FP6O_TILE_ROWS;
     int r = (int)(m % FP6O_TILE_ROWS);
-    int64_t k_tile = k / FP6O_TILE_K;
-    int kk = (int)(k % FP6O_TILE_K);
+    int64_t k_tile = k / 512;
+    int half = (int)(k % 512) / 256;
+    int kk = (int)(k % 256);
     int run = kk / 32;
     int q = (kk % 32) / 8;
     int j = kk % 8;
@@ -1032,9 +1041,9 @@ uint64_t fp3o_pos(int64_t M, int64_t K, int64_t m, int64_t k, int b)
     int word = i < 3 ? 3 * g + i : 3 * g + b;
     int bit = i < 3 ? 4 * j + b + 1 : 4 * j;
     uint64_t tile = (uint64_t)(k_tile * (M / FP6O_TILE_ROWS) + row_tile);
-    uint64_t byte_addr = tile * FP3O_TILE_BYTES
-                         + (word < 4 ? (uint64_t)slot * 16u + (uint64_t)word * 4u
-                                     : 1024u + (uint64_t)slot * 8u + (uint64_t)(word - 4) * 4u);
+    uint64_t byte_addr = tile * FP3O_TILE_BYTES + (uint64_t)slot * 16u
+                         + (word < 4 ? (uint64_t)(2 * half) * 1024u + (uint64_t)word * 4u
+                                     : 1024u + (uint64_t)(2 * half + word - 4) * 4u);
     return byte_addr * 8u + (uint64_t)bit;
 }
 

@@ -109,51 +109,64 @@ def test_every_code_round_trips(o5):
 
 
 def test_pos_is_a_bijection(o5):
-    for M, K in ((16, 256), (32, 512)):
-        seen = np.zeros(3 * M * K, dtype=np.uint8)
+    """Tiles of 16 x 512 codes, 3072 bytes, k-tile major.  K a multiple of 512: every bit of the stream is hit
+    exactly once.  K an odd multiple of 256: no bit twice, and exactly the second half of every last tile
+    (1536 bytes per row tile) is never hit."""
+    for M, K in ((16, 512), (32, 1024), (32, 768), (16, 256)):
+        total = o5.packed_bytes(M, K) * 8
+        assert o5.packed_bytes(M, K) == -(-K // 512) * (M // 16) * 3072
+        seen = np.zeros(total, dtype=np.uint8)
         for m in range(M):
             for k in range(K):
                 for b in range(3):
                     p = o5.pos(M, K, m, k, b)
-                    assert 0 <= p < 3 * M * K
+                    assert 0 <= p < total
                     seen[p] += 1
-                    assert p // (1536 * 8) == (k // 256) * (M // 16) + m // 16
-        assert np.all(seen == 1)
-        assert o5.packed_bytes(M, K) == 3 * M * K // 8
+                    assert p // (3072 * 8) == (k // 512) * (M // 16) + m // 16
+        assert seen.max() == 1
+        assert int(seen.sum()) == 3 * M * K
+        if K % 512 == 0:
+            assert np.all(seen == 1)
+        else:
+            assert total - 3 * M * K == (M // 16) * 1536 * 8
 
 
 def _swar_unpack_tile(tile_bytes):
-    """One tile (1536 bytes) -> codes [16][256], read the way a lane does: its six words are four from the
-    16-byte plane and two from the 8-byte plane; words 3g..3g+2 give runs 4g..4g+2 as 4-bit fields
-    "s e1 e0 ." after masking bit 0 of every field, and run 4g+3 is stitched from the masked-out bits.
+    """One tile (3072 bytes) -> codes [16][512], read the way a lane does after three 128-bit loads: half h of
+    the tile is the slot's four words of plane 2h and words 2h, 2h+1 of its four words of the middle plane;
+    of those six words, words 3g..3g+2 give runs 4g..4g+2 of the half as 4-bit fields "s e1 e0 ." after
+    masking bit 0 of every field, and run 4g+3 is stitched from the masked-out bits.
     Written from the layout's description, without pos()."""
-    plane0 = tile_bytes[:1024].view(np.uint32).reshape(64, 4)
-    plane1 = tile_bytes[1024:].view(np.uint32).reshape(64, 2)
-    codes = np.zeros((16, 256), dtype=np.uint8)
+    planes = tile_bytes.view(np.uint32).reshape(3, 64, 4)
+    codes = np.zeros((16, 512), dtype=np.uint8)
     for slot in range(64):
         r, q = slot % 16, slot // 16
-        words = [int(w) for w in plane0[slot]] + [int(w) for w in plane1[slot]]
-        for g in range(2):
-            A = words[3 * g:3 * g + 3]
-            T = [a & 0xEEEEEEEE for a in A]
-            T.append(((A[0] & 0x11111111) << 1) | ((A[1] & 0x11111111) << 2) | ((A[2] & 0x11111111) << 3))
-            for i in range(4):
-                for j in range(8):
-                    field = (T[i] >> (4 * j)) & 0xF
-                    assert field & 1 == 0
-                    codes[r, (4 * g + i) * 32 + q * 8 + j] = field >> 1
+        for h in range(2):
+            words = [int(w) for w in planes[2 * h, slot]] + [int(planes[1, slot, 2 * h]), int(planes[1, slot, 2 * h + 1])]
+            for g in range(2):
+                A = words[3 * g:3 * g + 3]
+                T = [a & 0xEEEEEEEE for a in A]
+                T.append(((A[0] & 0x11111111) << 1) | ((A[1] & 0x11111111) << 2) | ((A[2] & 0x11111111) << 3))
+                for i in range(4):
+                    for j in range(8):
+                        field = (T[i] >> (4 * j)) & 0xF
+                        assert field & 1 == 0
+                        codes[r, 256 * h + (4 * g + i) * 32 + q * 8 + j] = field >> 1
     return codes
 
 
-def test_register_level_reconstruction(o5):
-    M, K = 32, 512
+@pytest.mark.parametrize("M,K", [(32, 1024), (32, 768)])
+def test_register_level_reconstruction(o5, M, K):
     codes = (workloads.make_codes(M, K, 9).numpy() & 7).astype(np.uint8)
     packed = o5.pack(codes)
-    tiles = packed.reshape(K // 256, M // 16, 1536)
+    KT2 = -(-K // 512)
+    tiles = packed.reshape(KT2, M // 16, 3072)
+    padded = np.zeros((M, KT2 * 512), dtype=np.uint8)
+    padded[:, :K] = codes                                   # padding columns read as code 0
     for rt in range(M // 16):
-        for kt in range(K // 256):
+        for kt in range(KT2):
             got = _swar_unpack_tile(tiles[kt, rt])
-            assert np.array_equal(got, codes[rt * 16:(rt + 1) * 16, kt * 256:(kt + 1) * 256])
+            assert np.array_equal(got, padded[rt * 16:(rt + 1) * 16, kt * 512:(kt + 1) * 512])
     assert np.array_equal(o5.unpack_codes(packed, M, K), codes)
 
 

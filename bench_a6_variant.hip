@@ -39,6 +39,7 @@ struct ShiftMaskFp6Source {
     typedef PackedFp6Source::Tile Tile;
     static constexpr bool kHasScale = true;
     static constexpr int kLdsTileBytes = 0;
+    static constexpr int kTileCols = kTileK;
     static constexpr bool kTallTile = true;
     static constexpr int kLoads = 3;
     __device__ static __forceinline__ int tile_stride(int64_t RT) { return PackedFp6Source::tile_stride(RT); }

@@ -105,11 +105,11 @@ struct StreamPlan {
 // factor that keeps row blocks x S <= 256 (at least two k-tiles per slice); take the candidate with the
 // most blocks, on a tie the one with the taller blocks (more rows share each copy of the activations; with
 // the k-tiles dealt to the slices a larger S no longer costs a sweeping front of its own).
-StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed)
+StreamPlan plan_stream(int64_t M, int64_t N, int64_t K, bool packed, int tile_cols = kTileK)
 {
     const StreamCfg *table = packed ? kStreamCfg : kStreamCfgFp16;
     const int64_t row_tiles = M / kTileRows;
-    const int64_t KT = K / kTileK;
+    const int64_t KT = (K + tile_cols - 1) / tile_cols;  // steps of the streaming kernel for this source
     const int first = N <= 16 ? 0 : (N <= 32 ? 2 : 3);
     const int last = N <= 16 ? 1 : first;
     const int64_t forced = g_forced_split.load(std::memory_order_relaxed);
@@ -366,7 +366,8 @@ fp6_status launch_stream_cfg(const StreamPlan &p, const void *weights, const voi
         if (e.residual)
             e.residual += n0 * Mout;
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, weights, static_cast<const half_t *>(scales), Xp, Yp,
-                           (int)M, (int)n, (int)K, p.split, (int)(K / kTileK / p.split), partials, counters, e);
+                           (int)M, (int)n, (int)K, p.split, (int)((K + Src::kTileCols - 1) / Src::kTileCols / p.split),
+                           partials, counters, e);
         if (hipGetLastError() != hipSuccess)
             return FP6_ERR_HIP;
     }
@@ -377,7 +378,7 @@ template <class Src>
 fp6_status launch_stream(const void *weights, const void *scales, const void *X, void *Y, int64_t M, int64_t N,
                          int64_t K, const WorkspaceRef &workspace, const Epilogue &epi, hipStream_t stream)
 {
-    const StreamPlan p = plan_stream(M, N, K, Src::kPackedConfigs);
+    const StreamPlan p = plan_stream(M, N, K, Src::kPackedConfigs, Src::kTileCols);
     SplitBuffers buf;
     const fp6_status fits = workspace.view(p.counter_bytes, p.split > 1 ? p.partial_bytes : 0, buf);
     if (fits != FP6_OK)
@@ -496,7 +497,8 @@ fp6_status packed_linear_impl(const void *packed, const void *scales_f16, const 
         return FP6_ERR_ALIGN;
     if (N > kStreamMaxN)
         return launch_tiled<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, ws, epi, static_cast<hipStream_t>(stream));
-    return launch_stream<Src>(packed, scales_f16, X_f16, Y_f16, M, N, K, ws, epi, static_cast<hipStream_t>(stream));
+    return launch_stream<typename Src::StreamSource>(packed, scales_f16, X_f16, Y_f16, M, N, K, ws, epi,
+                                                     static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -690,9 +692,19 @@ fp6_status fp4_linear(const void *packed, const void *scales_f16, const void *X_
                                                stream);
 }
 
-size_t fp3_packed_bytes(int64_t M, int64_t K) { return packed_shape_ok(M, K) ? (size_t)(M * K / 8 * 3) : 0; }
+// tiles of 16 x 512 codes: a K that is an odd multiple of 256 pads its last tile
+size_t fp3_packed_bytes(int64_t M, int64_t K)
+{
+    return packed_shape_ok(M, K) ? (size_t)((K + 511) / 512 * (M / kTileRows) * kTileBytes3) : 0;
+}
 
-size_t fp3_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) { return fp6_linear_workspace_bytes(M, N, K); }
+size_t fp3_linear_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (!packed_shape_ok(M, K) || N <= 0)
+        return 0;
+    return N <= kStreamMaxN ? plan_stream(M, N, K, true, PackedFp3Source::StreamSource::kTileCols).total_bytes()
+                            : tiled_workspace_bytes(M, N, K, PackedFp3Source::kTallTile);
+}
 
 fp6_status fp3_quantize_pack(const void *W_f16, int64_t M, int64_t K, void *packed, void *scales_f16, void *stream)
 {
@@ -781,7 +793,7 @@ fp6_status fp16_linear(const void *W_f16, const void *X_f16, void *Y_f16, int64_
     if (N > kStreamMaxN)
         return launch_tiled<PlainFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, ws, Epilogue{nullptr, nullptr, 0},
                                              static_cast<hipStream_t>(stream));
-    return launch_stream<StagedFp16Source>(W_f16, nullptr, X_f16, Y_f16, M, N, K, ws, Epilogue{nullptr, nullptr, 0},
+    return launch_stream<PlainFp16Source::StreamSource>(W_f16, nullptr, X_f16, Y_f16, M, N, K, ws, Epilogue{nullptr, nullptr, 0},
                                           static_cast<hipStream_t>(stream));
 }
 

@@ -31,6 +31,7 @@
 // re-assembled values with 27 VALU instructions per 16 weights; the conversion
 // instruction made the kernels 4-7 % faster at every N and needs no layout tricks.)
 #pragma once
+#include <type_traits>
 #include <utility>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -237,12 +238,14 @@ __device__ __forceinline__ rsrc_t packed_slice_rsrc(const void *base, int64_t ro
 }
 
 struct PackedFp6Source {
+    typedef PackedFp6Source StreamSource;  // the source the streaming kernel uses for this format
     typedef SimpleStream<PackedFp6Source> Stream;
     static constexpr bool kPackedConfigs = true;  // which table of kernel configurations the host uses
     struct Tile {
         u32x4 p0, p1, p2;
     };
     static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
+    static constexpr int kTileCols = kTileK;  // columns of one weight tile in the streaming kernel
     static constexpr bool kHasScale = true;
     static constexpr bool kTallTile = true;  // a wave tile of 2 row tiles x 8 token tiles (64 accumulator registers) is affordable
     static constexpr int kLoads = 3;
@@ -291,8 +294,10 @@ struct PackedFp6Source {
 constexpr int kGroupColumns = 128;
 
 struct PackedFp6GroupSource {
+    typedef PackedFp6GroupSource StreamSource;  // the source the streaming kernel uses for this format
     static constexpr bool kPackedConfigs = true;
     static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
+    static constexpr int kTileCols = kTileK;  // columns of one weight tile in the streaming kernel
     static constexpr bool kHasScale = false;  // no per-row factor in the epilogue
     static constexpr bool kTallTile = false;  // the scales and their multiplies leave no room for the 2 x 8 wave tile
     static constexpr int kLoads = 4;
@@ -378,6 +383,7 @@ __device__ __forceinline__ half8_t e2m2_bytes_to_fragment(uint32_t b_lo, uint32_
 }
 
 struct PackedFp5Source {
+    typedef PackedFp5Source StreamSource;  // the source the streaming kernel uses for this format
     typedef SimpleStream<PackedFp5Source> Stream;
     static constexpr bool kPackedConfigs = true;  // which table of kernel configurations the host uses
     struct Tile {
@@ -385,6 +391,7 @@ struct PackedFp5Source {
         u32x2 p2;
     };
     static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
+    static constexpr int kTileCols = kTileK;  // columns of one weight tile in the streaming kernel
     static constexpr bool kHasScale = true;
     static constexpr bool kTallTile = true;
     static constexpr int kLoads = 3;
@@ -452,12 +459,14 @@ __device__ __forceinline__ half8_t e2m1_word_to_fragment(uint32_t w)
 }
 
 struct PackedFp4Source {
+    typedef PackedFp4Source StreamSource;  // the source the streaming kernel uses for this format
     typedef SimpleStream<PackedFp4Source> Stream;
     static constexpr bool kPackedConfigs = true;  // which table of kernel configurations the host uses
     struct Tile {
         u32x4 p0, p1;
     };
     static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
+    static constexpr int kTileCols = kTileK;  // columns of one weight tile in the streaming kernel
     static constexpr bool kHasScale = true;
     static constexpr bool kTallTile = true;
     static constexpr int kLoads = 2;
@@ -493,22 +502,45 @@ struct PackedFp4Source {
 // e2m0 (bias 1, no mantissa bits: 0 1 2 4) has no conversion instruction of its own, but code s e1 e0 has
 // the value of the e2m1 code s e1 e0 0, so a word of eight 4-bit fields "s e1 e0 0" goes through the FP4
 // conversion.  The layout (the paper's ahead-of-time bit-level pre-packing, Section 5.2, with a 3+1 split)
-// stores exactly such words: tile = 16 rows x 256 columns = 1536 bytes = a plane of 16 bytes per lane and
-// a plane of 8 bytes per lane; the lane's six words serve two groups of four runs, words 3g..3g+2 are runs
-// 4g..4g+2 in place with bit 0 of every field free, and those free bits carry run 4g+3: its bit b+1 of
-// field j is bit 4j of word 3g+b.  Unpack: one AND per in-place run, three AND/shift/OR for the fourth.
-struct PackedFp3Source {
-    typedef SimpleStream<PackedFp3Source> Stream;
+// stores exactly such words.  Tile = 16 rows x 512 columns = 3072 bytes = three planes of 16 bytes per lane,
+// so that the streaming kernel fetches a tile with three whole 128-bit loads (a 64-bit load costs the memory
+// pipeline what a 128-bit one costs).  Each half of the tile (256 columns) gives the lane six words: the four
+// of plane 0 (first half) or plane 2 (second half), then words 2h, 2h+1 of the middle plane.  Of those six,
+// words 3g..3g+2 are runs 4g..4g+2 of the half in place with bit 0 of every field free, and those free bits
+// carry run 4g+3: its bit b+1 of field j is bit 4j of word 3g+b.  Unpack: one AND per in-place run, three
+// AND/shift/OR for the fourth.
+// A fragments of runs 2G (even) and 2G+1 (odd) of one half, G = 0..3, from the half's six words
+template <int G>
+__device__ __forceinline__ void e2m0_half_fragments(const u32x4 &p0, uint32_t w4, uint32_t w5, half8_t &even_run,
+                                                    half8_t &odd_run)
+{
+    constexpr uint32_t kFields = 0xeeeeeeeeu, kFree = 0x11111111u;
+    const uint32_t a0 = G < 2 ? p0[0] : p0[3];
+    const uint32_t a1 = G < 2 ? p0[1] : w4;
+    const uint32_t a2 = G < 2 ? p0[2] : w5;
+    if ((G & 1) == 0) {
+        even_run = e2m1_word_to_fragment(a0 & kFields);
+        odd_run = e2m1_word_to_fragment(a1 & kFields);
+    } else {
+        even_run = e2m1_word_to_fragment(a2 & kFields);
+        odd_run = e2m1_word_to_fragment(((a0 & kFree) << 1) | ((a1 & kFree) << 2) | ((a2 & kFree) << 3));
+    }
+}
+constexpr int kTileBytes3 = 3072;  // 16 rows x 512 columns of 3-bit codes
+
+// The whole tile, for the streaming kernel: 512 columns per step.
+struct PackedFp3WideSource {
+    typedef SimpleStream<PackedFp3WideSource> Stream;
+    typedef PackedFp3WideSource StreamSource;
     static constexpr bool kPackedConfigs = true;  // which table of kernel configurations the host uses
     struct Tile {
-        u32x4 p0;
-        u32x2 p1;
+        u32x4 p0, p1, p2;
     };
     static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
+    static constexpr int kTileCols = 512;
     static constexpr bool kHasScale = true;
     static constexpr bool kTallTile = true;
-    static constexpr int kLoads = 2;
-    static constexpr int kTileBytes3 = 1536;
+    static constexpr int kLoads = 3;
     __device__ static __forceinline__ int tile_stride(int64_t RT) { return (int)(RT * kTileBytes3); }
     __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
     __device__ static __forceinline__ rsrc_t slice_rsrc(const void *base, int64_t row_tile, int kt_first, int kt_step,
@@ -519,41 +551,91 @@ struct PackedFp3Source {
     __device__ static __forceinline__ int lane_offset(int lane, int /*kt0*/, int /*K*/) { return lane * 16; }
     __device__ static __forceinline__ void issue(Tile &t, rsrc_t r, int off)
     {
-        // the second plane holds 8 bytes per lane: its offset is the tile's base + 1024 + 8 * lane
-        const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
         t.p0 = issue_load_b128<0, true>(r, off);
-        t.p1 = issue_load_b64<1024>(r, off - 8 * lane);
+        t.p1 = issue_load_b128<1024, true>(r, off);
+        t.p2 = issue_load_b128<2048, true>(r, off);
     }
     __device__ static __forceinline__ void pin_tile(Tile &t)
     {
         pin(t.p0);
         pin(t.p1);
+        pin(t.p2);
     }
-    // A fragments of runs 2G (even) and 2G+1 (odd): group g = G/2 uses words A0..A2 = words 3g..3g+2
+    // A fragments of runs 2G and 2G+1 of the tile, G = 0..7
     template <int G>
     __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
     {
-        constexpr uint32_t kFields = 0xeeeeeeeeu, kFree = 0x11111111u;
-        const uint32_t a0 = G < 2 ? t.p0[0] : t.p0[3];
-        const uint32_t a1 = G < 2 ? t.p0[1] : t.p1[0];
-        const uint32_t a2 = G < 2 ? t.p0[2] : t.p1[1];
-        if ((G & 1) == 0) {
-            even_run = e2m1_word_to_fragment(a0 & kFields);
-            odd_run = e2m1_word_to_fragment(a1 & kFields);
-        } else {
-            even_run = e2m1_word_to_fragment(a2 & kFields);
-            odd_run = e2m1_word_to_fragment(((a0 & kFree) << 1) | ((a1 & kFree) << 2) | ((a2 & kFree) << 3));
-        }
+        if (G < 4)
+            e2m0_half_fragments<G % 4>(t.p0, t.p1[0], t.p1[1], even_run, odd_run);
+        else
+            e2m0_half_fragments<G % 4>(t.p2, t.p1[2], t.p1[3], even_run, odd_run);
     }
 };
 
+// One half of a tile (256 columns) at a time, for the kernels that step through k in units of 256 columns
+// (the tiled kernel, unpack): k-tile kt is half kt % 2 of tile kt / 2, fetched with one 128-bit and one
+// 64-bit load.
+struct PackedFp3Source {
+    typedef PackedFp3WideSource StreamSource;
+    static constexpr bool kPackedConfigs = true;
+    struct Tile {
+        u32x4 p0;
+        u32x2 p1;
+    };
+    static constexpr int kLdsTileBytes = 0;
+    static constexpr int kTileCols = kTileK;
+    static constexpr bool kHasScale = true;
+    static constexpr bool kTallTile = true;
+    static constexpr int kLoads = 2;
+    __device__ static __forceinline__ int k_offset(int f, int q) { return f * 32 + q * 8; }
+    struct Stream {
+        rsrc_t rsrc;
+        int off, first, stride;  // lane offset, first k-tile, bytes from one tile of a row tile to the next
+        // k-tiles kt_first .. kt_first + n_tiles - 1 of one row tile (contiguous: kt_step is 1 for every user)
+        __device__ __forceinline__ void init(const void *weights, const half_t * /*scales*/, int64_t row_tile, int kt_first,
+                                             int /*kt_step*/, int n_tiles, int64_t RT, int64_t /*K*/, int lane)
+        {
+            const int t0 = kt_first >> 1, t1 = (kt_first + n_tiles - 1) >> 1;  // first and last tile touched
+            rsrc = make_rsrc(static_cast<const uint8_t *>(weights) + ((int64_t)t0 * RT + row_tile) * kTileBytes3,
+                             (uint32_t)(((int64_t)(t1 - t0) * RT + 1) * kTileBytes3));
+            off = lane * 16;
+            first = kt_first;
+            stride = __builtin_amdgcn_readfirstlane((int)(RT * kTileBytes3));
+        }
+        __device__ __forceinline__ void issue(Tile &tile, int t) const
+        {
+            const int kt = first + t, half = kt & 1;
+            const int o = off + ((kt >> 1) - (first >> 1)) * stride;
+            tile.p0 = issue_load_b128<0, true>(rsrc, o + half * 2048);
+            tile.p1 = issue_load_b64<1024>(rsrc, o + half * 8);
+        }
+        template <int D>
+        __device__ __forceinline__ void bind_slots(Tile (&)[D], u32x4 *, int) const
+        {
+        }
+    };
+    __device__ static __forceinline__ void pin_tile(Tile &t)
+    {
+        pin(t.p0);
+        pin(t.p1);
+    }
+    template <int G>
+    __device__ static __forceinline__ void fragments(const Tile &t, half8_t &even_run, half8_t &odd_run)
+    {
+        e2m0_half_fragments<G>(t.p0, t.p1[0], t.p1[1], even_run, odd_run);
+    }
+};
+
+struct StagedFp16Source;
 struct PlainFp16Source {
+    typedef StagedFp16Source StreamSource;  // the source the streaming kernel uses for this format
     typedef SimpleStream<PlainFp16Source> Stream;
     static constexpr bool kPackedConfigs = false;  // which table of kernel configurations the host uses
     struct Tile {
         u32x4 v[8];
     };
     static constexpr int kLdsTileBytes = 0;  // tiles in flight live in registers
+    static constexpr int kTileCols = kTileK;  // columns of one weight tile in the streaming kernel
     static constexpr bool kHasScale = false;
     static constexpr bool kTallTile = false;
     static constexpr int kLoads = 8;
@@ -618,11 +700,13 @@ struct PlainFp16Source {
 __device__ __forceinline__ int w_swizzle(int row) { return ((row >> 1) & 3) << 1; }
 
 struct StagedFp16Source {
+    typedef StagedFp16Source StreamSource;  // the source the streaming kernel uses for this format
     static constexpr bool kPackedConfigs = false;
     static constexpr bool kHasScale = false;
     static constexpr bool kTallTile = false;
     static constexpr int kLoads = 8;
     static constexpr int kLdsTileBytes = 8192;
+    static constexpr int kTileCols = kTileK;
     struct Tile {
         const u32x4 *even, *odd;  // this lane's fragment of run 0 (even runs) and of run 1 (odd runs) in the slot
         uint32_t lds;             // LDS byte address of the slot (wave-uniform)

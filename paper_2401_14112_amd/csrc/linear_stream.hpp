@@ -37,14 +37,15 @@ template <int NT_, int WAVES_, int DEPTH_, int G_, int XSPREAD_, bool DEAL_>
 struct StreamShape {
     static constexpr int NT = NT_, WAVES = WAVES_, DEPTH = DEPTH_, G = G_, XSPREAD = XSPREAD_;
     static constexpr bool DEAL = DEAL_;
-    static constexpr int kXBytes = 2 * G_ * NT_ * 8 * 1024;  // two stages of activations
+    // bytes of two stages of activations for weight tiles of tile_cols columns (1 KB per token tile and run of 32)
+    static constexpr int x_bytes(int tile_cols) { return 2 * G_ * NT_ * (tile_cols / 32) * 1024; }
     static constexpr int kThreads = WAVES_ * 64;
     // dynamic LDS of a launch: the activation stages, then (sources that stage their weights in LDS) DEPTH
     // tiles per wave
     template <class Src>
     static constexpr int lds_bytes()
     {
-        return kXBytes + WAVES_ * DEPTH_ * Src::kLdsTileBytes;
+        return x_bytes(Src::kTileCols) + WAVES_ * DEPTH_ * Src::kLdsTileBytes;
     }
 };
 
@@ -57,7 +58,9 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     constexpr int NT = Shape::NT, WAVES = Shape::WAVES, DEPTH = Shape::DEPTH, G = Shape::G;
     constexpr int XSPREAD = Shape::XSPREAD;
     constexpr bool KDEAL = Shape::DEAL;
-    constexpr int COPIES = G * NT * 8;  // copy instructions (1 KB each: one token tile x one run) per stage
+    constexpr int TILE_COLS = Src::kTileCols;  // columns of one weight tile: one step of the loop (a "k-tile" below)
+    constexpr int RUNS = TILE_COLS / 32;        // MFMA steps per tile
+    constexpr int COPIES = G * NT * RUNS;  // copy instructions (1 KB each: one token tile x one run) per stage
     static_assert(COPIES % WAVES == 0, "the copies of a stage must split evenly over the waves");
     constexpr int XPER = COPIES / WAVES;
     constexpr int STAGE_PIECES = COPIES * 64;  // 16-byte pieces of one stage
@@ -72,7 +75,7 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int KT = K / kTileK;
+    const int KT = (K + TILE_COLS - 1) / TILE_COLS;  // a K that is not a multiple of the tile: the last tile is padded
     const int n_row_tiles = M / kTileRows;
     // consecutive blocks take consecutive row blocks of the same k slice (measured a few per cent better at
     // N = 32, 64 than alternating the slices, no difference below)
@@ -99,12 +102,13 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     w_stream.init(weights, scales, active ? row_tile : n_row_tiles - 1, kt_first, kt_step, n_valid, n_row_tiles, K, lane);
     const rsrc_t x_rsrc = make_rsrc(X, (uint32_t)N * (uint32_t)K * 2u);
 
-    // ---- activation staging.  Copy j = wave + WAVES*i of a stage serves k-tile g = j / (8*NT) of the
-    // stage, token tile nt = (j/8) % NT and run f = j % 8; lane p of the copy fetches
-    // X[16*nt + n][k-tile*256 + k_offset(f, q) ..+8] for the (n, q) that piece p of the 1 KB holds, and
-    // its 16 bytes land at piece 64*j + p of the stage buffer.  Token columns >= N and k-tiles past the
-    // end of the slice get an offset outside the buffer: nothing is fetched and zeros land in LDS, which is
-    // what neutralises the k-tiles that the uniform trip count adds to the shorter slices.
+    // ---- activation staging.  Copy j = wave + WAVES*i of a stage serves k-tile g = j / (RUNS*NT) of the
+    // stage, token tile nt = (j/RUNS) % NT and run f = j % RUNS; lane p of the copy fetches
+    // X[16*nt + n][k-tile*TILE_COLS + k_offset(f, q) ..+8] for the (n, q) that piece p of the 1 KB holds, and
+    // its 16 bytes land at piece 64*j + p of the stage buffer.  Token columns >= N, k-tiles past the end of
+    // the slice and columns >= K (the padding of a last tile) get an offset outside the buffer: nothing is
+    // fetched and zeros land in LDS, which is what neutralises the k-tiles that the uniform trip count adds
+    // to the shorter slices.
     int xn, xq;
     x_source_of_piece(lane, xn, xq);
     const uint32_t xs_lds = (uint32_t)reinterpret_cast<uintptr_t>(xs_dyn);  // LDS byte address
@@ -115,12 +119,11 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
             if (i < i0 || i >= i1)
                 continue;
             const int j = wave + WAVES * i;
-            const int f = j & 7, nt = (j >> 3) % NT, g = j / (8 * NT);
+            const int f = j % RUNS, nt = (j / RUNS) % NT, g = j / (RUNS * NT);
             const int col = nt * 16 + xn;
             const int t = stage * G + g;
-            const int off = (t < n_valid && col < N)
-                                ? (col * K + (kt_first + t * kt_step) * kTileK + Src::k_offset(f, xq)) * 2
-                                : kOutOfRange;
+            const int k = (kt_first + t * kt_step) * TILE_COLS + Src::k_offset(f, xq);
+            const int off = (t < n_valid && col < N && (K % TILE_COLS == 0 || k < K)) ? (col * K + k) * 2 : kOutOfRange;
             const uint32_t lds_base = (uint32_t)__builtin_amdgcn_readfirstlane(
                 (int)(xs_lds + (uint32_t)(buf * STAGE_PIECES + j * 64) * 16u));
             issue_load_to_lds_b128<0>(x_rsrc, off, lds_base);
@@ -137,17 +140,17 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
     auto mma_pair = [&](const half8_t &a_even, const half8_t &a_odd, const u32x4 *xb, int p) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            half8_t b = bit_cast<half8_t>(xb[(nt * 8 + 2 * p) * 64 + b_piece]);
+            half8_t b = bit_cast<half8_t>(xb[(nt * RUNS + 2 * p) * 64 + b_piece]);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_even, b, acc[nt], 0, 0, 0);
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            half8_t b = bit_cast<half8_t>(xb[(nt * 8 + 2 * p + 1) * 64 + b_piece]);
+            half8_t b = bit_cast<half8_t>(xb[(nt * RUNS + 2 * p + 1) * 64 + b_piece]);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a_odd, b, acc[nt], 0, 0, 0);
         }
     };
     auto compute = [&](const typename Src::Tile &t, const u32x4 *xb) {
-        static_for<4>([&](auto pc) {
+        static_for<RUNS / 2>([&](auto pc) {
             constexpr int p = decltype(pc)::value;
             half8_t a_even, a_odd;
             Src::template fragments<p>(t, a_even, a_odd);
@@ -195,7 +198,7 @@ __global__ __launch_bounds__(Shape::kThreads) void linear_stream_kernel(
             if (g < XSPREAD)
                 x_issue(stage + 1, g * XPART, (g + 1) * XPART);
             if (t < T)
-                compute(w[slot], xs_dyn + (stage & 1) * STAGE_PIECES + g * (NT * 8 * 64));
+                compute(w[slot], xs_dyn + (stage & 1) * STAGE_PIECES + g * (NT * RUNS * 64));
             w_stream.issue(w[slot], t + DEPTH);
         });
     }

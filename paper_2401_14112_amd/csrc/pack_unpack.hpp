@@ -64,6 +64,7 @@ struct E3M2Format {
     static constexpr float kMax = 28.0f;
     static constexpr int kSignShift = 5;
     static constexpr int kTileBytes = 3072;
+    static constexpr bool kHalfTiles = false;
     __device__ static __forceinline__ uint32_t magnitude_code(float ratio) { return e3m2_magnitude_code(ratio); }
     __device__ static __forceinline__ void store_tile(const uint32_t (&code)[8][8], uint8_t *tile, int lane)
     {
@@ -98,6 +99,7 @@ struct E2M2Format {
     static constexpr float kMax = 7.0f;
     static constexpr int kSignShift = 4;
     static constexpr int kTileBytes = 2560;
+    static constexpr bool kHalfTiles = false;
     __device__ static __forceinline__ uint32_t magnitude_code(float ratio)
     {
         uint32_t g;
@@ -148,6 +150,7 @@ struct E2M1Format {
     static constexpr float kMax = 6.0f;
     static constexpr int kSignShift = 3;
     static constexpr int kTileBytes = 2048;
+    static constexpr bool kHalfTiles = false;
     __device__ static __forceinline__ uint32_t magnitude_code(float ratio)
     {
         uint32_t g;
@@ -181,7 +184,8 @@ struct E2M1Format {
 struct E2M0Format {
     static constexpr float kMax = 4.0f;
     static constexpr int kSignShift = 2;
-    static constexpr int kTileBytes = 1536;
+    static constexpr int kTileBytes = 3072;       // 16 rows x 512 columns: k-tile kt (256 columns) is half kt % 2 of tile kt / 2
+    static constexpr bool kHalfTiles = true;
     __device__ static __forceinline__ uint32_t magnitude_code(float ratio)
     {
         uint32_t g;
@@ -194,7 +198,11 @@ struct E2M0Format {
         }
         return g < 3u ? g : 3u;
     }
-    __device__ static __forceinline__ void store_tile(const uint32_t (&code)[8][8], uint8_t *tile, int lane)
+    // the lane's bytes of one half of a tile: 16 in plane 0 (first half) or 2 (second half), 8 in the middle
+    // plane; pad_other: the matrix ends with this half (K an odd multiple of 256) and the lane also writes the
+    // zero padding of the other half
+    __device__ static __forceinline__ void store_half(const uint32_t (&code)[8][8], uint8_t *tile, int half, bool pad_other,
+                                                      int lane)
     {
         uint32_t d[6];
 #pragma unroll
@@ -214,8 +222,32 @@ struct E2M0Format {
             for (int i = 0; i < 3; ++i)
                 d[3 * g + i] = w[i];
         }
-        *(reinterpret_cast<u32x4 *>(tile) + lane) = (u32x4){d[0], d[1], d[2], d[3]};
-        *(reinterpret_cast<u32x2 *>(tile + 1024) + lane) = (u32x2){d[4], d[5]};
+        *(reinterpret_cast<u32x4 *>(tile + half * 2048) + lane) = (u32x4){d[0], d[1], d[2], d[3]};
+        *(reinterpret_cast<u32x2 *>(tile + 1024) + 2 * lane + half) = (u32x2){d[4], d[5]};
+        if (pad_other) {
+            *(reinterpret_cast<u32x4 *>(tile + (half ^ 1) * 2048) + lane) = (u32x4){0, 0, 0, 0};
+            *(reinterpret_cast<u32x2 *>(tile + 1024) + 2 * lane + (half ^ 1)) = (u32x2){0, 0};
+        }
+    }
+};
+
+// The lane's bytes of k-tile kt (256 columns) of row tile `row_tile` into the packed stream (tiles stored
+// k-tile major; RT row tiles, KT k-tiles of 256 columns).
+template <class Fmt, class = void>
+struct KTileStore {
+    __device__ static __forceinline__ void store(const uint32_t (&code)[8][8], uint8_t *packed, int64_t kt, int64_t row_tile,
+                                                 int64_t RT, int /*KT*/, int lane)
+    {
+        Fmt::store_tile(code, packed + (kt * RT + row_tile) * Fmt::kTileBytes, lane);
+    }
+};
+template <class Fmt>
+struct KTileStore<Fmt, std::enable_if_t<Fmt::kHalfTiles>> {
+    __device__ static __forceinline__ void store(const uint32_t (&code)[8][8], uint8_t *packed, int64_t kt, int64_t row_tile,
+                                                 int64_t RT, int KT, int lane)
+    {
+        Fmt::store_half(code, packed + ((kt >> 1) * RT + row_tile) * Fmt::kTileBytes, (int)(kt & 1),
+                        (kt & 1) == 0 && kt == KT - 1, lane);
     }
 };
 
@@ -279,7 +311,7 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const half_t *__res
         return;
     // the waves of a block take neighbouring k-tiles of one row tile (2 KB of every row of W between them);
     // in the packed stream tiles are stored k-tile major
-    const int64_t RT = M / kTileRows, row_tile = tile / KT, kt = tile % KT, packed_tile = kt * RT + row_tile;
+    const int64_t RT = M / kTileRows, row_tile = tile / KT, kt = tile % KT;
     const int r = lane & 15, q = lane >> 4;  // lane (r, q) builds its bytes of the tile
     const half_t *row = W + (row_tile * kTileRows + r) * K + kt * kTileK + q * 8;
     u32x4 v[8];
@@ -295,7 +327,7 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const half_t *__res
             code[f][2 * j] = quantize_code<Fmt>(v[f][j] & 0xffffu, scale);
             code[f][2 * j + 1] = quantize_code<Fmt>(v[f][j] >> 16, scale);
         }
-    Fmt::store_tile(code, packed + packed_tile * Fmt::kTileBytes, lane);
+    KTileStore<Fmt>::store(code, packed, kt, row_tile, RT, KT, lane);
 }
 
 // Group-wise scales (one per row and per 128 columns): a group lies inside one tile and inside one of a

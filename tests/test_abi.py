@@ -61,7 +61,7 @@ def test_size_queries(lib):
     assert lib.fp4_packed_bytes(16, 256) == 2048 and lib.fp4_packed_bytes(16, 128) == 0
     assert lib.fp6_packed_bytes(15, 256) == 0 and lib.fp6_packed_bytes(16, 128) == 0
     assert lib.fp6_packed_bytes(0, 256) == 0 and lib.fp6_packed_bytes(-16, 256) == 0
-    assert lib.fp3_packed_bytes(16, 256) == 1536 and lib.fp3_packed_bytes(8192, 22016) == 67633152
+    assert lib.fp3_packed_bytes(16, 256) == 3072 and lib.fp3_packed_bytes(16, 512) == 3072 and lib.fp3_packed_bytes(8192, 22016) == 67633152
     # a token count whose activations exceed 2 GiB is cut into several launches: the query still answers
     assert lib.fp6_linear_workspace_bytes(32, 4194476, 256) % 16 == 0
     assert lib.fp6_linear_workspace_bytes(8192, 200000, 22016) <= 256 * 1024 * 1024

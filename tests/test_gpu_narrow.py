@@ -17,8 +17,9 @@ pytestmark = pytest.mark.gpu
 class Width:
     """What differs between the widths: the calls, the largest magnitude, hand-picked ties, tile bytes."""
 
-    def __init__(self, prefix, bits, top, ties, tile_bytes, unit, small):
+    def __init__(self, prefix, bits, top, ties, tile_bytes, unit, small, tile_cols=256):
         self.prefix, self.bits, self.top, self.ties, self.tile_bytes = prefix, bits, top, ties, tile_bytes
+        self.tile_cols = tile_cols
         self.unit = unit      # a value v with v / top * top exact in fp16: one non-zero per row gives scale v / top
         self.small = small    # three small multiples of 2^-24 (row of a subnormal scale) and one whose scale rounds down
         self.codes = 1 << bits
@@ -29,7 +30,7 @@ WIDTHS = {
                  (7, 3, 2, 10)),
     "fp4": Width("fp4", 4, 6.0, [5, 3.5, 2.5, 1.75, 1.25, 0.75, 0.25, 5.5, 4.5, 2.4, 2.6, 0.26, 0.24], 2048, 0.75,
                  (6, 3, 2, 8)),
-    "fp3": Width("fp3", 3, 4.0, [3, 1.5, 0.5, 3.1, 2.9, 3.5, 1.6, 1.4, 0.51, 0.49], 1536, 0.75, (4, 2, 1, 5)),
+    "fp3": Width("fp3", 3, 4.0, [3, 1.5, 0.5, 3.1, 2.9, 3.5, 1.6, 1.4, 0.51, 0.49], 3072, 0.75, (4, 2, 1, 5), tile_cols=512),
 }
 
 
@@ -101,7 +102,7 @@ def test_quantize_pack_bit_exact(pkg, o5, wd, M, K, seed):
     packed, scales = _call(pkg, wd, "quantize_pack")(W.cuda())
     torch.cuda.synchronize()
     ref_packed, ref_scales = o5.quantize_pack(W.numpy())
-    assert packed.numel() == wd.bits * M * K // 8
+    assert packed.numel() == o5.packed_bytes(M, K) == wd.bits * 16 * wd.tile_cols // 8 * (M // 16) * -(-K // wd.tile_cols)
     assert np.array_equal(_np(scales).view(np.uint16), ref_scales.view(np.uint16))
     assert np.array_equal(_np(packed), ref_packed)
 
@@ -205,7 +206,7 @@ def test_full_size_layer_sampled(pkg, o5, wd):
     tiles = np.array(sorted(set([0, M // 16 - 1]) | set(int(t) for t in rng.choice(M // 16, size=14, replace=False))))
     rows = (tiles[:, None] * 16 + np.arange(16)[None, :]).ravel()
     ref_packed, ref_scales = o5.quantize_pack(_np(W[torch.from_numpy(rows).cuda()]))
-    got_packed = row_tiles_of(packed, M, K, tiles, wd.tile_bytes)
+    got_packed = row_tiles_of(packed, M, K, tiles, wd.tile_bytes, wd.tile_cols)
     assert np.array_equal(_np(scales)[rows].view(np.uint16), ref_scales.view(np.uint16))
     assert np.array_equal(got_packed, ref_packed)
     del W

@@ -469,7 +469,7 @@ int fp6go_linear(const uint8_t *packed, const uint16_t *scales, const uint16_t *
  * Everything below mirrors the 6-bit functions above, written out again.
  * ====================================================================== */
 
-#define FP5O_TILE_BYTES 5120 /* 16 * 512 * 5 / 8 */
+#define FP5O_TILE_BYTES 2560 /* 16 * 256 * 5 / 8 */
 
 double fp5o_decode(int code)
 {
@@ -545,22 +545,17 @@ int fp5o_quantize(const uint16_t *W, int64_t M, int64_t K, uint8_t *codes, uint1
     return bad;
 }
 
-/* tiles of 16 rows x 512 columns; a matrix whose K is an odd multiple of 256 pads its last tile */
-int64_t fp5o_packed_bytes(int64_t M, int64_t K) { return (K + 511) / 512 * (M / FP6O_TILE_ROWS) * FP5O_TILE_BYTES; }
+int64_t fp5o_packed_bytes(int64_t M, int64_t K) { return M * K * 5 / 8; }
 
 /*
  * Bit address, in the packed 5-bit stream, of bit b of the code of weight (m, k);
  * b = 0..4 = m0, m1, e0, e1, s.
  *
- * Tiles of 16 rows x 512 columns, k-tile major as in the 6-bit layout, 5120 bytes each: five
- * planes of 1024 bytes (64 slots of 16 bytes; slot = 16*q + r as in the 6-bit layout), so that
- * a lane fetches its share of a tile with five whole 128-bit loads.  The two halves of a tile
- * (half h = columns 256h .. 256h+255) are laid out alike.  A half gives the slot ten 32-bit
- * words: words 0..3 fill the slot's 16 bytes of plane 3h, words 4..7 those of plane 3h+1, and
- * words 8, 9 are words 2h, 2h+1 of the slot's 16 bytes of the middle plane (plane 2).  A reader
- * that wants one half only fetches two 16-byte pieces and one 8-byte piece.  When K is an odd
- * multiple of 256 the second half of the last tile of every row tile is padding (zero bits).
- * Words 0..4 (D0..D4) of a half serve its column runs 0..3, words 5..9 its runs 4..7.  The 32 codes
+ * Tiles of 16 rows x 256 columns, k-tile major as in the 6-bit layout, 2560 bytes each.  A tile is two
+ * planes of 1024 bytes (64 slots of 16 bytes) followed by one plane of 512 bytes
+ * (64 slots of 8 bytes); slot = 16*q + r as in the 6-bit layout.  The slot owns
+ * ten 32-bit words: words 0..3 in plane 0, 4..7 in plane 1, 8..9 in plane 2.
+ * Words 0..4 (D0..D4) serve column runs 0..3, words 5..9 runs 4..7.  The 32 codes
  * of four runs, index i = 8*(run%4) + j, are placed so that shifts and masks on
  * whole words rebuild four codes at a time (Section 5.3): code i < 20 sits in
  * place in byte i%4 of D[i/4] as  s . . . e1 e0 m1 m0  (sign at bit 7, the rest at
@@ -580,10 +575,8 @@ uint64_t fp5o_pos(int64_t M, int64_t K, int64_t m, int64_t k, int b)
         {5, 6, 4, 5, 6}, {6, 4, 5, 6, 4}, {4, 5, 6, 4, 5}};
     int64_t row_tile = m / FP6O_TILE_ROWS;
     int r = (int)(m % FP6O_TILE_ROWS);
-    (void)K;
-    int64_t k_tile = k / 512;
-    int tile_half = (int)(k % 512) / 256;
-    int kk = (int)(k % 256);
+    int64_t k_tile = k / FP6O_TILE_K;
+    int kk = (int)(k % FP6O_TILE_K);
     int run = kk / 32;
     int q = (kk % 32) / 8;
     int j = kk % 8;
@@ -600,11 +593,10 @@ uint64_t fp5o_pos(int64_t M, int64_t K, int64_t m, int64_t k, int b)
         word = spread_word[g][b];
         bit = spread_bit[g][b];
     }
-    int d = 5 * half + word;      /* word of the slot within its half of the tile, 0..9 */
+    int d = 5 * half + word;      /* word of the slot, 0..9 */
     uint64_t tile = (uint64_t)(k_tile * (M / FP6O_TILE_ROWS) + row_tile);
-    uint64_t in_tile = (uint64_t)slot * 16u
-                       + (d < 8 ? (uint64_t)(3 * tile_half + d / 4) * 1024u + (uint64_t)(d % 4) * 4u
-                                : 2048u + (uint64_t)(2 * tile_half + d - 8) * 4u);
+    uint64_t in_tile = d < 8 ? (uint64_t)(d / 4) * 1024u + (uint64_t)slot * 16u + (uint64_t)(d % 4) * 4u
+                             : 2048u + (uint64_t)slot * 8u + (uint64_t)(d - 8) * 4u;
     return (tile * FP5O_TILE_BYTES + in_tile + (uint64_t)lane_byte) * 8u + (uint64_t)bit;
 }
 

@@ -102,69 +102,54 @@ def test_every_code_round_trips(o5):
 
 
 def test_pos_is_a_bijection(o5):
-    """Tiles of 16 x 512 codes, 5120 bytes, k-tile major.  K a multiple of 512: every bit of the stream is hit
-    exactly once.  K an odd multiple of 256: no bit twice, and exactly the second half of every last tile
-    (2560 bytes per row tile) is never hit."""
-    for M, K in ((16, 512), (32, 1024), (32, 768), (16, 256)):
-        total = o5.packed_bytes(M, K) * 8
-        assert o5.packed_bytes(M, K) == -(-K // 512) * (M // 16) * 5120
-        seen = np.zeros(total, dtype=np.uint8)
+    for M, K in ((16, 256), (32, 512)):
+        seen = np.zeros(5 * M * K, dtype=np.uint8)
         for m in range(M):
             for k in range(K):
                 for b in range(5):
                     p = o5.pos(M, K, m, k, b)
-                    assert 0 <= p < total
+                    assert 0 <= p < 5 * M * K
                     seen[p] += 1
-                    assert p // (5120 * 8) == (k // 512) * (M // 16) + m // 16
-        assert seen.max() == 1
-        assert int(seen.sum()) == 5 * M * K
-        if K % 512 == 0:
-            assert np.all(seen == 1)
-        else:
-            assert total - 5 * M * K == (M // 16) * 2560 * 8
+                    assert p // (2560 * 8) == (k // 256) * (M // 16) + m // 16
+        assert np.all(seen == 1)
+        assert o5.packed_bytes(M, K) == 5 * M * K // 8
 
 
 def _swar_unpack_tile(tile_bytes):
-    """One tile (5120 bytes) -> codes [16][512], rebuilt with whole-word shifts and masks as a lane would after
-    five 128-bit loads: half h of the tile is the slot's four words of plane 3h, its four words of plane 3h+1
-    and words 2h, 2h+1 of its four words of the middle plane; of those ten words, five masked words give
-    twenty codes in place and three three-term stitches give the other twelve, per group of four runs.
-    Written from the layout's description, without pos()."""
-    planes = tile_bytes.view(np.uint32).reshape(5, 64, 4)
-    codes = np.zeros((16, 512), dtype=np.uint8)
+    """One tile (2560 bytes) -> codes [16][256], rebuilt with whole-word shifts and masks as a lane would:
+    five masked words give twenty codes in place, three three-term stitches give the other twelve.  Written
+    from the layout's description, without pos()."""
+    p01 = tile_bytes[:2048].view(np.uint32).reshape(2, 64, 4)
+    p2 = tile_bytes[2048:].view(np.uint32).reshape(64, 2)
+    codes = np.zeros((16, 256), dtype=np.uint8)
     for slot in range(64):
         r, q = slot % 16, slot // 16
-        for h in range(2):
-            words = ([int(w) for w in planes[3 * h, slot]] + [int(w) for w in planes[3 * h + 1, slot]]
-                     + [int(planes[2, slot, 2 * h]), int(planes[2, slot, 2 * h + 1])])
-            for half in range(2):
-                D = words[5 * half:5 * half + 5]
-                B = [d & 0x8F8F8F8F for d in D]
-                B.append(((D[0] << 1) & 0x80808080) | ((D[0] >> 2) & 0x0C0C0C0C) | ((D[1] >> 5) & 0x03030303))
-                B.append(((D[1] << 3) & 0x80808080) | ((D[2] >> 3) & 0x0E0E0E0E) | ((D[3] >> 6) & 0x01010101))
-                B.append(((D[3] << 2) & 0x80808080) | ((D[3] >> 1) & 0x08080808) | ((D[4] >> 4) & 0x07070707))
-                for w in range(8):
-                    for byte in range(4):
-                        v = (B[w] >> (8 * byte)) & 0xFF
-                        assert v & 0x70 == 0
-                        i = 4 * w + byte
-                        run, j = 4 * half + i // 8, i % 8
-                        codes[r, 256 * h + run * 32 + q * 8 + j] = ((v >> 7) << 4) | (v & 0x0F)
+        words = [int(p01[0][slot, i]) for i in range(4)] + [int(p01[1][slot, i]) for i in range(4)] + [int(p2[slot, 0]), int(p2[slot, 1])]
+        for half in range(2):
+            D = words[5 * half:5 * half + 5]
+            B = [d & 0x8F8F8F8F for d in D]
+            B.append(((D[0] << 1) & 0x80808080) | ((D[0] >> 2) & 0x0C0C0C0C) | ((D[1] >> 5) & 0x03030303))
+            B.append(((D[1] << 3) & 0x80808080) | ((D[2] >> 3) & 0x0E0E0E0E) | ((D[3] >> 6) & 0x01010101))
+            B.append(((D[3] << 2) & 0x80808080) | ((D[3] >> 1) & 0x08080808) | ((D[4] >> 4) & 0x07070707))
+            for w in range(8):
+                for byte in range(4):
+                    v = (B[w] >> (8 * byte)) & 0xFF
+                    assert v & 0x70 == 0
+                    i = 4 * w + byte
+                    run, j = 4 * half + i // 8, i % 8
+                    codes[r, run * 32 + q * 8 + j] = ((v >> 7) << 4) | (v & 0x0F)
     return codes
 
 
-@pytest.mark.parametrize("M,K", [(32, 1024), (32, 768)])
-def test_register_level_reconstruction(o5, M, K):
+def test_register_level_reconstruction(o5):
+    M, K = 32, 512
     codes = (workloads.make_codes(M, K, 9).numpy() & 31).astype(np.uint8)
     packed = o5.pack(codes)
-    KT2 = -(-K // 512)
-    tiles = packed.reshape(KT2, M // 16, 5120)
-    padded = np.zeros((M, KT2 * 512), dtype=np.uint8)
-    padded[:, :K] = codes                                   # padding columns read as code 0
+    tiles = packed.reshape(K // 256, M // 16, 2560)
     for rt in range(M // 16):
-        for kt in range(KT2):
+        for kt in range(K // 256):
             got = _swar_unpack_tile(tiles[kt, rt])
-            assert np.array_equal(got, padded[rt * 16:(rt + 1) * 16, kt * 512:(kt + 1) * 512])
+            assert np.array_equal(got, codes[rt * 16:(rt + 1) * 16, kt * 256:(kt + 1) * 256])
     assert np.array_equal(o5.unpack_codes(packed, M, K), codes)
 
 

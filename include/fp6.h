@@ -51,8 +51,9 @@ typedef enum {
 /* Human-readable name of a status code (static string). */
 const char *fp6_status_str(int status);
 
-/* Version of the packed weight layout written by fp6_quantize_pack and read by
- * fp6_unpack / fp6_linear.  Store it next to any packed buffer that is saved. */
+/* Version of the packed weight layouts written by the *_quantize_pack calls and read by the
+ * *_unpack / *_linear calls.  Store it next to any packed buffer that is saved.  (4: the
+ * 3-bit stream moved to tiles of 512 columns; the 6-, 5- and 4-bit streams are those of 3.) */
 int fp6_layout_version(void);
 
 /* Bytes of the packed code stream of an M x K matrix: 6 bits per weight, no
@@ -241,9 +242,13 @@ fp6_status fp4_linear(const void *packed, const void *scales_f16, const void *X_
  * the scheme covers): FP3 is read as e2m0, code = s e1 e0, Eq. 1 with bias 1 and no
  * mantissa bits, E = 0 holding only zero, no inf/NaN: magnitudes 0 1 2 4.  Quantizer:
  * scale[m] = fp16_rne(max_k |W[m][k]| / 4), nearest magnitude, ties to the even code,
- * saturating at 4.  fp3_packed_bytes(M, K) = 3*M*K/8 (tiles of 1536 bytes; the codes
- * are pre-arranged bit by bit so that the kernel rebuilds four 4-bit words from three
- * stored ones with a handful of AND/shift/OR).  Everything else as for the fp6_ calls.
+ * saturating at 4.  The stream is made of tiles of 16 rows x 512 columns, 3072 bytes each
+ * (three whole 128-bit pieces per lane; the codes are pre-arranged bit by bit so that the
+ * kernel rebuilds four 4-bit words from three stored ones with a handful of AND/shift/OR):
+ * fp3_packed_bytes(M, K) = ceil(K/512) * (M/16) * 3072, i.e. 3*M*K/8 when K is a multiple
+ * of 512 and half a tile of zero padding per row tile otherwise (written by
+ * fp3_quantize_pack).  This layout is the one of fp6_layout_version() >= 4.  Everything
+ * else as for the fp6_ calls.
  */
 size_t fp3_packed_bytes(int64_t M, int64_t K);
 size_t fp3_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);

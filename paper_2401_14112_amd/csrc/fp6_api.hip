@@ -14,7 +14,7 @@ namespace {
 
 using namespace fp6;
 
-constexpr int kLayoutVersion = 3;
+constexpr int kLayoutVersion = 4;  // 4: 3-bit tiles of 512 columns (6-, 5-, 4-bit streams as in 3)
 // Configurations of the streaming kernel: {token tiles per wave, waves per block, weight tiles in flight per
 // wave, k-tiles per activation stage, iterations over which the activation copies of a stage are spread,
 // k-tiles dealt round-robin to the split-K slices}.

@@ -2,10 +2,13 @@
 // layer is bound by reading the weights once from HBM (Section 3 and Section 7.1 of
 // the paper: linear layers at batch < 128 are limited by weight traffic).
 //
-// Work split: one wave owns one 16-row tile and one split-K slice of its 256-column
-// k-tiles; weights go HBM -> VGPR with three (packed) 128-bit loads per lane per tile,
-// prefetched DEPTH tiles ahead, and are used by exactly one wave, so they never touch
-// LDS.  The activations (16*NT tokens) are the only shared operand: the block copies
+// Work split: one wave owns one 16-row tile and one split-K slice of its k-tiles (the
+// weight source says how wide a tile is: 256 columns, 512 for the sources whose lane
+// loads only come out as whole 128-bit pieces that way); weights go HBM -> VGPR with a
+// few 128-bit loads per lane per tile (three for 6 bits), prefetched DEPTH tiles ahead,
+// and are used by exactly one wave, so they never touch LDS (one source, row-major fp16
+// weights, stages its tiles in a region of LDS private to the wave instead).  The
+// activations (16*NT tokens) are the only shared operand: the block copies
 // them global -> LDS without passing through registers, already in MFMA B-fragment
 // order, a STAGE of G k-tiles at a time, double-buffered, with one barrier per stage.
 // fp32 accumulation in v_mfma_f32_16x16x32_f16; the row scale is applied once in the

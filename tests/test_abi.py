@@ -19,7 +19,10 @@ def lib():
 
 
 def _declared_functions():
-    text = "".join(open(f).read() for f in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
+    text = ""
+    for path in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        with open(path) as f:
+            text += f.read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b(fp6g?_\w+|fp5_\w+|fp4_\w+|fp3_\w+|fp16_\w+)\s*\(", text)
     return sorted(set(names))

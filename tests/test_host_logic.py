@@ -19,7 +19,8 @@ def _gpu_style_codes(w_bits: np.ndarray, s_bits: np.ndarray) -> np.ndarray:
     q = (a * inv).astype(np.float32)
     rem = (a.astype(np.float64) - q.astype(np.float64) * s.astype(np.float64)).astype(np.float32)   # fma(-q, s, a)
     ratio = (rem.astype(np.float64) * inv.astype(np.float64) + q.astype(np.float64)).astype(np.float32)  # fma(rem, inv, q)
-    sub = np.rint(ratio * np.float32(16)).astype(np.uint32)                 # ratio < 0.25: multiples of 1/16
+    small = np.where(ratio < np.float32(0.25), ratio, np.float32(0))        # the other lanes take the normal route
+    sub = np.rint(small * np.float32(16)).astype(np.uint32)                 # ratio < 0.25: multiples of 1/16
     u = ratio.view(np.uint32).astype(np.uint64)
     u = u + 0x000FFFFF + ((u >> 21) & 1)
     nor = ((u >> 21) - (124 << 2)).astype(np.int64)

@@ -10,6 +10,9 @@ Every token count runs a different kernel instantiation (16-, 32-, 64-token stre
 kernel's block shapes), so the dispatches of one run are told apart by kernel name.  Weights are synthetic
 (N(0, 0.02) rounded to fp16, quantized by fp6_quantize_pack); every launch reads another of `--buffers`
 packed copies so that the weights come from HBM, not from the last-level cache.
+
+    python3 bench_case.py --chain80      # the 80-GEMM decoder chain of bench.py alone (one graph; with and without
+                                         # a branch that reads ahead in the next layer's weights)
 """
 from __future__ import annotations
 
@@ -28,6 +31,9 @@ def main():
     ap.add_argument("--reps", type=int, default=16)
     ap.add_argument("--buffers", type=int, default=8)
     ap.add_argument("--which", choices=("fp6", "fp6g", "fp5", "fp4", "fp3", "fp16"), default="fp6")
+    ap.add_argument("--chain80", action="store_true",
+                    help="instead: the 80 GEMMs of 20 decoder blocks of a 70B-class model from one HIP graph, plain and "
+                         "with a second graph branch that reads half of the next layer's weights (bench.py's measurement)")
     args = ap.parse_args()
 
     import torch
@@ -37,12 +43,22 @@ def main():
 
     pkg.load_library()
     dev = "cuda:0"
+    if args.chain80:
+        import json
+
+        import numpy as np
+
+        import bench
+
+        out = bench.decoder_set_measurements(pkg, torch, np, workloads, dev)
+        print(json.dumps(out["weight_stream_80_gemms_one_graph"]), flush=True)
+        return
     M, K = args.M, args.K
     weights = []
     for b in range(args.buffers):
         W = workloads.make_weights(M, K, seed=b, device=dev)
         weights.append((W,) if args.which == "fp16" else getattr(pkg, args.which + "_quantize_pack")(W))
-    query = pkg.fp16_linear_workspace_bytes if args.which == "fp16" else pkg.fp6_linear_workspace_bytes
+    query = getattr(pkg, ("fp6" if args.which == "fp6g" else args.which) + "_linear_workspace_bytes")
     for N in [int(v) for v in args.N.split(",")]:
         X = workloads.make_activations(N, K, seed=N, device=dev)
         Y = torch.empty((N, M), dtype=torch.float16, device=dev)

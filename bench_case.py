@@ -11,6 +11,8 @@ kernel's block shapes), so the dispatches of one run are told apart by kernel na
 (N(0, 0.02) rounded to fp16, quantized by fp6_quantize_pack); every launch reads another of `--buffers`
 packed copies so that the weights come from HBM, not from the last-level cache.
 
+    python3 bench_case.py --M 512 --N 512 --tile 256x128 --split 1   # a pinned block shape and split-K factor: with
+                                         # S = 1 every block does all K/256 k-tiles, so M sets how many CUs are busy
     python3 bench_case.py --chain80      # the 80-GEMM decoder chain of bench.py alone (one graph; with and without
                                          # a branch that reads ahead in the next layer's weights)
 """
@@ -31,6 +33,8 @@ def main():
     ap.add_argument("--reps", type=int, default=16)
     ap.add_argument("--buffers", type=int, default=8)
     ap.add_argument("--which", choices=("fp6", "fp6g", "fp5", "fp4", "fp3", "fp16"), default="fp6")
+    ap.add_argument("--tile", type=str, default="", help="force the block of the tiled kernel, e.g. 256x128 (rows x tokens)")
+    ap.add_argument("--split", type=int, default=0, help="force the split-K factor (0 = automatic)")
     ap.add_argument("--chain80", action="store_true",
                     help="instead: the 80 GEMMs of 20 decoder blocks of a 70B-class model from one HIP graph, plain and "
                          "with a second graph branch that reads half of the next layer's weights (bench.py's measurement)")
@@ -54,6 +58,10 @@ def main():
         print(json.dumps(out["weight_stream_80_gemms_one_graph"]), flush=True)
         return
     M, K = args.M, args.K
+    if args.tile:
+        rows, tokens = (int(v) for v in args.tile.split("x"))
+        pkg.fp6_tuning_set_tile(rows, tokens)
+    pkg.fp6_tuning_set_split_k(args.split)
     weights = []
     for b in range(args.buffers):
         W = workloads.make_weights(M, K, seed=b, device=dev)
